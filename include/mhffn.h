@@ -1,0 +1,151 @@
+/*
+ * mhffn.h -- C ABI of the MI355X (gfx950) fused Multi-Head FFN library.
+ *
+ * The operation is the gated Multi-Head FFN of FlashMHF: tokens are split into
+ * H heads of width d_h (paper, Preliminary, "Headwise Operation Functions");
+ * every head owns E SwiGLU sub-networks of width d_e (Methodology, "Parallel
+ * FFN Sub-Networks"); their outputs are mixed with per-token weights
+ * R = sigmoid(P) / (sum_e sigmoid(P) + eps), P = q W^h (eq:routing) and the
+ * heads are concatenated again:
+ *
+ *   Y[l, h*d_h + j] = sum_e R[l,h,e] * sum_c SiLU(q.K[h,e,c,:]) * (q.U[h,e,c,:]) * V[h,e,c,j]
+ *   with q = X[l, h*d_h : (h+1)*d_h]               (eq:intuitive-ffn, aggregation eq.)
+ *
+ * The fused entry points evaluate the sum over the intermediate index (e,c)
+ * block by block on chip (eq:flash-ffn-loop), so the [N, H, E*d_e] activation
+ * never reaches device memory; the backward recomputes it (appendix algorithms
+ * "Backward (dQ,dR)" and "Backward (dK,dU,dV)").
+ *
+ * Conventions for every entry point
+ *  - All tensor pointers are DEVICE pointers, 16-byte aligned, owned by the
+ *    caller.  `desc` is a HOST pointer.  `hip_stream` is a hipStream_t passed
+ *    as void* (NULL = the default stream).
+ *  - The library never allocates or frees device memory, never synchronises
+ *    and keeps no state between calls: all work is enqueued on `hip_stream`
+ *    and the call returns immediately.  Scratch comes from the caller through
+ *    `workspace` (at least mhffn_workspace_bytes() bytes, 256-byte aligned;
+ *    may be NULL when that size is 0).
+ *  - Outputs are overwritten, never accumulated into.
+ *  - Errors are reported by return code only; every argument is validated on
+ *    the host before anything is launched, so a non-zero return means nothing
+ *    was enqueued (except MHFFN_ERR_LAUNCH, which reports a HIP launch error).
+ *
+ * Layouts (row-major, innermost index last)
+ *   X, Y, dX, dY : [n_tokens][ld]            head h = columns h*d_h .. (h+1)*d_h-1
+ *   W_gate (paper K), W_up (U), W_down (V) and their gradients:
+ *                  [n_heads][n_sub][d_sub][d_head]   (one row per intermediate neuron)
+ *   route, MHFFN_ROUTE_PARAMS : W_r [n_heads][d_head][n_sub], dtype = desc.dtype
+ *   route, MHFFN_ROUTE_WEIGHTS: R   [n_tokens][n_heads][n_sub], always fp32
+ *   d_route has the shape and dtype of `route` for the mode in use.
+ */
+#ifndef MHFFN_H
+#define MHFFN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  MHFFN_OK = 0,
+  MHFFN_ERR_NULL = 1,        /* a required pointer is NULL                       */
+  MHFFN_ERR_SHAPE = 2,       /* a size is non-positive or a stride is too small  */
+  MHFFN_ERR_UNSUPPORTED = 3, /* valid problem, but no kernel for it (see below)  */
+  MHFFN_ERR_ALIGN = 4,       /* a pointer or stride breaks the alignment rule    */
+  MHFFN_ERR_WORKSPACE = 5,   /* workspace NULL or smaller than required          */
+  MHFFN_ERR_LAUNCH = 6       /* HIP reported an error when launching             */
+} mhffn_status;
+
+typedef enum {
+  MHFFN_F32 = 0, /* fp32 storage, fp32 arithmetic                         */
+  MHFFN_BF16 = 1 /* bf16 storage, bf16 MFMA with fp32 accumulation        */
+} mhffn_dtype;
+
+typedef enum {
+  MHFFN_ROUTE_PARAMS = 0, /* route = W_r; R is computed in-kernel (eq:routing)          */
+  MHFFN_ROUTE_WEIGHTS = 1 /* route = R, used as given (the paper's kernel-level input)  */
+} mhffn_route_mode;
+
+typedef enum {
+  MHFFN_OP_FORWARD = 0,
+  MHFFN_OP_BACKWARD = 1,
+  MHFFN_OP_UNFUSED_FORWARD = 2,
+  MHFFN_OP_UNFUSED_BACKWARD = 3 /* mhffn_reference_unfused with dY != NULL */
+} mhffn_op;
+
+typedef struct {
+  int64_t n_tokens;  /* N = batch * sequence; any N >= 1, ragged tails are masked    */
+  int32_t n_heads;   /* H                                                            */
+  int32_t d_head;    /* d_h; d_model = H*d_h                                         */
+  int32_t n_sub;     /* E, sub-networks per head                                     */
+  int32_t d_sub;     /* d_e, width of one sub-network; d_ff = E*d_e                  */
+  int64_t ld_x;      /* row stride of X and dX in elements (>= H*d_h); 0 => H*d_h    */
+  int64_t ld_y;      /* row stride of Y and dY in elements (>= H*d_h); 0 => H*d_h    */
+  int32_t dtype;     /* mhffn_dtype of X, Y, weights, W_r and all their gradients    */
+  int32_t route_mode;/* mhffn_route_mode                                             */
+  float eps;         /* epsilon of eq:routing (the paper gives no value)             */
+} mhffn_desc;
+
+/*
+ * Shape support.
+ *   bf16: the fused kernels need d_head == 128, d_sub % 32 == 0 and
+ *         n_sub <= 64; other shapes return MHFFN_ERR_UNSUPPORTED.
+ *   fp32: the fused kernels take d_head % 4 == 0, d_head <= 256, any n_sub, d_sub.
+ *   mhffn_reference_unfused takes any shape with d_head % 8 == 0.
+ *   Row strides must keep every row 16-byte aligned.
+ */
+
+/* Bytes of caller-provided scratch needed by `op` (an mhffn_op) for `desc`.
+ * Returns 0 for an invalid descriptor as well; validate with the entry point.
+ * For MHFFN_OP_FORWARD this is 0: the fused forward touches nothing but its
+ * inputs and Y, which is the "intermediate never reaches HBM" property of
+ * eq:flash-ffn-loop stated as a number.  For the unfused ops it is the three
+ * materialised [N][H][d_ff] activations plus the [N][H][E] weights, i.e. the
+ * O((L*H + d_model)*d_ff) footprint of the naive multi-head FFN. */
+size_t mhffn_workspace_bytes(const mhffn_desc* desc, int op);
+
+/* Fused forward (appendix algorithm "SRAMFFN-Forward"; gating of eq:routing is
+ * evaluated in the same kernel in MHFFN_ROUTE_PARAMS mode).  Writes Y. */
+int mhffn_forward(const mhffn_desc* desc, const void* X, const void* W_gate,
+                  const void* W_up, const void* W_down, const void* route,
+                  void* Y, void* workspace, size_t workspace_bytes,
+                  void* hip_stream);
+
+/* Fused, recompute-based backward (appendix algorithms "Backward (dQ,dR)" and
+ * "Backward (dK,dU,dV)"; the derivative through eq:routing is taken here too).
+ * Needs only X, the weights and dY: nothing is saved by the forward.
+ * Any of dX, dW_gate, dW_up, dW_down, d_route may be NULL => not computed.
+ * d_route is dW_r (PARAMS mode) or dR (WEIGHTS mode). */
+int mhffn_backward(const mhffn_desc* desc, const void* X, const void* W_gate,
+                   const void* W_up, const void* W_down, const void* route,
+                   const void* dY, void* dX, void* dW_gate, void* dW_up,
+                   void* dW_down, void* d_route, void* workspace,
+                   size_t workspace_bytes, void* hip_stream);
+
+/* Unfused GPU baseline: the naive execution of the same layer (Methodology,
+ * "Naive Multi-Head FFN", Limitations: memory pressure).  Separate kernels with
+ * a device-memory round trip between them: (i) R, (ii) per-head products
+ * G = X_h K^T and U' = X_h U^T, (iii) A = SiLU(G)*U'*R, (iv) Y_h = A_h V;
+ * G, U' and A are materialised in `workspace`.  With dY != NULL it also runs
+ * the backward from those saved activations and writes the non-NULL
+ * gradients.  With dY == NULL the gradient pointers are ignored. */
+int mhffn_reference_unfused(const mhffn_desc* desc, const void* X,
+                            const void* W_gate, const void* W_up,
+                            const void* W_down, const void* route, void* Y,
+                            const void* dY, void* dX, void* dW_gate,
+                            void* dW_up, void* dW_down, void* d_route,
+                            void* workspace, size_t workspace_bytes,
+                            void* hip_stream);
+
+/* Static, human-readable name of a status code. */
+const char* mhffn_status_string(int status);
+
+/* Library version string (static storage). */
+const char* mhffn_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MHFFN_H */

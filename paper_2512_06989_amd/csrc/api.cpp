@@ -1,0 +1,155 @@
+// C ABI of the fused Multi-Head FFN library: argument validation on the host,
+// then dispatch to the gfx950 kernels.  Nothing here allocates, synchronises or
+// keeps state; see include/mhffn.h for the contract.
+#include "../../include/mhffn.h"
+
+#include "mhffn_internal.h"
+
+namespace {
+
+using mhffn::Problem;
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline size_t elt_size(int dtype) { return dtype == MHFFN_BF16 ? 2 : 4; }
+
+// Descriptor checks common to all entry points.
+int check_desc(const mhffn_desc* d, Problem* p) {
+  if (!d) return MHFFN_ERR_NULL;
+  if (d->n_tokens < 0 || d->n_heads < 1 || d->d_head < 1 || d->n_sub < 1 || d->d_sub < 1)
+    return MHFFN_ERR_SHAPE;
+  if (d->dtype != MHFFN_F32 && d->dtype != MHFFN_BF16) return MHFFN_ERR_UNSUPPORTED;
+  if (d->route_mode != MHFFN_ROUTE_PARAMS && d->route_mode != MHFFN_ROUTE_WEIGHTS)
+    return MHFFN_ERR_UNSUPPORTED;
+  if (!(d->eps >= 0.0f)) return MHFFN_ERR_SHAPE;  // also rejects NaN
+  const int64_t dm = (int64_t)d->n_heads * d->d_head;
+  if ((d->ld_x != 0 && d->ld_x < dm) || (d->ld_y != 0 && d->ld_y < dm)) return MHFFN_ERR_SHAPE;
+  // sizes whose products would not fit the index arithmetic of the kernels
+  if (d->n_tokens > ((int64_t)1 << 40) || dm > (1 << 24) ||
+      (int64_t)d->n_sub * d->d_sub > (1 << 24))
+    return MHFFN_ERR_SHAPE;
+  p->N = d->n_tokens;
+  p->H = d->n_heads; p->dh = d->d_head; p->E = d->n_sub; p->de = d->d_sub;
+  p->ldx = d->ld_x ? d->ld_x : dm;
+  p->ldy = d->ld_y ? d->ld_y : dm;
+  p->route_mode = d->route_mode;
+  p->eps = d->eps;
+  const size_t es = elt_size(d->dtype);
+  if ((p->ldx * es) % 16 != 0 || (p->ldy * es) % 16 != 0) return MHFFN_ERR_ALIGN;
+  return MHFFN_OK;
+}
+
+// Can the fused kernels run this shape?
+int check_fused_shape(const mhffn_desc* d, const Problem& p) {
+  if (d->dtype == MHFFN_BF16) {
+    if (p.dh != 128 || p.de % 32 != 0 || p.E > mhffn::kFwdBf16MaxSub) return MHFFN_ERR_UNSUPPORTED;
+  } else {
+    if (p.dh % 4 != 0 || p.dh > 256) return MHFFN_ERR_UNSUPPORTED;
+    if (mhffn::fwd_f32_lds_bytes(p) > mhffn::kLdsBytesPerWorkgroup) return MHFFN_ERR_UNSUPPORTED;
+  }
+  return MHFFN_OK;
+}
+
+int check_workspace(size_t need, const void* ws, size_t have) {
+  if (need == 0) return MHFFN_OK;
+  if (!ws || have < need) return MHFFN_ERR_WORKSPACE;
+  if ((reinterpret_cast<uintptr_t>(ws) & 255u) != 0) return MHFFN_ERR_ALIGN;
+  return MHFFN_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* mhffn_status_string(int status) {
+  switch (status) {
+    case MHFFN_OK: return "ok";
+    case MHFFN_ERR_NULL: return "a required pointer is NULL";
+    case MHFFN_ERR_SHAPE: return "invalid size or stride";
+    case MHFFN_ERR_UNSUPPORTED: return "shape, dtype or mode not supported by this kernel set";
+    case MHFFN_ERR_ALIGN: return "pointer or stride not 16-byte aligned (workspace: 256)";
+    case MHFFN_ERR_WORKSPACE: return "workspace missing or too small";
+    case MHFFN_ERR_LAUNCH: return "HIP kernel launch failed";
+    default: return "unknown status";
+  }
+}
+
+const char* mhffn_version(void) { return "mhffn-gfx950 0.1"; }
+
+size_t mhffn_workspace_bytes(const mhffn_desc* desc, int op) {
+  Problem p;
+  if (check_desc(desc, &p) != MHFFN_OK) return 0;
+  switch (op) {
+    case MHFFN_OP_FORWARD: return 0;
+    case MHFFN_OP_BACKWARD:
+      if (check_fused_shape(desc, p) != MHFFN_OK) return 0;
+      return mhffn::bwd_workspace_bytes(p, desc->dtype);
+    case MHFFN_OP_UNFUSED_FORWARD: return mhffn::unfused_workspace_bytes(p, desc->dtype, false);
+    case MHFFN_OP_UNFUSED_BACKWARD: return mhffn::unfused_workspace_bytes(p, desc->dtype, true);
+    default: return 0;
+  }
+}
+
+int mhffn_forward(const mhffn_desc* desc, const void* X, const void* W_gate, const void* W_up,
+                  const void* W_down, const void* route, void* Y, void* workspace,
+                  size_t workspace_bytes, void* hip_stream) {
+  (void)workspace; (void)workspace_bytes;  // the fused forward needs no scratch
+  Problem p;
+  int rc = check_desc(desc, &p);
+  if (rc) return rc;
+  if (!X || !W_gate || !W_up || !W_down || !route || !Y) return MHFFN_ERR_NULL;
+  if (!aligned16(X) || !aligned16(W_gate) || !aligned16(W_up) || !aligned16(W_down) ||
+      !aligned16(route) || !aligned16(Y))
+    return MHFFN_ERR_ALIGN;
+  rc = check_fused_shape(desc, p);
+  if (rc) return rc;
+  if (p.N == 0) return MHFFN_OK;
+  const int e = (desc->dtype == MHFFN_BF16)
+                    ? mhffn::launch_fwd_bf16(p, X, W_gate, W_up, W_down, route, Y, hip_stream)
+                    : mhffn::launch_fwd_f32(p, X, W_gate, W_up, W_down, route, Y, hip_stream);
+  return e == 0 ? MHFFN_OK : MHFFN_ERR_LAUNCH;
+}
+
+int mhffn_backward(const mhffn_desc* desc, const void* X, const void* W_gate, const void* W_up,
+                   const void* W_down, const void* route, const void* dY, void* dX,
+                   void* dW_gate, void* dW_up, void* dW_down, void* d_route, void* workspace,
+                   size_t workspace_bytes, void* hip_stream) {
+  Problem p;
+  int rc = check_desc(desc, &p);
+  if (rc) return rc;
+  if (!X || !W_gate || !W_up || !W_down || !route || !dY) return MHFFN_ERR_NULL;
+  const void* ptrs[] = {X, W_gate, W_up, W_down, route, dY, dX, dW_gate, dW_up, dW_down, d_route};
+  for (const void* q : ptrs)
+    if (!aligned16(q)) return MHFFN_ERR_ALIGN;
+  rc = check_fused_shape(desc, p);
+  if (rc) return rc;
+  rc = check_workspace(mhffn::bwd_workspace_bytes(p, desc->dtype), workspace, workspace_bytes);
+  if (rc) return rc;
+  const int e = mhffn::launch_bwd(p, desc->dtype, X, W_gate, W_up, W_down, route, dY, dX, dW_gate,
+                                  dW_up, dW_down, d_route, workspace, hip_stream);
+  if (e == -1) return MHFFN_ERR_UNSUPPORTED;
+  return e == 0 ? MHFFN_OK : MHFFN_ERR_LAUNCH;
+}
+
+int mhffn_reference_unfused(const mhffn_desc* desc, const void* X, const void* W_gate,
+                            const void* W_up, const void* W_down, const void* route, void* Y,
+                            const void* dY, void* dX, void* dW_gate, void* dW_up, void* dW_down,
+                            void* d_route, void* workspace, size_t workspace_bytes,
+                            void* hip_stream) {
+  Problem p;
+  int rc = check_desc(desc, &p);
+  if (rc) return rc;
+  if (!X || !W_gate || !W_up || !W_down || !route || !Y) return MHFFN_ERR_NULL;
+  const void* ptrs[] = {X, W_gate, W_up, W_down, route, Y, dY, dX, dW_gate, dW_up, dW_down, d_route};
+  for (const void* q : ptrs)
+    if (!aligned16(q)) return MHFFN_ERR_ALIGN;
+  if (p.dh % 8 != 0) return MHFFN_ERR_UNSUPPORTED;
+  rc = check_workspace(mhffn::unfused_workspace_bytes(p, desc->dtype, dY != nullptr), workspace,
+                       workspace_bytes);
+  if (rc) return rc;
+  const int e = mhffn::launch_unfused(p, desc->dtype, X, W_gate, W_up, W_down, route, Y, dY, dX,
+                                      dW_gate, dW_up, dW_down, d_route, workspace, hip_stream);
+  if (e == -1) return MHFFN_ERR_UNSUPPORTED;
+  return e == 0 ? MHFFN_OK : MHFFN_ERR_LAUNCH;
+}
+
+}  // extern "C"

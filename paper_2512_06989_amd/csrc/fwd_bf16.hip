@@ -1,0 +1,309 @@
+// Fused Multi-Head FFN forward, bf16 storage / fp32 accumulation, gfx950.
+//
+// One workgroup owns BM tokens of one head and walks the head's whole
+// intermediate dimension in tiles of 32 neurons (the block loop of
+// eq:flash-ffn-loop; appendix algorithm "SRAMFFN-Forward"):
+//
+//   per tile:  M^T = K_tile q^T,  N^T = U_tile q^T          (bf16 MFMA, fp32 acc)
+//              A^T = SiLU(M^T) .* N^T .* r_e                 (fp32 VALU, one bf16 rounding)
+//              O^T += V_tile^T A^T                           (bf16 MFMA, fp32 acc)
+//
+// Products are kept transposed (neurons on the MFMA row axis, tokens on the
+// column axis): the fp32 accumulator of M^T/N^T then has exactly the lane
+// layout of a B operand of the third product, so A never leaves registers.
+// V is read from LDS with the transposing LDS load, so all three weight tiles
+// are staged in their natural [neuron][d_h] layout.
+//
+// The gating weights of eq:routing are computed in the same kernel (P^T = W_r^T
+// q^T on the MFMA, sigmoid and the sum over sub-networks in fp32, the two
+// half-waves of a token combined with one cross-lane exchange) and parked in
+// LDS as R[e][token]; nothing but X, the weights and Y touches device memory.
+#include "mhffn_device.h"
+#include "mhffn_internal.h"
+
+namespace mhffn {
+namespace {
+
+constexpr int kDh = 128;            // head width this kernel is built for
+constexpr int kBI = 32;             // neurons per tile
+constexpr int kKUStride = 272;      // bytes per LDS row of a K/U tile (256 + 16 pad)
+constexpr int kVStride = 320;       // bytes per LDS row of a V tile   (256 + 64 pad)
+constexpr int kKBytes = kBI * kKUStride;
+constexpr int kVBytes = kBI * kVStride;
+constexpr int kStageBytes = 2 * kKBytes + kVBytes;  // 27648
+constexpr int kStages = 2;
+
+struct FwdArgs {
+  const uint16_t* X;
+  const uint16_t* Wg;
+  const uint16_t* Wu;
+  const uint16_t* Wd;
+  const void* route;
+  uint16_t* Y;
+  int64_t N, ldx, ldy, n_tiles, n_items;
+  int H, E, de, route_mode;
+  float eps;
+};
+
+template <int TB, int NW>
+__global__ __launch_bounds__(64 * NW) void fwd_bf16_kernel(FwdArgs a) {
+  constexpr int BM = 32 * TB * NW;
+  constexpr int THREADS = 64 * NW;
+  constexpr int CH = (kBI * kDh * 2 / 16) / THREADS;  // 16-byte chunks per thread per tile
+  static_assert(CH >= 1, "tile smaller than the workgroup");
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  unsigned char* stage_base = smem;
+  float* Rs = reinterpret_cast<float*>(smem + kStages * kStageBytes);  // [E][BM]
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int r = lane & 31, g = lane >> 5;
+  const int64_t item = xcd_work_item(blockIdx.x, a.n_items);
+  if (item >= a.n_items) return;  // whole workgroup leaves together
+  const int h = (int)(item / a.n_tiles);
+  const int64_t tile_tok0 = (item % a.n_tiles) * BM;
+  const int wtok = wave * 32 * TB;  // first token of this wave inside the tile
+  const int E = a.E;
+
+  // ---- q fragments (B operands), resident for the whole kernel -------------
+  bf16x8 q[TB][8];
+#pragma unroll
+  for (int tb = 0; tb < TB; ++tb) {
+    const int64_t tok = tile_tok0 + wtok + 32 * tb + r;
+    const bool valid = tok < a.N;
+    const uint16_t* src = a.X + (valid ? tok : 0) * a.ldx + h * kDh + 8 * g;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+      bf16x8 v = *reinterpret_cast<const bf16x8*>(src + 16 * ks);
+      if (!valid) v = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+      q[tb][ks] = v;
+    }
+  }
+
+  // ---- gating weights R[e][token] into LDS ---------------------------------
+  if (a.route_mode == 0) {
+    const int EB = (E + 31) >> 5;
+    uint16_t* WrT = reinterpret_cast<uint16_t*>(stage_base);  // [32*EB][136] bf16
+    const uint16_t* Wr = reinterpret_cast<const uint16_t*>(a.route) + (size_t)h * kDh * E;
+    for (int idx = tid; idx < kDh * E; idx += THREADS) {
+      const int j = idx / E, e = idx - j * E;
+      WrT[e * (kKUStride / 2) + j] = Wr[idx];
+    }
+    for (int idx = tid; idx < (32 * EB - E) * kDh; idx += THREADS) {
+      const int e = E + idx / kDh, j = idx % kDh;
+      WrT[e * (kKUStride / 2) + j] = 0;
+    }
+    __syncthreads();
+    float zsum[TB];
+#pragma unroll
+    for (int tb = 0; tb < TB; ++tb) zsum[tb] = 0.f;
+    // pass 0 accumulates Z = sum_e sigmoid(p_e); pass 1 recomputes and writes r_e.
+    float inv[TB];
+    for (int pass = 0; pass < 2; ++pass) {
+      for (int eb = 0; eb < EB; ++eb) {
+        const unsigned char* arow =
+            reinterpret_cast<const unsigned char*>(WrT) + (32 * eb + r) * kKUStride + 16 * g;
+#pragma unroll
+        for (int tb = 0; tb < TB; ++tb) {
+          f32x16 acc = {0};
+#pragma unroll
+          for (int ks = 0; ks < 8; ++ks) {
+            bf16x8 af = *reinterpret_cast<const bf16x8*>(arow + 32 * ks);
+            acc = mfma32(af, q[tb][ks], acc);
+          }
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            const int e = 32 * eb + 8 * (v / 4) + 4 * g + (v % 4);
+            const float s = (e < E) ? sigmoid_fast(acc[v]) : 0.f;
+            if (pass == 0) {
+              zsum[tb] += s;
+            } else if (e < E) {
+              Rs[e * BM + wtok + 32 * tb + r] = s * inv[tb];
+            }
+          }
+        }
+      }
+      if (pass == 0) {
+#pragma unroll
+        for (int tb = 0; tb < TB; ++tb) {
+          const float z = zsum[tb] + __shfl_xor(zsum[tb], 32);
+          inv[tb] = 1.0f / (z + a.eps);
+        }
+      }
+    }
+  } else {
+    const float* R = reinterpret_cast<const float*>(a.route);
+    for (int idx = tid; idx < BM * E; idx += THREADS) {
+      const int tl = idx / E, e = idx - tl * E;
+      const int64_t tok = tile_tok0 + tl;
+      Rs[e * BM + tl] = (tok < a.N) ? R[((size_t)tok * a.H + h) * E + e] : 0.f;
+    }
+  }
+  __syncthreads();  // R complete; the staging area is free again
+
+  // ---- main loop over tiles of 32 neurons ----------------------------------
+  const int tiles_per_sub = a.de / kBI;
+  const int T = E * tiles_per_sub;
+  const size_t head_off = (size_t)h * E * a.de * kDh;
+  const uint16_t* Kh = a.Wg + head_off;
+  const uint16_t* Uh = a.Wu + head_off;
+  const uint16_t* Vh = a.Wd + head_off;
+
+  u32x4 kreg[CH], ureg[CH], vreg[CH];
+  auto gload = [&](int t) {
+#pragma unroll
+    for (int i = 0; i < CH; ++i) {
+      const int chunk = tid + THREADS * i;
+      const size_t off = ((size_t)t * kBI + (chunk >> 4)) * kDh + (chunk & 15) * 8;
+      kreg[i] = *reinterpret_cast<const u32x4*>(Kh + off);
+      ureg[i] = *reinterpret_cast<const u32x4*>(Uh + off);
+      vreg[i] = *reinterpret_cast<const u32x4*>(Vh + off);
+    }
+  };
+  auto lstore = [&](int s) {
+    unsigned char* st = stage_base + s * kStageBytes;
+#pragma unroll
+    for (int i = 0; i < CH; ++i) {
+      const int chunk = tid + THREADS * i;
+      const int row = chunk >> 4, c16 = chunk & 15;
+      *reinterpret_cast<u32x4*>(st + row * kKUStride + c16 * 16) = kreg[i];
+      *reinterpret_cast<u32x4*>(st + kKBytes + row * kKUStride + c16 * 16) = ureg[i];
+      *reinterpret_cast<u32x4*>(st + 2 * kKBytes + row * kVStride + c16 * 16) = vreg[i];
+    }
+  };
+
+  f32x16 O[TB][4];
+#pragma unroll
+  for (int tb = 0; tb < TB; ++tb)
+#pragma unroll
+    for (int jb = 0; jb < 4; ++jb) O[tb][jb] = f32x16{0};
+
+  // per-lane byte offsets of the operand reads inside a stage
+  const int ku_off = r * kKUStride + 16 * g;
+  // transposing V read: 16-lane block b = lane/16 serves rows 4*(b/2).. and columns 16*(b%2)..
+  const int li = lane & 15;
+  const int v_off = 2 * kKBytes + (4 * g + (li >> 2)) * kVStride + (16 * ((lane >> 4) & 1) + 4 * (li & 3)) * 2;
+
+  gload(0);
+  lstore(0);
+  __syncthreads();
+  float rw[TB];
+  for (int t = 0; t < T; ++t) {
+    const bool more = (t + 1 < T);
+    if (more) gload(t + 1);
+    if (t % tiles_per_sub == 0) {
+      const int e = t / tiles_per_sub;
+#pragma unroll
+      for (int tb = 0; tb < TB; ++tb) rw[tb] = Rs[e * BM + wtok + 32 * tb + r];
+    }
+    const unsigned char* st = stage_base + (t & 1) * kStageBytes;
+
+    // gate and up products
+    f32x16 accM[TB], accN[TB];
+#pragma unroll
+    for (int tb = 0; tb < TB; ++tb) { accM[tb] = f32x16{0}; accN[tb] = f32x16{0}; }
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+      const bf16x8 ak = *reinterpret_cast<const bf16x8*>(st + ku_off + 32 * ks);
+      const bf16x8 au = *reinterpret_cast<const bf16x8*>(st + kKBytes + ku_off + 32 * ks);
+#pragma unroll
+      for (int tb = 0; tb < TB; ++tb) {
+        accM[tb] = mfma32(ak, q[tb][ks], accM[tb]);
+        accN[tb] = mfma32(au, q[tb][ks], accN[tb]);
+      }
+    }
+    // activation, weighting, one rounding to bf16; registers 8*t2 .. 8*t2+7 of
+    // the accumulator are the 8 contraction slots of down-projection step t2.
+    bf16x8 bfrag[TB][2];
+#pragma unroll
+    for (int tb = 0; tb < TB; ++tb) {
+#pragma unroll
+      for (int t2 = 0; t2 < 2; ++t2) {
+        u32x4 pk;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const float m0 = accM[tb][8 * t2 + 2 * i], m1 = accM[tb][8 * t2 + 2 * i + 1];
+          const float a0 = m0 * accN[tb][8 * t2 + 2 * i] * rw[tb] * sigmoid_fast(m0);
+          const float a1 = m1 * accN[tb][8 * t2 + 2 * i + 1] * rw[tb] * sigmoid_fast(m1);
+          pk[i] = pack_bf16(a0, a1);
+        }
+        bfrag[tb][t2] = __builtin_bit_cast(bf16x8, pk);
+      }
+    }
+    // down projection: contraction slot s of step t2 is neuron
+    // 16*t2 + 8*(s/4) + 4g + s%4, so the V operand is two transposed reads of
+    // 4 consecutive tile rows each.
+#pragma unroll
+    for (int t2 = 0; t2 < 2; ++t2) {
+#pragma unroll
+      for (int jb = 0; jb < 4; ++jb) {
+        const unsigned char* vp = st + v_off + (16 * t2) * kVStride + 64 * jb;
+        const s16x4 lo = lds_read_tr16(vp);
+        const s16x4 hi = lds_read_tr16(vp + 8 * kVStride);
+        typedef short s16x8 __attribute__((ext_vector_type(8)));
+        const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        const bf16x8 av = __builtin_bit_cast(bf16x8, both);
+#pragma unroll
+        for (int tb = 0; tb < TB; ++tb) O[tb][jb] = mfma32(av, bfrag[tb][t2], O[tb][jb]);
+      }
+    }
+    if (more) lstore((t + 1) & 1);
+    __syncthreads();
+  }
+
+  // ---- store Y (concat_H: head h owns columns h*d_h ..) --------------------
+#pragma unroll
+  for (int tb = 0; tb < TB; ++tb) {
+    const int64_t tok = tile_tok0 + wtok + 32 * tb + r;
+    if (tok < a.N) {
+      uint16_t* dst = a.Y + tok * a.ldy + h * kDh + 4 * g;
+#pragma unroll
+      for (int jb = 0; jb < 4; ++jb) {
+#pragma unroll
+        for (int vq = 0; vq < 4; ++vq) {
+          u32x2 pk;
+          pk[0] = pack_bf16(O[tb][jb][4 * vq], O[tb][jb][4 * vq + 1]);
+          pk[1] = pack_bf16(O[tb][jb][4 * vq + 2], O[tb][jb][4 * vq + 3]);
+          *reinterpret_cast<u32x2*>(dst + 32 * jb + 8 * vq) = pk;
+        }
+      }
+    }
+  }
+}
+
+template <int TB, int NW>
+int launch_variant(const Problem& p, FwdArgs a, hipStream_t stream) {
+  constexpr int BM = 32 * TB * NW;
+  a.n_tiles = (p.N + BM - 1) / BM;
+  a.n_items = a.n_tiles * p.H;
+  const size_t lds = (size_t)kStages * kStageBytes + (size_t)p.E * BM * sizeof(float);
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&fwd_bf16_kernel<TB, NW>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)kLdsBytesPerWorkgroup);
+    if (e != hipSuccess) return (int)e;
+    attr_set = true;
+  }
+  const dim3 grid((unsigned)xcd_grid_size(a.n_items));
+  hipLaunchKernelGGL((fwd_bf16_kernel<TB, NW>), grid, dim3(64 * NW), lds, stream, a);
+  return (int)hipGetLastError();
+}
+
+}  // namespace
+
+int launch_fwd_bf16(const Problem& p, const void* X, const void* Wg, const void* Wu,
+                    const void* Wd, const void* route, void* Y, void* stream) {
+  FwdArgs a;
+  a.X = static_cast<const uint16_t*>(X);
+  a.Wg = static_cast<const uint16_t*>(Wg);
+  a.Wu = static_cast<const uint16_t*>(Wu);
+  a.Wd = static_cast<const uint16_t*>(Wd);
+  a.route = route;
+  a.Y = static_cast<uint16_t*>(Y);
+  a.N = p.N; a.ldx = p.ldx; a.ldy = p.ldy;
+  a.H = p.H; a.E = p.E; a.de = p.de; a.route_mode = p.route_mode; a.eps = p.eps;
+  a.n_tiles = 0; a.n_items = 0;
+  return launch_variant<2, 4>(p, a, static_cast<hipStream_t>(stream));
+}
+
+}  // namespace mhffn

@@ -1,0 +1,78 @@
+// Device-side helpers shared by the gfx950 kernels of the fused Multi-Head FFN.
+//
+// MFMA lane layouts used throughout (wave64, lane l, g = l / 32, r = l % 32):
+//   v_mfma_f32_32x32x16_bf16  D[32x32] += A[32x16] * B[16x32]
+//     A operand: lane holds row r,    k = 8g .. 8g+7   (8 bf16, k contiguous)
+//     B operand: lane holds column r, k = 8g .. 8g+7
+//     D / C    : lane holds column r, register v (0..15) is row 8*(v/4) + 4g + v%4
+// Every kernel computes the *transposed* products (intermediate neurons on the
+// MFMA row axis, tokens on the column axis), so that the accumulator of the
+// gate/up products is, register for register, a B operand of the following
+// down-projection: the chained contraction never leaves the register file.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace mhffn {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+#define MHFFN_LOG2E 1.4426950408889634f
+
+__device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+// 1 / (1 + 2^(-x*log2e)): one v_exp_f32 and one v_rcp_f32 (1 ulp each), safe
+// for either sign: exp2 overflows to +inf for very negative x and rcp(inf) = 0.
+__device__ __forceinline__ float sigmoid_fast(float x) {
+  float t = __builtin_amdgcn_exp2f(-MHFFN_LOG2E * x);
+  return __builtin_amdgcn_rcpf(1.0f + t);
+}
+
+// Two fp32 -> packed bf16 (round to nearest even), low half = a.
+__device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
+  bf16x2 p;
+  p[0] = (__bf16)a;
+  p[1] = (__bf16)b;
+  return __builtin_bit_cast(uint32_t, p);
+}
+
+__device__ __forceinline__ float bf16_bits_to_f32(uint16_t b) {
+  return __builtin_bit_cast(float, (uint32_t)b << 16);
+}
+
+// LDS transpose read (gfx950 ds_read_b64_tr_b16).  Within each block of 16
+// lanes, lane i supplies the address of 4 consecutive 16-bit elements and
+// receives element (i % 4) of the 4 lanes 4e + i/4, e = 0..3:
+//     out[i][e] = in[4e + i/4][i % 4].
+// Pointing lane i at row (i / 4), columns 4*(i % 4).. of a row-major [k][n]
+// tile therefore returns, to lane i, column i of rows 0..3: an MFMA operand
+// whose contraction index is the tile's slow dimension.
+__device__ __forceinline__ s16x4 lds_read_tr16(const void* lds_ptr) {
+  typedef __attribute__((address_space(3))) s16x4* lds_s16x4_ptr;
+  return __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)lds_ptr);
+}
+
+// XCD-aware work distribution.  Workgroups are handed to the 8 XCDs round
+// robin by blockIdx, and every XCD has a private L2.  The head-major work list
+// (item = head * n_tiles + tile) is cut into 8 contiguous chunks, one per XCD,
+// so the workgroups resident on an XCD stream the same head's weights at the
+// same time and all but the first reader of a weight tile hit that XCD's L2.
+__device__ __forceinline__ int64_t xcd_work_item(int64_t bid, int64_t n_items) {
+  const int64_t per_xcd = (n_items + 7) / 8;
+  return (bid % 8) * per_xcd + bid / 8;
+}
+__host__ __device__ __forceinline__ int64_t xcd_grid_size(int64_t n_items) {
+  return 8 * ((n_items + 7) / 8);
+}
+
+}  // namespace mhffn

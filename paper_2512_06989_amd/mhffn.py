@@ -1,0 +1,171 @@
+"""Thin binding over the C ABI in include/mhffn.h (libmhffn.so, built from csrc/).
+
+Argument marshalling only: every step of the operation runs in the HIP kernels
+of the library.  PyTorch is used for device memory and the current stream.
+There is no fallback: if the library is missing or a call fails, this raises."""
+import ctypes
+import os
+
+import torch
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libmhffn.so")
+
+OK = 0
+F32, BF16 = 0, 1
+ROUTE_PARAMS, ROUTE_WEIGHTS = 0, 1
+OP_FORWARD, OP_BACKWARD, OP_UNFUSED_FORWARD, OP_UNFUSED_BACKWARD = 0, 1, 2, 3
+EXPORTS = ("mhffn_workspace_bytes", "mhffn_forward", "mhffn_backward",
+           "mhffn_reference_unfused", "mhffn_status_string", "mhffn_version")
+
+
+class Desc(ctypes.Structure):
+    """Mirror of `mhffn_desc`."""
+    _fields_ = [("n_tokens", ctypes.c_int64), ("n_heads", ctypes.c_int32),
+                ("d_head", ctypes.c_int32), ("n_sub", ctypes.c_int32),
+                ("d_sub", ctypes.c_int32), ("ld_x", ctypes.c_int64),
+                ("ld_y", ctypes.c_int64), ("dtype", ctypes.c_int32),
+                ("route_mode", ctypes.c_int32), ("eps", ctypes.c_float)]
+
+
+class MhffnError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = int(status)
+        super().__init__("%s: status %d (%s)" % (where, status, status_string(status)))
+
+
+_lib = None
+
+
+def load():
+    """Load libmhffn.so (building it first only if it was never built)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        from . import build as _build
+        _build.build(force=True)
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, sz = ctypes.c_void_p, ctypes.c_size_t
+    dp = ctypes.POINTER(Desc)
+    lib.mhffn_workspace_bytes.argtypes = [dp, ctypes.c_int]
+    lib.mhffn_workspace_bytes.restype = sz
+    lib.mhffn_forward.argtypes = [dp] + [vp] * 6 + [vp, sz, vp]
+    lib.mhffn_forward.restype = ctypes.c_int
+    lib.mhffn_backward.argtypes = [dp] + [vp] * 11 + [vp, sz, vp]
+    lib.mhffn_backward.restype = ctypes.c_int
+    lib.mhffn_reference_unfused.argtypes = [dp] + [vp] * 12 + [vp, sz, vp]
+    lib.mhffn_reference_unfused.restype = ctypes.c_int
+    lib.mhffn_status_string.argtypes = [ctypes.c_int]
+    lib.mhffn_status_string.restype = ctypes.c_char_p
+    lib.mhffn_version.restype = ctypes.c_char_p
+    _lib = lib
+    return lib
+
+
+def status_string(status):
+    return load().mhffn_status_string(int(status)).decode()
+
+
+def version():
+    return load().mhffn_version().decode()
+
+
+def _dtype_code(t):
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    raise TypeError("unsupported dtype %s" % t.dtype)
+
+
+def make_desc(X, W_gate, route_mode, eps, Y=None):
+    H, E, d_e, d_h = W_gate.shape
+    if X.dim() != 2 or X.shape[1] != H * d_h:
+        raise ValueError("X must be [N, H*d_h] = [N, %d], got %s" % (H * d_h, tuple(X.shape)))
+    if X.stride(1) != 1:
+        raise ValueError("X rows must be contiguous")
+    ld_y = X.stride(0) if Y is None else Y.stride(0)
+    return Desc(X.shape[0], H, d_h, E, d_e, X.stride(0) if X.shape[0] > 1 else H * d_h,
+                ld_y if X.shape[0] > 1 else H * d_h, _dtype_code(X), int(route_mode), float(eps))
+
+
+def _p(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def workspace_bytes(desc, op):
+    return int(load().mhffn_workspace_bytes(ctypes.byref(desc), int(op)))
+
+
+def _workspace(desc, op, device, workspace):
+    need = workspace_bytes(desc, op)
+    if workspace is None and need:
+        workspace = torch.empty(need, dtype=torch.uint8, device=device)
+    have = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    return workspace, have
+
+
+def forward(X, W_gate, W_up, W_down, route, eps=1e-6, route_mode=ROUTE_PARAMS, out=None,
+            stream=None):
+    """Fused forward.  Returns Y [N, H*d_h] (dtype of X)."""
+    Y = torch.empty_like(X) if out is None else out
+    d = make_desc(X, W_gate, route_mode, eps, Y)
+    rc = load().mhffn_forward(ctypes.byref(d), _p(X), _p(W_gate), _p(W_up), _p(W_down),
+                              _p(route), _p(Y), None, 0, _stream(stream))
+    if rc != OK:
+        raise MhffnError(rc, "mhffn_forward")
+    return Y
+
+
+def backward(X, W_gate, W_up, W_down, route, dY, eps=1e-6, route_mode=ROUTE_PARAMS,
+             want=("dX", "dW_gate", "dW_up", "dW_down", "d_route"), workspace=None, out=None,
+             stream=None):
+    """Fused recompute-based backward.  Returns a dict of the requested gradients."""
+    d = make_desc(X, W_gate, route_mode, eps, dY)
+    out = dict(out or {})
+    like = {"dX": X, "dW_gate": W_gate, "dW_up": W_up, "dW_down": W_down, "d_route": route}
+    for k in want:
+        if k not in out:
+            out[k] = torch.empty_like(like[k])
+    workspace, have = _workspace(d, OP_BACKWARD, X.device, workspace)
+    rc = load().mhffn_backward(ctypes.byref(d), _p(X), _p(W_gate), _p(W_up), _p(W_down),
+                               _p(route), _p(dY), _p(out.get("dX")), _p(out.get("dW_gate")),
+                               _p(out.get("dW_up")), _p(out.get("dW_down")),
+                               _p(out.get("d_route")), _p(workspace), have, _stream(stream))
+    if rc != OK:
+        raise MhffnError(rc, "mhffn_backward")
+    return out
+
+
+def reference_unfused(X, W_gate, W_up, W_down, route, eps=1e-6, route_mode=ROUTE_PARAMS,
+                      dY=None, want=("dX", "dW_gate", "dW_up", "dW_down", "d_route"),
+                      workspace=None, out=None, stream=None):
+    """Unfused GPU baseline (materialises the intermediates in `workspace`).
+    Returns Y, or (Y, grads) when dY is given."""
+    d = make_desc(X, W_gate, route_mode, eps)
+    out = dict(out or {})
+    Y = out.get("Y")
+    if Y is None:
+        Y = torch.empty_like(X)
+    like = {"dX": X, "dW_gate": W_gate, "dW_up": W_up, "dW_down": W_down, "d_route": route}
+    if dY is not None:
+        for k in want:
+            if k not in out:
+                out[k] = torch.empty_like(like[k])
+    op = OP_UNFUSED_FORWARD if dY is None else OP_UNFUSED_BACKWARD
+    workspace, have = _workspace(d, op, X.device, workspace)
+    rc = load().mhffn_reference_unfused(
+        ctypes.byref(d), _p(X), _p(W_gate), _p(W_up), _p(W_down), _p(route), _p(Y), _p(dY),
+        _p(out.get("dX")), _p(out.get("dW_gate")), _p(out.get("dW_up")), _p(out.get("dW_down")),
+        _p(out.get("d_route")), _p(workspace), have, _stream(stream))
+    if rc != OK:
+        raise MhffnError(rc, "mhffn_reference_unfused")
+    if dY is None:
+        return Y
+    return Y, {k: out[k] for k in want}

@@ -1,0 +1,80 @@
+"""Host-only tests of the C-ABI library: it loads without a GPU, exports every
+symbol the header declares, and rejects bad arguments before launching."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2512_06989_amd import mhffn
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "mhffn.h")).read()
+    declared = set(re.findall(r"\b(mhffn_[a-z_]+)\s*\(", header))
+    assert declared == set(mhffn.EXPORTS)
+    lib = mhffn.load()
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert mhffn.version().startswith("mhffn-gfx950")
+
+
+def test_desc_struct_matches_header_field_order():
+    header = open(os.path.join(ROOT, "include", "mhffn.h")).read()
+    body = header[header.index("typedef struct {"):header.index("} mhffn_desc;")]
+    names = re.findall(r"\b(?:int64_t|int32_t|float)\s+(\w+);", body)
+    assert names == [f[0] for f in mhffn.Desc._fields_]
+
+
+def desc(**kw):
+    base = dict(n_tokens=64, n_heads=2, d_head=128, n_sub=3, d_sub=128, ld_x=0, ld_y=0,
+                dtype=mhffn.BF16, route_mode=mhffn.ROUTE_PARAMS, eps=1e-6)
+    base.update(kw)
+    return mhffn.Desc(*[base[f[0]] for f in mhffn.Desc._fields_])
+
+
+FAKE = ctypes.c_void_p(0x10000)   # aligned, never dereferenced: validation fails first
+
+
+def fwd(d, ptrs=None):
+    ptrs = ptrs or [FAKE] * 6
+    return mhffn.load().mhffn_forward(ctypes.byref(d), *ptrs, None, 0, None)
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(n_tokens=-1), 2), (dict(n_heads=0), 2), (dict(d_sub=0), 2), (dict(ld_x=100), 2),
+    (dict(eps=-1.0), 2), (dict(eps=float("nan")), 2), (dict(dtype=7), 3), (dict(route_mode=2), 3),
+    (dict(d_head=64), 3), (dict(d_sub=48), 3), (dict(n_sub=1000), 3),
+    (dict(ld_x=260), 4),
+    (dict(dtype=mhffn.F32, d_head=130), 3), (dict(dtype=mhffn.F32, d_head=512), 3),
+])
+def test_forward_rejects_bad_descriptors(kw, status):
+    assert fwd(desc(**kw)) == status
+
+
+def test_forward_rejects_null_and_misaligned_pointers():
+    d = desc()
+    for i in range(6):
+        ptrs = [FAKE] * 6
+        ptrs[i] = None
+        assert fwd(d, ptrs) == 1
+        ptrs[i] = ctypes.c_void_p(0x10004)
+        assert fwd(d, ptrs) == 4
+    assert mhffn.load().mhffn_forward(None, *([FAKE] * 6), None, 0, None) == 1
+
+
+def test_empty_input_is_ok_and_launches_nothing():
+    assert fwd(desc(n_tokens=0)) == 0
+
+
+def test_status_strings():
+    seen = {mhffn.status_string(i) for i in range(7)}
+    assert len(seen) == 7 and mhffn.status_string(99) == "unknown status"
+
+
+def test_forward_needs_no_workspace():
+    for name in ("dtype",):
+        assert mhffn.workspace_bytes(desc(n_tokens=16384, n_heads=16, n_sub=44), mhffn.OP_FORWARD) == 0
+    assert mhffn.workspace_bytes(desc(n_heads=0), mhffn.OP_FORWARD) == 0
