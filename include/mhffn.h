@@ -91,7 +91,7 @@ typedef struct {
 /*
  * Shape support.
  *   bf16: the fused kernels need d_head == 128, d_sub % 32 == 0 and
- *         n_sub <= 64; other shapes return MHFFN_ERR_UNSUPPORTED.
+ *         n_sub <= 96; other shapes return MHFFN_ERR_UNSUPPORTED.
  *   fp32: the fused kernels take d_head % 4 == 0, d_head <= 256, any n_sub, d_sub.
  *   mhffn_reference_unfused takes any shape with d_head % 8 == 0.
  *   Row strides must keep every row 16-byte aligned.

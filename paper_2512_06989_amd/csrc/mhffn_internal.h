@@ -19,7 +19,7 @@ struct Problem {
 
 // ---- fused forward ---------------------------------------------------------
 // bf16, d_h = 128, d_e % 32 == 0, E <= kFwdBf16MaxSub.
-constexpr int kFwdBf16MaxSub = 64;
+constexpr int kFwdBf16MaxSub = 96;
 int launch_fwd_bf16(const Problem& p, const void* X, const void* Wg, const void* Wu,
                     const void* Wd, const void* route, void* Y, void* stream);
 // fp32, d_h % 4 == 0, d_h <= 256.
