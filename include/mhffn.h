@@ -76,7 +76,7 @@ typedef enum {
 } mhffn_op;
 
 typedef struct {
-  int64_t n_tokens;  /* N = batch * sequence; any N >= 1, ragged tails are masked    */
+  int64_t n_tokens;  /* N = batch * sequence; any N >= 0, ragged tails are masked    */
   int32_t n_heads;   /* H                                                            */
   int32_t d_head;    /* d_h; d_model = H*d_h                                         */
   int32_t n_sub;     /* E, sub-networks per head                                     */
@@ -123,6 +123,22 @@ int mhffn_backward(const mhffn_desc* desc, const void* X, const void* W_gate,
                    const void* dY, void* dX, void* dW_gate, void* dW_up,
                    void* dW_down, void* d_route, void* workspace,
                    size_t workspace_bytes, void* hip_stream);
+
+/* mhffn_backward with timing marks, for profiling the phases of the fused
+ * backward on the caller's stream without a tracing tool.  The phases are, in
+ * launch order (appendix algorithms "Backward (dQ,dR)" and "Backward
+ * (dK,dU,dV)"): 0 token-major kernel (dX, R, dp), 1 weight-major kernel
+ * (dW_gate, dW_up, dW_down), 2 gating-parameter gradient (dW_r).
+ * `phase_events` is a HOST array of `n_phase_events` hipEvent_t handles owned
+ * by the caller (entries may be NULL = skipped): event 0 is recorded on
+ * `hip_stream` before the first launch, event i after phase i-1; at most 4 are
+ * used.  Everything else is exactly mhffn_backward. */
+int mhffn_backward_phases(const mhffn_desc* desc, const void* X, const void* W_gate,
+                          const void* W_up, const void* W_down, const void* route,
+                          const void* dY, void* dX, void* dW_gate, void* dW_up,
+                          void* dW_down, void* d_route, void* workspace,
+                          size_t workspace_bytes, void* hip_stream,
+                          void* const* phase_events, int n_phase_events);
 
 /* Unfused GPU baseline: the naive execution of the same layer (Methodology,
  * "Naive Multi-Head FFN", Limitations: memory pressure).  Separate kernels with

@@ -113,6 +113,16 @@ int mhffn_backward(const mhffn_desc* desc, const void* X, const void* W_gate, co
                    const void* W_down, const void* route, const void* dY, void* dX,
                    void* dW_gate, void* dW_up, void* dW_down, void* d_route, void* workspace,
                    size_t workspace_bytes, void* hip_stream) {
+  return mhffn_backward_phases(desc, X, W_gate, W_up, W_down, route, dY, dX, dW_gate, dW_up,
+                               dW_down, d_route, workspace, workspace_bytes, hip_stream, nullptr, 0);
+}
+
+int mhffn_backward_phases(const mhffn_desc* desc, const void* X, const void* W_gate,
+                          const void* W_up, const void* W_down, const void* route,
+                          const void* dY, void* dX, void* dW_gate, void* dW_up, void* dW_down,
+                          void* d_route, void* workspace, size_t workspace_bytes,
+                          void* hip_stream, void* const* phase_events, int n_phase_events) {
+  if (n_phase_events < 0 || (n_phase_events > 0 && !phase_events)) return MHFFN_ERR_NULL;
   Problem p;
   int rc = check_desc(desc, &p);
   if (rc) return rc;
@@ -125,7 +135,8 @@ int mhffn_backward(const mhffn_desc* desc, const void* X, const void* W_gate, co
   rc = check_workspace(mhffn::bwd_workspace_bytes(p, desc->dtype), workspace, workspace_bytes);
   if (rc) return rc;
   const int e = mhffn::launch_bwd(p, desc->dtype, X, W_gate, W_up, W_down, route, dY, dX, dW_gate,
-                                  dW_up, dW_down, d_route, workspace, hip_stream);
+                                  dW_up, dW_down, d_route, workspace, hip_stream, phase_events,
+                                  n_phase_events);
   if (e == -1) return MHFFN_ERR_UNSUPPORTED;
   return e == 0 ? MHFFN_OK : MHFFN_ERR_LAUNCH;
 }

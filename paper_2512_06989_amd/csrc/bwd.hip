@@ -419,7 +419,6 @@ __global__ __launch_bounds__(kWgtThreads) void bwd_wgt_kernel(BwdArgs a) {
   const int blk = (int)(item % wg_per_head) * kWgtWaves + wave;
   const bool active = blk < nblk;
   const int blk_c = active ? blk : nblk - 1;     // idle waves shadow a valid block, store nothing
-  const int e_w = blk_c / (a.de / 32);
   const int64_t N = a.N;
   const size_t row0 = (size_t)h * nblk * 32 + (size_t)blk_c * 32;  // first neuron row of this wave
 
@@ -645,10 +644,18 @@ size_t bwd_workspace_bytes(const Problem& p, int dtype) {
 
 int launch_bwd(const Problem& p, int dtype, const void* X, const void* Wg, const void* Wu,
                const void* Wd, const void* route, const void* dY, void* dX, void* dWg,
-               void* dWu, void* dWd, void* d_route, void* ws, void* stream_) {
+               void* dWu, void* dWd, void* d_route, void* ws, void* stream_,
+               void* const* phase_events, int n_phase_events) {
   if (dtype != 1) return -1;        // fp32 fused backward: not built
   if (p.E > 2 * kRouteMaxHalfSub) return -1;
   hipStream_t stream = static_cast<hipStream_t>(stream_);
+  // event i is recorded after phase i-1 (event 0: before anything is launched)
+  auto mark = [&](int i) -> hipError_t {
+    if (i < n_phase_events && phase_events && phase_events[i])
+      return hipEventRecord(static_cast<hipEvent_t>(phase_events[i]), stream);
+    return hipSuccess;
+  };
+  if (mark(0) != hipSuccess) return (int)hipErrorInvalidHandle;
   const size_t wcount = (size_t)p.H * p.E * p.de * kDh;
   if (p.N == 0) {
     void* outs[4] = {dWg, dWu, dWd, p.route_mode == 0 ? d_route : nullptr};
@@ -699,6 +706,7 @@ int launch_bwd(const Problem& p, int dtype, const void* X, const void* Wg, const
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return (int)e;
   }
+  if (mark(1) != hipSuccess) return (int)hipErrorInvalidHandle;
   if (dWg || dWu || dWd) {
     const int nblk = p.E * p.de / 32;
     const int wg_per_head = (nblk + kWgtWaves - 1) / kWgtWaves;
@@ -708,6 +716,7 @@ int launch_bwd(const Problem& p, int dtype, const void* X, const void* Wg, const
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return (int)e;
   }
+  if (mark(2) != hipSuccess) return (int)hipErrorInvalidHandle;
   if (d_route && p.route_mode == 0) {
     hipLaunchKernelGGL(bwd_route_partial_kernel, dim3(p.H, kRouteSplit), dim3(256), 0, stream, a);
     const int64_t n = (int64_t)p.H * kDh * p.E;
@@ -716,6 +725,7 @@ int launch_bwd(const Problem& p, int dtype, const void* X, const void* Wg, const
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return (int)e;
   }
+  if (mark(3) != hipSuccess) return (int)hipErrorInvalidHandle;
   return 0;
 }
 

@@ -32,7 +32,10 @@ constexpr size_t kLdsBytesPerWorkgroup = 160 * 1024;
 size_t bwd_workspace_bytes(const Problem& p, int dtype);
 int launch_bwd(const Problem& p, int dtype, const void* X, const void* Wg, const void* Wu,
                const void* Wd, const void* route, const void* dY, void* dX, void* dWg,
-               void* dWu, void* dWd, void* d_route, void* ws, void* stream);
+               void* dWu, void* dWd, void* d_route, void* ws, void* stream,
+               void* const* phase_events = nullptr, int n_phase_events = 0);
+// Phases of the fused backward, in launch order (see mhffn_backward_phases).
+constexpr int kBwdPhases = 3;
 
 // ---- unfused baseline ------------------------------------------------------
 size_t unfused_workspace_bytes(const Problem& p, int dtype, bool backward);

@@ -15,7 +15,7 @@ OK = 0
 F32, BF16 = 0, 1
 ROUTE_PARAMS, ROUTE_WEIGHTS = 0, 1
 OP_FORWARD, OP_BACKWARD, OP_UNFUSED_FORWARD, OP_UNFUSED_BACKWARD = 0, 1, 2, 3
-EXPORTS = ("mhffn_workspace_bytes", "mhffn_forward", "mhffn_backward",
+EXPORTS = ("mhffn_workspace_bytes", "mhffn_forward", "mhffn_backward", "mhffn_backward_phases",
            "mhffn_reference_unfused", "mhffn_status_string", "mhffn_version")
 
 
@@ -54,6 +54,9 @@ def load():
     lib.mhffn_forward.restype = ctypes.c_int
     lib.mhffn_backward.argtypes = [dp] + [vp] * 11 + [vp, sz, vp]
     lib.mhffn_backward.restype = ctypes.c_int
+    lib.mhffn_backward_phases.argtypes = [dp] + [vp] * 11 + [vp, sz, vp, ctypes.POINTER(vp),
+                                          ctypes.c_int]
+    lib.mhffn_backward_phases.restype = ctypes.c_int
     lib.mhffn_reference_unfused.argtypes = [dp] + [vp] * 12 + [vp, sz, vp]
     lib.mhffn_reference_unfused.restype = ctypes.c_int
     lib.mhffn_status_string.argtypes = [ctypes.c_int]
@@ -125,8 +128,10 @@ def forward(X, W_gate, W_up, W_down, route, eps=1e-6, route_mode=ROUTE_PARAMS, o
 
 def backward(X, W_gate, W_up, W_down, route, dY, eps=1e-6, route_mode=ROUTE_PARAMS,
              want=("dX", "dW_gate", "dW_up", "dW_down", "d_route"), workspace=None, out=None,
-             stream=None):
-    """Fused recompute-based backward.  Returns a dict of the requested gradients."""
+             stream=None, phase_events=None):
+    """Fused recompute-based backward.  Returns a dict of the requested gradients.
+    `phase_events`: optional list of raw hipEvent_t handles (ints) recorded between
+    the phases of the backward (see mhffn_backward_phases)."""
     d = make_desc(X, W_gate, route_mode, eps, dY)
     out = dict(out or {})
     like = {"dX": X, "dW_gate": W_gate, "dW_up": W_up, "dW_down": W_down, "d_route": route}
@@ -134,10 +139,14 @@ def backward(X, W_gate, W_up, W_down, route, dY, eps=1e-6, route_mode=ROUTE_PARA
         if k not in out:
             out[k] = torch.empty_like(like[k])
     workspace, have = _workspace(d, OP_BACKWARD, X.device, workspace)
-    rc = load().mhffn_backward(ctypes.byref(d), _p(X), _p(W_gate), _p(W_up), _p(W_down),
-                               _p(route), _p(dY), _p(out.get("dX")), _p(out.get("dW_gate")),
-                               _p(out.get("dW_up")), _p(out.get("dW_down")),
-                               _p(out.get("d_route")), _p(workspace), have, _stream(stream))
+    args = (ctypes.byref(d), _p(X), _p(W_gate), _p(W_up), _p(W_down), _p(route), _p(dY),
+            _p(out.get("dX")), _p(out.get("dW_gate")), _p(out.get("dW_up")),
+            _p(out.get("dW_down")), _p(out.get("d_route")), _p(workspace), have, _stream(stream))
+    if phase_events:
+        ev = (ctypes.c_void_p * len(phase_events))(*phase_events)
+        rc = load().mhffn_backward_phases(*args, ev, len(phase_events))
+    else:
+        rc = load().mhffn_backward(*args)
     if rc != OK:
         raise MhffnError(rc, "mhffn_backward")
     return out
