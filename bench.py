@@ -63,7 +63,7 @@ class HipEvents:
         return float(ms.value)
 
 
-def cpu_baseline(w, d, budget_heads=2, budget_tokens=2048):
+def cpu_baseline(w, d, budget_heads=16, budget_tokens=6144):
     """The fp64 oracle, as it stands, on a bounded sample of the workload:
     `budget_heads` whole heads x the first `budget_tokens` tokens, forward + backward."""
     import numpy as np
@@ -99,6 +99,9 @@ def main():
     ap.add_argument("--workload", default="1p3b_fwdbwd")
     ap.add_argument("--tokens", type=int, default=0, help="override the token count")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 256 MiB device copy (reference for the HBM byte "
+                         "counters of a profiler run)")
     ap.add_argument("--forward-only", action="store_true",
                     help="time the forward alone (step = forward); for profiling")
     args = ap.parse_args()
@@ -146,6 +149,14 @@ def main():
 
     for _ in range(args.warmup):
         step()
+    if args.calibrate_copy:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        src.fill_(1)
+        torch.cuda.synchronize()
+        dst.copy_(src)   # reads 256 MiB, writes 256 MiB
+        torch.cuda.synchronize()
+        del src, dst
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(K):

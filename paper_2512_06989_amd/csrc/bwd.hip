@@ -583,32 +583,90 @@ __global__ __launch_bounds__(kWgtThreads) void bwd_wgt_kernel(BwdArgs a) {
 // dW_r[h][j][e] = sum_tok q[tok][j] dp[tok][e]: partial sums per token split,
 // then a fixed-order reduction (deterministic).
 // ---------------------------------------------------------------------------
-constexpr int kRouteMaxHalfSub = 48;  // E <= 96: each thread keeps E/2 accumulators
+constexpr int kRouteSplit = 16;                 // workgroups per head
+constexpr int kRouteParts = kRouteSplit * 4;    // one partial per wave
+constexpr int kRouteMaxSub = 96;
 
+// D[j][e] += sum_tok q^T[j][tok] dp[tok][e] on the MFMA: the A operand is the
+// transposing LDS read of a [32 tok][128] tile of X, the B operand (contraction
+// slot s <-> token 16*t2 + 8*(s/4) + 4g + s%4, column e) comes straight from
+// the [H][E][N] dp array.  Each wave walks its own token blocks and leaves its
+// own partial [128][E] in the workspace.
+template <int EB>
 __global__ __launch_bounds__(256) void bwd_route_partial_kernel(BwdArgs a) {
-  const int h = blockIdx.x, s = blockIdx.y;
-  const int j = threadIdx.x & 127, par = threadIdx.x >> 7;  // sub-networks e = 2i + par
+  __shared__ __attribute__((aligned(16))) unsigned char tiles[4 * kTileBytes];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int r = lane & 31, g = lane >> 5;
+  const int h = blockIdx.x;
+  const int part = blockIdx.y * 4 + wave;
   const int64_t N = a.N;
-  const int64_t per = (N + a.n_split - 1) / a.n_split;
-  const int64_t t0 = s * per, t1 = (t0 + per < N) ? t0 + per : N;
   const int E = a.E;
+  const int64_t nb = (N + 31) / 32;
+  const int64_t iters = (nb + kRouteParts - 1) / kRouteParts;  // same for every wave
   const float* DPh = a.DPws + (size_t)h * E * N;
-  float acc[kRouteMaxHalfSub];
+  unsigned char* tile = tiles + wave * kTileBytes;
+  f32x16 acc[EB][4];
 #pragma unroll
-  for (int i = 0; i < kRouteMaxHalfSub; ++i) acc[i] = 0.f;
-  for (int64_t t = t0; t < t1; ++t) {
-    const float qv = bf16_bits_to_f32(a.X[t * a.ldx + h * kDh + j]);
+  for (int eb = 0; eb < EB; ++eb)
 #pragma unroll
-    for (int i = 0; i < kRouteMaxHalfSub; ++i) {
-      const int e = 2 * i + par;
-      if (e < E) acc[i] = fmaf(qv, DPh[(size_t)e * N + t], acc[i]);
+    for (int jb = 0; jb < 4; ++jb) acc[eb][jb] = f32x16{0};
+
+  for (int64_t it = 0; it < iters; ++it) {
+    const int64_t b = it * kRouteParts + part;
+    const int64_t tok0 = b * 32;   // may lie beyond N: then everything loaded is zero
+    // X tile -> this wave's LDS tile (8 chunks per lane)
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int chunk = lane + 64 * i;
+      const int64_t t = tok0 + (chunk >> 4);
+      u32x4 v = {0, 0, 0, 0};
+      if (t < N) v = *reinterpret_cast<const u32x4*>(a.X + t * a.ldx + h * kDh + (chunk & 15) * 8);
+      *reinterpret_cast<u32x4*>(tile + tile_off(chunk >> 4, chunk & 15)) = v;
     }
-  }
-  float* out = a.WRws + ((size_t)h * a.n_split + s) * kDh * E;
+    // dp operands
+    bf16x8 bp[EB][2];
 #pragma unroll
-  for (int i = 0; i < kRouteMaxHalfSub; ++i) {
-    const int e = 2 * i + par;
-    if (e < E) out[j * E + e] = acc[i];
+    for (int eb = 0; eb < EB; ++eb) {
+      const int e = 32 * eb + r;
+#pragma unroll
+      for (int t2 = 0; t2 < 2; ++t2) {
+        float v[8];
+#pragma unroll
+        for (int s8 = 0; s8 < 8; ++s8) {
+          const int64_t t = tok0 + 16 * t2 + 8 * (s8 >> 2) + 4 * g + (s8 & 3);
+          v[s8] = (e < E && t < N) ? DPh[(size_t)e * N + t] : 0.f;
+        }
+        u32x4 pk;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) pk[i] = pack_bf16(v[2 * i], v[2 * i + 1]);
+        bp[eb][t2] = __builtin_bit_cast(bf16x8, pk);
+      }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int t2 = 0; t2 < 2; ++t2) {
+#pragma unroll
+      for (int jb = 0; jb < 4; ++jb) {
+        const bf16x8 qT = tile_read_tr(tile, 16 * t2 + 4 * g, 32 * jb, lane);
+#pragma unroll
+        for (int eb = 0; eb < EB; ++eb) acc[eb][jb] = mfma32(qT, bp[eb][t2], acc[eb][jb]);
+      }
+    }
+    __syncthreads();
+  }
+  float* out = a.WRws + ((size_t)h * kRouteParts + part) * kDh * E;
+#pragma unroll
+  for (int eb = 0; eb < EB; ++eb) {
+    const int e = 32 * eb + r;
+    if (e < E) {
+#pragma unroll
+      for (int jb = 0; jb < 4; ++jb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int j = 32 * jb + 8 * (v / 4) + 4 * g + (v % 4);
+          out[j * E + e] = acc[eb][jb][v];
+        }
+    }
   }
 }
 
@@ -629,8 +687,6 @@ __global__ void fill_zero_kernel(uint32_t* p, size_t n_words) {
   if (i < n_words) p[i] = 0;
 }
 
-constexpr int kRouteSplit = 32;
-
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 }  // namespace
@@ -638,7 +694,7 @@ size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 size_t bwd_workspace_bytes(const Problem& p, int dtype) {
   if (dtype != 1) return 0;
   const size_t nhe = align256((size_t)p.N * p.H * p.E * sizeof(float));
-  const size_t wr = align256((size_t)p.H * kRouteSplit * kDh * p.E * sizeof(float));
+  const size_t wr = align256((size_t)p.H * kRouteParts * kDh * p.E * sizeof(float));
   return 2 * nhe + wr;
 }
 
@@ -647,7 +703,7 @@ int launch_bwd(const Problem& p, int dtype, const void* X, const void* Wg, const
                void* dWu, void* dWd, void* d_route, void* ws, void* stream_,
                void* const* phase_events, int n_phase_events) {
   if (dtype != 1) return -1;        // fp32 fused backward: not built
-  if (p.E > 2 * kRouteMaxHalfSub) return -1;
+  if (p.E > kRouteMaxSub) return -1;
   hipStream_t stream = static_cast<hipStream_t>(stream_);
   // event i is recorded after phase i-1 (event 0: before anything is launched)
   auto mark = [&](int i) -> hipError_t {
@@ -685,7 +741,7 @@ int launch_bwd(const Problem& p, int dtype, const void* X, const void* Wg, const
   a.WRws = reinterpret_cast<float*>(static_cast<unsigned char*>(ws) + 2 * nhe);
   a.N = p.N; a.ldx = p.ldx; a.ldy = p.ldy;
   a.H = p.H; a.E = p.E; a.de = p.de; a.route_mode = p.route_mode; a.eps = p.eps;
-  a.n_split = kRouteSplit;
+  a.n_split = kRouteParts;
 
   // token-major kernel (always: it also produces R for the weight-major kernel)
   {
@@ -718,7 +774,10 @@ int launch_bwd(const Problem& p, int dtype, const void* X, const void* Wg, const
   }
   if (mark(2) != hipSuccess) return (int)hipErrorInvalidHandle;
   if (d_route && p.route_mode == 0) {
-    hipLaunchKernelGGL(bwd_route_partial_kernel, dim3(p.H, kRouteSplit), dim3(256), 0, stream, a);
+    const dim3 rgrid(p.H, kRouteSplit);
+    if (p.E <= 32) hipLaunchKernelGGL(bwd_route_partial_kernel<1>, rgrid, dim3(256), 0, stream, a);
+    else if (p.E <= 64) hipLaunchKernelGGL(bwd_route_partial_kernel<2>, rgrid, dim3(256), 0, stream, a);
+    else hipLaunchKernelGGL(bwd_route_partial_kernel<3>, rgrid, dim3(256), 0, stream, a);
     const int64_t n = (int64_t)p.H * kDh * p.E;
     hipLaunchKernelGGL(bwd_route_reduce_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0,
                        stream, a);

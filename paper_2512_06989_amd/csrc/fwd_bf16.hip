@@ -21,6 +21,8 @@
 #include "mhffn_device.h"
 #include "mhffn_internal.h"
 
+#include <cstdlib>
+
 namespace mhffn {
 namespace {
 
@@ -303,7 +305,9 @@ int launch_fwd_bf16(const Problem& p, const void* X, const void* Wg, const void*
   a.N = p.N; a.ldx = p.ldx; a.ldy = p.ldy;
   a.H = p.H; a.E = p.E; a.de = p.de; a.route_mode = p.route_mode; a.eps = p.eps;
   a.n_tiles = 0; a.n_items = 0;
-  return launch_variant<2, 4>(p, a, static_cast<hipStream_t>(stream));
+  // 8 waves x 32 tokens (two waves per SIMD) measured 25% faster than 4 waves x
+  // 64 tokens at the 1.3B shape: the second wave hides LDS and barrier latency.
+  return launch_variant<1, 8>(p, a, static_cast<hipStream_t>(stream));
 }
 
 }  // namespace mhffn
