@@ -1,9 +1,477 @@
-// placeholder until the unfused baseline lands
+// Unfused GPU baseline of the gated Multi-Head FFN: the naive execution the
+// paper calls memory-prohibitive (Methodology, "Naive Multi-Head FFN",
+// Limitations: memory pressure).  Every step is its own kernel and the
+// [H][N][d_ff] intermediates make a round trip through device memory:
+//
+//   forward : R = eq:routing(X W_r)                     gating_kernel
+//             G = X_h K_h^T,  U' = X_h U_h^T            batched GEMM (x2)
+//             A = SiLU(G) .* U' .* R                    act_fwd_kernel
+//             Y_h = A_h V_h                             batched GEMM
+//   backward: dA = dY_h V_h^T                           batched GEMM
+//             dG, dU', dr from G, U', dA, R             act_bwd_kernel
+//             dX_h = dG K_h + dU' U_h                   batched GEMM (two operand pairs)
+//             dK_h = dG^T X_h, dU_h = dU'^T X_h, dV_h = A^T dY_h     batched GEMM (x3)
+//             dp from dr; dX_h += dp W_r^T              route_bwd_kernel
+//             dW_r[h] = X_h^T dp                        batched GEMM
+//
+// One generic batched GEMM (MFMA, LDS tiled, arbitrary strides, bf16 or fp32)
+// serves all products.  Shape-generic: any H, E, d_e, d_h % 8 == 0.
 #include "mhffn_device.h"
 #include "mhffn_internal.h"
+
 namespace mhffn {
-size_t unfused_workspace_bytes(const Problem&, int, bool) { return 0; }
-int launch_unfused(const Problem&, int, const void*, const void*, const void*, const void*,
-                   const void*, void*, const void*, void*, void*, void*, void*, void*, void*,
-                   void*) { return -1; }
+namespace {
+
+template <typename T> __device__ __forceinline__ float ldf(const T* p, size_t i);
+template <> __device__ __forceinline__ float ldf<float>(const float* p, size_t i) { return p[i]; }
+template <> __device__ __forceinline__ float ldf<uint16_t>(const uint16_t* p, size_t i) {
+  return bf16_bits_to_f32(p[i]);
+}
+template <typename T> __device__ __forceinline__ void stf(T* p, size_t i, float v);
+template <> __device__ __forceinline__ void stf<float>(float* p, size_t i, float v) { p[i] = v; }
+template <> __device__ __forceinline__ void stf<uint16_t>(uint16_t* p, size_t i, float v) {
+  p[i] = (uint16_t)(pack_bf16(v, 0.f) & 0xFFFFu);
+}
+
+__device__ __forceinline__ float sigmoid_exact(float x) {
+  if (x >= 0.f) return 1.0f / (1.0f + __expf(-x));
+  const float t = __expf(x);
+  return t / (1.0f + t);
+}
+
+// ---------------------------------------------------------------------------
+// Batched GEMM  C[b][m][n] (+)= sum_k A[b](m,k) B[b](n,k)  (+ sum_k A2(m,k) B2(n,k))
+// with element strides for every index; fp32 accumulation on the MFMA.
+// ---------------------------------------------------------------------------
+struct GemmArgs {
+  const void* A; const void* B; const void* A2; const void* B2; void* C;
+  int64_t M, N, K;
+  int64_t a_ms, a_ks, a_bs;   // strides of A along m, k, batch
+  int64_t b_ns, b_ks, b_bs;   // strides of B along n, k, batch
+  int64_t c_ms, c_bs;         // C row stride (n is contiguous) and batch stride
+  int accumulate;             // add to what C holds
+};
+
+constexpr int kGM = 128, kGN = 128, kGK = 32;
+
+template <typename T> struct Frag;
+template <> struct Frag<uint16_t> {
+  static constexpr int kPad = 8;          // LDS row = 32 + 8 bf16 = 80 bytes
+  static constexpr int kSteps = 2;        // 16 k per MFMA
+};
+template <> struct Frag<float> {
+  static constexpr int kPad = 1;          // LDS row = 33 floats
+  static constexpr int kSteps = 16;       // 2 k per MFMA
+};
+
+// Stage a [128][32] tile (rows along `rs`, k along `ks`) into LDS, zero filled
+// outside (rows, kk).  16-byte vector loads along whichever index is contiguous.
+template <typename T>
+__device__ __forceinline__ void stage_tile(T* lds, const T* src, int64_t rs, int64_t ks,
+                                           int64_t rows, int64_t kk, int tid) {
+  constexpr int LD = kGK + Frag<T>::kPad;
+  constexpr int V = 16 / sizeof(T);       // elements per 16-byte vector
+  const bool al = (reinterpret_cast<uintptr_t>(src) & 15u) == 0;
+  if (ks == 1 && al && (rs % V) == 0) {
+    // k contiguous: 128 rows x (32/V) vectors
+    constexpr int VPR = kGK / V;
+    for (int idx = tid; idx < kGM * VPR; idx += 256) {
+      const int row = idx / VPR, kv = (idx % VPR) * V;
+      T tmp[V];
+      if (row < rows && kv + V <= kk) {
+        *reinterpret_cast<u32x4*>(tmp) = *reinterpret_cast<const u32x4*>(src + row * rs + kv);
+      } else {
+#pragma unroll
+        for (int i = 0; i < V; ++i)
+          tmp[i] = (row < rows && kv + i < kk) ? src[row * rs + (kv + i)] : T(0);
+      }
+#pragma unroll
+      for (int i = 0; i < V; ++i) lds[row * LD + kv + i] = tmp[i];
+    }
+  } else if (rs == 1 && al && (ks % V) == 0) {
+    // rows contiguous: 32 k x (128/V) vectors, scattered (transposed) into LDS
+    constexpr int VPK = kGM / V;
+    for (int idx = tid; idx < kGK * VPK; idx += 256) {
+      const int k = idx / VPK, rv = (idx % VPK) * V;
+      T tmp[V];
+      if (k < kk && rv + V <= rows) {
+        *reinterpret_cast<u32x4*>(tmp) = *reinterpret_cast<const u32x4*>(src + k * ks + rv);
+      } else {
+#pragma unroll
+        for (int i = 0; i < V; ++i)
+          tmp[i] = (k < kk && rv + i < rows) ? src[k * ks + (rv + i)] : T(0);
+      }
+#pragma unroll
+      for (int i = 0; i < V; ++i) lds[(rv + i) * LD + k] = tmp[i];
+    }
+  } else {
+    for (int idx = tid; idx < kGM * kGK; idx += 256) {
+      const int row = idx / kGK, k = idx % kGK;
+      lds[row * LD + k] = (row < rows && k < kk) ? src[row * rs + k * ks] : T(0);
+    }
+  }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g) {
+  constexpr int LD = kGK + Frag<T>::kPad;
+  __shared__ __attribute__((aligned(16))) T As[kGM * LD];
+  __shared__ __attribute__((aligned(16))) T Bs[kGN * LD];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int r = lane & 31, gh = lane >> 5;
+  const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
+  const int64_t m0 = (int64_t)blockIdx.y * kGM, n0 = (int64_t)blockIdx.x * kGN;
+  const int64_t b = blockIdx.z;
+  f32x16 acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j) acc[i][j] = f32x16{0};
+
+  const int npairs = g.A2 ? 2 : 1;
+  for (int pair = 0; pair < npairs; ++pair) {
+    const T* A = static_cast<const T*>(pair ? g.A2 : g.A) + b * g.a_bs + m0 * g.a_ms;
+    const T* B = static_cast<const T*>(pair ? g.B2 : g.B) + b * g.b_bs + n0 * g.b_ns;
+    for (int64_t k0 = 0; k0 < g.K; k0 += kGK) {
+      stage_tile<T>(As, A + k0 * g.a_ks, g.a_ms, g.a_ks, g.M - m0, g.K - k0, tid);
+      stage_tile<T>(Bs, B + k0 * g.b_ks, g.b_ns, g.b_ks, g.N - n0, g.K - k0, tid);
+      __syncthreads();
+#pragma unroll
+      for (int ks = 0; ks < Frag<T>::kSteps; ++ks) {
+        if constexpr (sizeof(T) == 2) {
+          bf16x8 af[2], bf[2];
+#pragma unroll
+          for (int i = 0; i < 2; ++i) {
+            af[i] = *reinterpret_cast<const bf16x8*>(&As[(wm + 32 * i + r) * LD + 16 * ks + 8 * gh]);
+            bf[i] = *reinterpret_cast<const bf16x8*>(&Bs[(wn + 32 * i + r) * LD + 16 * ks + 8 * gh]);
+          }
+#pragma unroll
+          for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j) acc[i][j] = mfma32(af[i], bf[j], acc[i][j]);
+        } else {
+          float af[2], bf[2];
+#pragma unroll
+          for (int i = 0; i < 2; ++i) {
+            af[i] = As[(wm + 32 * i + r) * LD + 2 * ks + gh];
+            bf[i] = Bs[(wn + 32 * i + r) * LD + 2 * ks + gh];
+          }
+#pragma unroll
+          for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+              acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[i], bf[j], acc[i][j], 0, 0, 0);
+        }
+      }
+      __syncthreads();
+    }
+  }
+  T* C = static_cast<T*>(g.C) + b * g.c_bs;
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int64_t n = n0 + wn + 32 * j + r;
+      if (n >= g.N) continue;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int64_t m = m0 + wm + 32 * i + 8 * (v / 4) + 4 * gh + (v % 4);
+        if (m >= g.M) continue;
+        const size_t o = (size_t)m * g.c_ms + n;
+        float val = acc[i][j][v];
+        if (g.accumulate) val += ldf<T>(C, o);
+        stf<T>(C, o, val);
+      }
+    }
+}
+
+template <typename T>
+int run_gemm(const GemmArgs& g, int batch, hipStream_t st) {
+  if (g.M <= 0 || g.N <= 0 || batch <= 0) return 0;
+  dim3 grid((unsigned)((g.N + kGN - 1) / kGN), (unsigned)((g.M + kGM - 1) / kGM), (unsigned)batch);
+  hipLaunchKernelGGL(gemm_kernel<T>, grid, dim3(256), 0, st, g);
+  return (int)hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// elementwise / small kernels
+// ---------------------------------------------------------------------------
+struct UArgs {
+  const void* X; const void* route; const void* dY; void* dX;
+  float* R;      // [N][H][E]
+  float* Zinv;   // [N][H]
+  float* DR;     // [N][H][E]
+  void* DPt;     // [H][N][E] in the storage dtype
+  void* G; void* U; void* A; void* dA;   // [H][N][d_ff]
+  int64_t N, ldx, ldy;
+  int H, dh, E, de, route_mode;
+  float eps;
+};
+
+// one thread per (token, head): eq:routing
+template <typename T>
+__global__ void gating_kernel(UArgs a) {
+  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= a.N * a.H) return;
+  const int64_t l = idx / a.H;
+  const int h = (int)(idx % a.H);
+  float* r = a.R + idx * a.E;
+  if (a.route_mode == 1) {
+    const float* Rin = static_cast<const float*>(a.route);
+    for (int e = 0; e < a.E; ++e) r[e] = Rin[idx * a.E + e];
+    a.Zinv[idx] = 0.f;
+    return;
+  }
+  const T* q = static_cast<const T*>(a.X) + l * a.ldx + (size_t)h * a.dh;
+  const T* W = static_cast<const T*>(a.route) + (size_t)h * a.dh * a.E;
+  float z = 0.f;
+  for (int e = 0; e < a.E; ++e) {
+    float p = 0.f;
+    for (int j = 0; j < a.dh; ++j) p = fmaf(ldf<T>(q, j), ldf<T>(W, (size_t)j * a.E + e), p);
+    const float s = sigmoid_exact(p);
+    r[e] = s;
+    z += s;
+  }
+  const float zi = 1.0f / (z + a.eps);
+  for (int e = 0; e < a.E; ++e) r[e] *= zi;
+  a.Zinv[idx] = zi;
+}
+
+// A = SiLU(G) .* U' .* R, one thread per element of [H][N][d_ff]
+template <typename T>
+__global__ void act_fwd_kernel(UArgs a) {
+  const int64_t dff = (int64_t)a.E * a.de;
+  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= (int64_t)a.H * a.N * dff) return;
+  const int64_t c = idx % dff;
+  const int64_t l = (idx / dff) % a.N;
+  const int h = (int)(idx / (dff * a.N));
+  const float gv = ldf<T>(static_cast<const T*>(a.G), idx), uv = ldf<T>(static_cast<const T*>(a.U), idx);
+  const float rr = a.R[(l * a.H + h) * a.E + c / a.de];
+  stf<T>(static_cast<T*>(a.A), idx, gv * sigmoid_exact(gv) * uv * rr);
+}
+
+// dG, dU' (in place of G, U') and dr; one workgroup of 64 threads per (head, token, sub-network)
+template <typename T>
+__global__ __launch_bounds__(64) void act_bwd_kernel(UArgs a) {
+  const int64_t dff = (int64_t)a.E * a.de;
+  const int64_t blk = blockIdx.x;                 // (h * N + l) * E + e
+  const int e = (int)(blk % a.E);
+  const int64_t hl = blk / a.E;
+  const int64_t l = hl % a.N;
+  const int h = (int)(hl / a.N);
+  const float rr = a.R[(l * a.H + h) * a.E + e];
+  T* G = static_cast<T*>(a.G);
+  T* U = static_cast<T*>(a.U);
+  const T* dA = static_cast<const T*>(a.dA);
+  float dr = 0.f;
+  for (int c = threadIdx.x; c < a.de; c += 64) {
+    const size_t i = (size_t)hl * dff + (size_t)e * a.de + c;
+    const float gv = ldf<T>(G, i), uv = ldf<T>(U, i), da = ldf<T>(dA, i);
+    const float sg = sigmoid_exact(gv);
+    const float silu = gv * sg;
+    dr = fmaf(da, silu * uv, dr);
+    stf<T>(U, i, rr * da * silu);
+    stf<T>(G, i, rr * da * uv * (sg + silu * (1.0f - sg)));
+  }
+  for (int off = 32; off > 0; off >>= 1) dr += __shfl_xor(dr, off);
+  if (threadIdx.x == 0) a.DR[(l * a.H + h) * a.E + e] = dr;
+}
+
+// per (token, head): dp from dr (params mode) and dX_h += dp W_r^T; DPt[h][l][e] = dp
+template <typename T>
+__global__ __launch_bounds__(128) void route_bwd_kernel(UArgs a, void* dR_out) {
+  const int64_t idx = blockIdx.x;                 // l * H + h
+  const int64_t l = idx / a.H;
+  const int h = (int)(idx % a.H);
+  const float* r = a.R + idx * a.E;
+  const float* dr = a.DR + idx * a.E;
+  if (a.route_mode == 1) {
+    if (dR_out)
+      for (int e = threadIdx.x; e < a.E; e += 128) static_cast<float*>(dR_out)[idx * a.E + e] = dr[e];
+    return;
+  }
+  extern __shared__ float dps[];                  // [E]
+  const float zi = a.Zinv[idx];
+  float dot = 0.f;
+  for (int e = 0; e < a.E; ++e) dot = fmaf(dr[e], r[e], dot);
+  for (int e = threadIdx.x; e < a.E; e += 128) {
+    const float s = r[e] / zi;
+    const float dp = (dr[e] - dot) * zi * s * (1.0f - s);
+    dps[e] = dp;
+    stf<T>(static_cast<T*>(a.DPt), ((size_t)h * a.N + l) * a.E + e, dp);
+  }
+  __syncthreads();
+  if (a.dX) {
+    const T* W = static_cast<const T*>(a.route) + (size_t)h * a.dh * a.E;
+    T* dx = static_cast<T*>(a.dX) + l * a.ldx + (size_t)h * a.dh;
+    for (int j = threadIdx.x; j < a.dh; j += 128) {
+      float acc = ldf<T>(dx, j);
+      for (int e = 0; e < a.E; ++e) acc = fmaf(dps[e], ldf<T>(W, (size_t)j * a.E + e), acc);
+      stf<T>(dx, j, acc);
+    }
+  }
+}
+
+__global__ void zero_words_kernel(uint32_t* p, size_t n) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = 0;
+}
+
+size_t al256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+struct Layout {
+  size_t R, Zinv, G, U, A, dA, DR, DPt, total;
+};
+Layout make_layout(const Problem& p, size_t es, bool backward) {
+  Layout L{};
+  const size_t nhe = (size_t)p.N * p.H * p.E, nh = (size_t)p.N * p.H;
+  const size_t big = (size_t)p.N * p.H * p.E * p.de * es;
+  size_t o = 0;
+  L.R = o; o += al256(nhe * 4);
+  L.Zinv = o; o += al256(nh * 4);
+  L.G = o; o += al256(big);
+  L.U = o; o += al256(big);
+  L.A = o; o += al256(big);
+  if (backward) {
+    L.dA = o; o += al256(big);
+    L.DR = o; o += al256(nhe * 4);
+    L.DPt = o; o += al256(nhe * es);
+  }
+  L.total = o;
+  return L;
+}
+
+template <typename T>
+int run_unfused(const Problem& p, const void* X, const void* Wg, const void* Wu, const void* Wd,
+                const void* route, void* Y, const void* dY, void* dX, void* dWg, void* dWu,
+                void* dWd, void* d_route, void* ws, hipStream_t st) {
+  const bool backward = dY != nullptr;
+  const int64_t dff = (int64_t)p.E * p.de;
+  const size_t wcount = (size_t)p.H * dff * p.dh;
+  if (p.N == 0) {
+    if (backward) {
+      void* outs[4] = {dWg, dWu, dWd, p.route_mode == 0 ? d_route : nullptr};
+      const size_t bytes[4] = {wcount * sizeof(T), wcount * sizeof(T), wcount * sizeof(T),
+                               (size_t)p.H * p.dh * p.E * sizeof(T)};
+      for (int i = 0; i < 4; ++i)
+        if (outs[i])
+          hipLaunchKernelGGL(zero_words_kernel, dim3((unsigned)((bytes[i] / 4 + 255) / 256)),
+                             dim3(256), 0, st, static_cast<uint32_t*>(outs[i]), bytes[i] / 4);
+    }
+    return (int)hipGetLastError();
+  }
+  const Layout L = make_layout(p, sizeof(T), backward);
+  unsigned char* w = static_cast<unsigned char*>(ws);
+  UArgs a{};
+  a.X = X; a.route = route; a.dY = dY; a.dX = dX;
+  a.R = reinterpret_cast<float*>(w + L.R);
+  a.Zinv = reinterpret_cast<float*>(w + L.Zinv);
+  a.G = w + L.G; a.U = w + L.U; a.A = w + L.A;
+  a.dA = backward ? w + L.dA : nullptr;
+  a.DR = backward ? reinterpret_cast<float*>(w + L.DR) : nullptr;
+  a.DPt = backward ? w + L.DPt : nullptr;
+  a.N = p.N; a.ldx = p.ldx; a.ldy = p.ldy;
+  a.H = p.H; a.dh = p.dh; a.E = p.E; a.de = p.de; a.route_mode = p.route_mode; a.eps = p.eps;
+  const T* Xp = static_cast<const T*>(X);
+  const int64_t hs = (int64_t)p.N * dff;  // batch stride of the [H][N][d_ff] buffers
+  int rc;
+
+  // (i) gating weights
+  hipLaunchKernelGGL(gating_kernel<T>, dim3((unsigned)((p.N * p.H + 127) / 128)), dim3(128), 0, st, a);
+  // (ii) G = X_h K_h^T, U' = X_h U_h^T
+  for (int which = 0; which < 2; ++which) {
+    GemmArgs g{};
+    g.A = Xp; g.B = which ? Wu : Wg; g.C = which ? a.U : a.G;
+    g.M = p.N; g.N = dff; g.K = p.dh;
+    g.a_ms = p.ldx; g.a_ks = 1; g.a_bs = p.dh;
+    g.b_ns = p.dh; g.b_ks = 1; g.b_bs = dff * p.dh;
+    g.c_ms = dff; g.c_bs = hs;
+    if ((rc = run_gemm<T>(g, p.H, st))) return rc;
+  }
+  // (iii) activation and weighting
+  {
+    const int64_t n = (int64_t)p.H * p.N * dff;
+    hipLaunchKernelGGL(act_fwd_kernel<T>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, a);
+  }
+  // (iv) Y_h = A_h V_h
+  {
+    GemmArgs g{};
+    g.A = a.A; g.B = Wd; g.C = static_cast<T*>(Y);
+    g.M = p.N; g.N = p.dh; g.K = dff;
+    g.a_ms = dff; g.a_ks = 1; g.a_bs = hs;
+    g.b_ns = 1; g.b_ks = p.dh; g.b_bs = dff * p.dh;
+    g.c_ms = p.ldy; g.c_bs = p.dh;
+    if ((rc = run_gemm<T>(g, p.H, st))) return rc;
+  }
+  if (!backward) return (int)hipGetLastError();
+
+  const T* dYp = static_cast<const T*>(dY);
+  // dA = dY_h V_h^T
+  {
+    GemmArgs g{};
+    g.A = dYp; g.B = Wd; g.C = a.dA;
+    g.M = p.N; g.N = dff; g.K = p.dh;
+    g.a_ms = p.ldy; g.a_ks = 1; g.a_bs = p.dh;
+    g.b_ns = p.dh; g.b_ks = 1; g.b_bs = dff * p.dh;
+    g.c_ms = dff; g.c_bs = hs;
+    if ((rc = run_gemm<T>(g, p.H, st))) return rc;
+  }
+  // dG, dU' in place of G, U'; dr
+  hipLaunchKernelGGL(act_bwd_kernel<T>, dim3((unsigned)((int64_t)p.H * p.N * p.E)), dim3(64), 0, st, a);
+  // dX_h = dG K_h + dU' U_h
+  if (dX) {
+    GemmArgs g{};
+    g.A = a.G; g.B = Wg; g.A2 = a.U; g.B2 = Wu; g.C = dX;
+    g.M = p.N; g.N = p.dh; g.K = dff;
+    g.a_ms = dff; g.a_ks = 1; g.a_bs = hs;
+    g.b_ns = 1; g.b_ks = p.dh; g.b_bs = dff * p.dh;
+    g.c_ms = p.ldx; g.c_bs = p.dh;
+    if ((rc = run_gemm<T>(g, p.H, st))) return rc;
+  }
+  // dK_h = dG^T X_h, dU_h = dU'^T X_h, dV_h = A^T dY_h   (contraction over tokens)
+  for (int which = 0; which < 3; ++which) {
+    void* out = which == 0 ? dWg : which == 1 ? dWu : dWd;
+    if (!out) continue;
+    GemmArgs g{};
+    g.A = which == 0 ? a.G : which == 1 ? a.U : a.A;
+    g.B = which == 2 ? dYp : Xp;
+    g.C = out;
+    g.M = dff; g.N = p.dh; g.K = p.N;
+    g.a_ms = 1; g.a_ks = dff; g.a_bs = hs;
+    g.b_ns = 1; g.b_ks = which == 2 ? p.ldy : p.ldx; g.b_bs = p.dh;
+    g.c_ms = p.dh; g.c_bs = dff * p.dh;
+    if ((rc = run_gemm<T>(g, p.H, st))) return rc;
+  }
+  // routing derivative
+  hipLaunchKernelGGL(route_bwd_kernel<T>, dim3((unsigned)(p.N * p.H)), dim3(128),
+                     (size_t)p.E * sizeof(float), st, a, p.route_mode == 1 ? d_route : nullptr);
+  if (p.route_mode == 0 && d_route) {
+    GemmArgs g{};
+    g.A = Xp; g.B = a.DPt; g.C = d_route;
+    g.M = p.dh; g.N = p.E; g.K = p.N;
+    g.a_ms = 1; g.a_ks = p.ldx; g.a_bs = p.dh;
+    g.b_ns = 1; g.b_ks = p.E; g.b_bs = (int64_t)p.N * p.E;
+    g.c_ms = p.E; g.c_bs = (int64_t)p.dh * p.E;
+    if ((rc = run_gemm<T>(g, p.H, st))) return rc;
+  }
+  return (int)hipGetLastError();
+}
+
+}  // namespace
+
+size_t unfused_workspace_bytes(const Problem& p, int dtype, bool backward) {
+  return make_layout(p, dtype == 1 ? 2 : 4, backward).total;
+}
+
+int launch_unfused(const Problem& p, int dtype, const void* X, const void* Wg, const void* Wu,
+                   const void* Wd, const void* route, void* Y, const void* dY, void* dX,
+                   void* dWg, void* dWu, void* dWd, void* d_route, void* ws, void* stream) {
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if ((int64_t)p.N * p.H * p.E > 0x7fffffffLL) return -1;  // one workgroup per (token, head, sub-network)
+  if (dtype == 1)
+    return run_unfused<uint16_t>(p, X, Wg, Wu, Wd, route, Y, dY, dX, dWg, dWu, dWd, d_route, ws, st);
+  return run_unfused<float>(p, X, Wg, Wu, Wd, route, Y, dY, dX, dWg, dWu, dWd, d_route, ws, st);
+}
+
 }  // namespace mhffn
