@@ -102,6 +102,11 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 256 MiB device copy (reference for the HBM byte "
                          "counters of a profiler run)")
+    ap.add_argument("--rotate-weights", type=int, default=-1,
+                    help="number of distinct weight copies to rotate over (default: 8 for the "
+                         "HBM-bound small-N forward, else 1)")
+    ap.add_argument("--no-unfused", dest="unfused", action="store_false",
+                    help="skip the unfused GPU baseline comparison")
     ap.add_argument("--forward-only", action="store_true",
                     help="time the forward alone (step = forward); for profiling")
     args = ap.parse_args()
@@ -136,11 +141,21 @@ def main():
     hip = HipEvents()
     K = args.steps
     ev = [hip.create(6) for _ in range(K)]   # per step: fwd start, fwd end/bwd start.. (4 bwd marks)
+    fwd_ws_bytes = mhffn.workspace_bytes(desc, mhffn.OP_FORWARD)
+    fwd_ws = torch.empty(max(fwd_ws_bytes, 256), dtype=torch.uint8, device="cuda")
+    # A weight-streaming (HBM-bound) shape must not be served from the 256 MB
+    # Infinity Cache: rotate over distinct copies of the weights (> 256 MB in total).
+    hbm_bound = args.forward_only and w.n_tokens <= 128
+    n_rot = args.rotate_weights if args.rotate_weights >= 0 else (8 if hbm_bound else 1)
+    wsets = [(Wg, Wu, Wd)] + [(Wg.clone(), Wu.clone(), Wd.clone()) for _ in range(max(n_rot, 1) - 1)]
+    counter = [0]
 
     def step(events=None):
+        Wg_, Wu_, Wd_ = wsets[counter[0] % len(wsets)]
+        counter[0] += 1
         if events is not None:
             hip.record(events[0], stream)
-        mhffn.forward(X, Wg, Wu, Wd, Wr, w.eps, out=Y)
+        mhffn.forward(X, Wg_, Wu_, Wd_, Wr, w.eps, out=Y, workspace=fwd_ws)
         if events is not None:
             hip.record(events[1], stream)
         if not args.forward_only:
@@ -181,6 +196,14 @@ def main():
                     "bwd_route": "bwd_route_*"}
 
     def roof(k):
+        if k == "fwd" and hbm_bound:
+            # compulsory bytes of one forward: weights + W_r + X + Y
+            nbytes = (3 * w.d_model * w.d_ff + w.d_model * w.n_sub + 2 * w.n_tokens * w.d_model) * 2
+            ach = nbytes / (avg[k] * 1e-3) / 1e9 if avg[k] > 0 else 0.0
+            return {"bound": "hbm", "kernel": kernel_names[k], "achieved": round(ach, 1),
+                    "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(ach / PEAK_HBM_GBS, 4),
+                    "traffic": None, "avg_ms": round(avg[k], 5), "algorithmic_bytes": nbytes,
+                    "weight_copies_rotated": len(wsets)}
         ach = units[k] * unit / (avg[k] * 1e-3) / 1e12 if avg[k] > 0 else 0.0
         return {"bound": "mfma", "kernel": kernel_names[k], "achieved": round(ach, 1),
                 "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(ach / PEAK_BF16_TFLOPS, 4),
@@ -210,13 +233,39 @@ def main():
         "roofline_fwd": roof("fwd"),
         "peak_activation_bytes": {
             "fused_forward": act_fused,
-            "fused_forward_workspace": mhffn.workspace_bytes(desc, mhffn.OP_FORWARD),
+            "fused_forward_workspace": fwd_ws_bytes,
             "fused_backward_workspace": ws_bytes,
             "unfused_forward_workspace": unfused_ws or None,
             "unfused_backward_workspace": unfused_ws_bwd or None,
             "intermediate_if_materialised": 3 * w.n_tokens * w.n_heads * w.d_ff * 2,
         },
     }
+    if args.unfused:
+        # the unfused GPU baseline on the same inputs (outside the timed region)
+        uws = torch.empty(unfused_ws_bwd, dtype=torch.uint8, device="cuda")
+        uout = {"Y": torch.empty_like(X), **{k: torch.empty_like(v) for k, v in grads.items()}}
+
+        def time_unfused(with_bwd, reps=3):
+            mhffn.reference_unfused(X, Wg, Wu, Wd, Wr, w.eps, dY=dY if with_bwd else None,
+                                    workspace=uws, out=uout)
+            e0, e1 = hip.create(2)
+            hip.record(e0, stream)
+            for _ in range(reps):
+                mhffn.reference_unfused(X, Wg, Wu, Wd, Wr, w.eps, dY=dY if with_bwd else None,
+                                        workspace=uws, out=uout)
+            hip.record(e1, stream)
+            torch.cuda.synchronize()
+            return hip.elapsed_ms(e0, e1) / reps
+
+        u_fwd = time_unfused(False)
+        u_all = time_unfused(True)
+        out["unfused_baseline"] = {
+            "forward_ms": round(u_fwd, 3), "forward_backward_ms": round(u_all, 3),
+            "fused_forward_speedup": round(u_fwd / avg["fwd"], 2) if avg["fwd"] else None,
+            "fused_step_speedup": None if args.forward_only else round(u_all / ms_per_step, 2),
+            "activation_bytes_ratio_forward": round((act_fused + unfused_ws) / act_fused, 1),
+        }
+        del uws, uout
     if not args.forward_only:
         out["roofline_bwd_tok"] = roof("bwd_tok")
         out["roofline_bwd_wgt"] = roof("bwd_wgt")

@@ -99,9 +99,14 @@ typedef struct {
 
 /* Bytes of caller-provided scratch needed by `op` (an mhffn_op) for `desc`.
  * Returns 0 for an invalid descriptor as well; validate with the entry point.
- * For MHFFN_OP_FORWARD this is 0: the fused forward touches nothing but its
- * inputs and Y, which is the "intermediate never reaches HBM" property of
- * eq:flash-ffn-loop stated as a number.  For the unfused ops it is the three
+ * For MHFFN_OP_FORWARD this is 0 whenever the token tiles alone fill the chip
+ * (n_tokens * n_heads >= 384 * 256): the fused forward then touches nothing but
+ * its inputs and Y, which is the "intermediate never reaches HBM" property of
+ * eq:flash-ffn-loop stated as a number.  For fewer tokens (decode, short
+ * prefill) the blocks of eq:flash-ffn-loop are shared out over several
+ * workgroups per token tile and their fp32 partial outputs, n_split * N *
+ * d_model * 4 bytes (a few output-sized buffers, never d_ff-sized ones), pass
+ * through the workspace.  For the unfused ops it is the three
  * materialised [N][H][d_ff] activations plus the [N][H][E] weights, i.e. the
  * O((L*H + d_model)*d_ff) footprint of the naive multi-head FFN. */
 size_t mhffn_workspace_bytes(const mhffn_desc* desc, int op);

@@ -79,7 +79,9 @@ size_t mhffn_workspace_bytes(const mhffn_desc* desc, int op) {
   Problem p;
   if (check_desc(desc, &p) != MHFFN_OK) return 0;
   switch (op) {
-    case MHFFN_OP_FORWARD: return 0;
+    case MHFFN_OP_FORWARD:
+      if (desc->dtype != MHFFN_BF16 || check_fused_shape(desc, p) != MHFFN_OK) return 0;
+      return mhffn::fwd_bf16_workspace_bytes(p);
     case MHFFN_OP_BACKWARD:
       if (check_fused_shape(desc, p) != MHFFN_OK) return 0;
       return mhffn::bwd_workspace_bytes(p, desc->dtype);
@@ -92,7 +94,6 @@ size_t mhffn_workspace_bytes(const mhffn_desc* desc, int op) {
 int mhffn_forward(const mhffn_desc* desc, const void* X, const void* W_gate, const void* W_up,
                   const void* W_down, const void* route, void* Y, void* workspace,
                   size_t workspace_bytes, void* hip_stream) {
-  (void)workspace; (void)workspace_bytes;  // the fused forward needs no scratch
   Problem p;
   int rc = check_desc(desc, &p);
   if (rc) return rc;
@@ -103,8 +104,14 @@ int mhffn_forward(const mhffn_desc* desc, const void* X, const void* W_gate, con
   rc = check_fused_shape(desc, p);
   if (rc) return rc;
   if (p.N == 0) return MHFFN_OK;
+  if (desc->dtype == MHFFN_BF16) {
+    // non-zero only for small N, where the intermediate dimension is split over workgroups
+    rc = check_workspace(mhffn::fwd_bf16_workspace_bytes(p), workspace, workspace_bytes);
+    if (rc) return rc;
+  }
   const int e = (desc->dtype == MHFFN_BF16)
-                    ? mhffn::launch_fwd_bf16(p, X, W_gate, W_up, W_down, route, Y, hip_stream)
+                    ? mhffn::launch_fwd_bf16(p, X, W_gate, W_up, W_down, route, Y, workspace,
+                                             hip_stream)
                     : mhffn::launch_fwd_f32(p, X, W_gate, W_up, W_down, route, Y, hip_stream);
   return e == 0 ? MHFFN_OK : MHFFN_ERR_LAUNCH;
 }

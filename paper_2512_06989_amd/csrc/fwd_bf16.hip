@@ -42,8 +42,10 @@ struct FwdArgs {
   const uint16_t* Wd;
   const void* route;
   uint16_t* Y;
+  float* P;     // [n_split][N][H*128] fp32 partial outputs (only when n_split > 1)
   int64_t N, ldx, ldy, n_tiles, n_items;
   int H, E, de, route_mode;
+  int n_split, tiles_per_split;
   float eps;
 };
 
@@ -61,8 +63,12 @@ __global__ __launch_bounds__(64 * NW) void fwd_bf16_kernel(FwdArgs a) {
   const int r = lane & 31, g = lane >> 5;
   const int64_t item = xcd_work_item(blockIdx.x, a.n_items);
   if (item >= a.n_items) return;  // whole workgroup leaves together
-  const int h = (int)(item / a.n_tiles);
-  const int64_t tile_tok0 = (item % a.n_tiles) * BM;
+  // item = (head * n_tiles + token tile) * n_split + split: the splits of one
+  // token tile sit next to each other and share the head's weights in L2
+  const int split = (int)(item % a.n_split);
+  const int64_t ht = item / a.n_split;
+  const int h = (int)(ht / a.n_tiles);
+  const int64_t tile_tok0 = (ht % a.n_tiles) * BM;
   const int wtok = wave * 32 * TB;  // first token of this wave inside the tile
   const int E = a.E;
 
@@ -144,7 +150,9 @@ __global__ __launch_bounds__(64 * NW) void fwd_bf16_kernel(FwdArgs a) {
 
   // ---- main loop over tiles of 32 neurons ----------------------------------
   const int tiles_per_sub = a.de / kBI;
-  const int T = E * tiles_per_sub;
+  const int T_all = E * tiles_per_sub;
+  const int t_begin = split * a.tiles_per_split;          // this workgroup's share of the
+  const int T = min(T_all, t_begin + a.tiles_per_split);   // intermediate dimension
   const size_t head_off = (size_t)h * E * a.de * kDh;
   const uint16_t* Kh = a.Wg + head_off;
   const uint16_t* Uh = a.Wu + head_off;
@@ -185,14 +193,14 @@ __global__ __launch_bounds__(64 * NW) void fwd_bf16_kernel(FwdArgs a) {
   const int li = lane & 15;
   const int v_off = 2 * kKBytes + (4 * g + (li >> 2)) * kVStride + (16 * ((lane >> 4) & 1) + 4 * (li & 3)) * 2;
 
-  gload(0);
-  lstore(0);
+  gload(t_begin);
+  lstore(t_begin & 1);
   __syncthreads();
   float rw[TB];
-  for (int t = 0; t < T; ++t) {
+  for (int t = t_begin; t < T; ++t) {
     const bool more = (t + 1 < T);
     if (more) gload(t + 1);
-    if (t % tiles_per_sub == 0) {
+    if (t % tiles_per_sub == 0 || t == t_begin) {
       const int e = t / tiles_per_sub;
 #pragma unroll
       for (int tb = 0; tb < TB; ++tb) rw[tb] = Rs[e * BM + wtok + 32 * tb + r];
@@ -252,6 +260,25 @@ __global__ __launch_bounds__(64 * NW) void fwd_bf16_kernel(FwdArgs a) {
     __syncthreads();
   }
 
+  // ---- split runs leave an fp32 partial; fwd_bf16_reduce_kernel sums them ---
+  if (a.n_split > 1) {
+#pragma unroll
+    for (int tb = 0; tb < TB; ++tb) {
+      const int64_t tok = tile_tok0 + wtok + 32 * tb + r;
+      if (tok < a.N) {
+        float* dst = a.P + (((size_t)split * a.N + tok) * a.H + h) * kDh + 4 * g;
+#pragma unroll
+        for (int jb = 0; jb < 4; ++jb)
+#pragma unroll
+          for (int vq = 0; vq < 4; ++vq) {
+            f32x4 o = {O[tb][jb][4 * vq], O[tb][jb][4 * vq + 1], O[tb][jb][4 * vq + 2],
+                       O[tb][jb][4 * vq + 3]};
+            *reinterpret_cast<f32x4*>(dst + 32 * jb + 8 * vq) = o;
+          }
+      }
+    }
+    return;
+  }
   // ---- store Y (concat_H: head h owns columns h*d_h ..) --------------------
 #pragma unroll
   for (int tb = 0; tb < TB; ++tb) {
@@ -272,11 +299,44 @@ __global__ __launch_bounds__(64 * NW) void fwd_bf16_kernel(FwdArgs a) {
   }
 }
 
+// Y[tok][col] = bf16(sum_s P[s][tok][col]), fixed order
+__global__ void fwd_bf16_reduce_kernel(FwdArgs a) {
+  const int64_t dm = (int64_t)a.H * kDh;
+  const int64_t idx = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
+  if (idx >= a.N * dm) return;
+  f32x4 sum = {0.f, 0.f, 0.f, 0.f};
+  for (int s = 0; s < a.n_split; ++s)
+    sum += *reinterpret_cast<const f32x4*>(a.P + (size_t)s * a.N * dm + idx);
+  const int64_t tok = idx / dm, col = idx % dm;
+  u32x2 pk;
+  pk[0] = pack_bf16(sum[0], sum[1]);
+  pk[1] = pack_bf16(sum[2], sum[3]);
+  *reinterpret_cast<u32x2*>(a.Y + tok * a.ldy + col) = pk;
+}
+
+// How the intermediate dimension is shared out when the token tiles alone
+// cannot fill the chip (decode / short prefill): aim for >= 2 workgroups per CU.
+struct SplitPlan { int bm, n_split, tiles_per_split; };
+SplitPlan plan_split(const Problem& p) {
+  SplitPlan s;
+  s.bm = (p.N <= 128) ? 64 : 256;
+  const int64_t base = ((p.N + s.bm - 1) / s.bm) * p.H;
+  const int T = p.E * (p.de / kBI);
+  int want = 1;
+  if (base < 384) want = (int)((512 + base - 1) / base);
+  if (want > T / 2) want = T / 2 > 0 ? T / 2 : 1;   // at least two tiles per split
+  s.tiles_per_split = (T + want - 1) / want;
+  s.n_split = (T + s.tiles_per_split - 1) / s.tiles_per_split;
+  return s;
+}
+
 template <int TB, int NW>
-int launch_variant(const Problem& p, FwdArgs a, hipStream_t stream) {
+int launch_variant(const Problem& p, FwdArgs a, const SplitPlan& sp, hipStream_t stream) {
   constexpr int BM = 32 * TB * NW;
   a.n_tiles = (p.N + BM - 1) / BM;
-  a.n_items = a.n_tiles * p.H;
+  a.n_split = sp.n_split;
+  a.tiles_per_split = sp.tiles_per_split;
+  a.n_items = a.n_tiles * p.H * sp.n_split;
   const size_t lds = (size_t)kStages * kStageBytes + (size_t)p.E * BM * sizeof(float);
   static bool attr_set = false;
   if (!attr_set) {
@@ -288,13 +348,24 @@ int launch_variant(const Problem& p, FwdArgs a, hipStream_t stream) {
   }
   const dim3 grid((unsigned)xcd_grid_size(a.n_items));
   hipLaunchKernelGGL((fwd_bf16_kernel<TB, NW>), grid, dim3(64 * NW), lds, stream, a);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess || sp.n_split == 1) return (int)e;
+  const int64_t n4 = p.N * p.H * kDh / 4;
+  hipLaunchKernelGGL(fwd_bf16_reduce_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0,
+                     stream, a);
   return (int)hipGetLastError();
 }
 
 }  // namespace
 
+size_t fwd_bf16_workspace_bytes(const Problem& p) {
+  if (p.N == 0) return 0;
+  const SplitPlan sp = plan_split(p);
+  return sp.n_split > 1 ? (size_t)sp.n_split * p.N * p.H * kDh * sizeof(float) : 0;
+}
+
 int launch_fwd_bf16(const Problem& p, const void* X, const void* Wg, const void* Wu,
-                    const void* Wd, const void* route, void* Y, void* stream) {
+                    const void* Wd, const void* route, void* Y, void* ws, void* stream) {
   FwdArgs a;
   a.X = static_cast<const uint16_t*>(X);
   a.Wg = static_cast<const uint16_t*>(Wg);
@@ -302,12 +373,16 @@ int launch_fwd_bf16(const Problem& p, const void* X, const void* Wg, const void*
   a.Wd = static_cast<const uint16_t*>(Wd);
   a.route = route;
   a.Y = static_cast<uint16_t*>(Y);
+  a.P = static_cast<float*>(ws);
   a.N = p.N; a.ldx = p.ldx; a.ldy = p.ldy;
   a.H = p.H; a.E = p.E; a.de = p.de; a.route_mode = p.route_mode; a.eps = p.eps;
-  a.n_tiles = 0; a.n_items = 0;
+  a.n_tiles = 0; a.n_items = 0; a.n_split = 1; a.tiles_per_split = 0;
+  const SplitPlan sp = plan_split(p);
+  hipStream_t st = static_cast<hipStream_t>(stream);
   // 8 waves x 32 tokens (two waves per SIMD) measured 25% faster than 4 waves x
   // 64 tokens at the 1.3B shape: the second wave hides LDS and barrier latency.
-  return launch_variant<1, 8>(p, a, static_cast<hipStream_t>(stream));
+  if (sp.bm == 64) return launch_variant<1, 2>(p, a, sp, st);
+  return launch_variant<1, 8>(p, a, sp, st);
 }
 
 }  // namespace mhffn

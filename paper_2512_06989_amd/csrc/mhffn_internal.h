@@ -20,8 +20,11 @@ struct Problem {
 // ---- fused forward ---------------------------------------------------------
 // bf16, d_h = 128, d_e % 32 == 0, E <= kFwdBf16MaxSub.
 constexpr int kFwdBf16MaxSub = 96;
+// Scratch of the bf16 forward: 0 unless the token tiles cannot fill the chip and the
+// intermediate dimension is split over workgroups (fp32 partial outputs).
+size_t fwd_bf16_workspace_bytes(const Problem& p);
 int launch_fwd_bf16(const Problem& p, const void* X, const void* Wg, const void* Wu,
-                    const void* Wd, const void* route, void* Y, void* stream);
+                    const void* Wd, const void* route, void* Y, void* ws, void* stream);
 // fp32, d_h % 4 == 0, d_h <= 256.
 int launch_fwd_f32(const Problem& p, const void* X, const void* Wg, const void* Wu,
                    const void* Wd, const void* route, void* Y, void* stream);

@@ -115,12 +115,14 @@ def _workspace(desc, op, device, workspace):
 
 
 def forward(X, W_gate, W_up, W_down, route, eps=1e-6, route_mode=ROUTE_PARAMS, out=None,
-            stream=None):
-    """Fused forward.  Returns Y [N, H*d_h] (dtype of X)."""
+            stream=None, workspace=None):
+    """Fused forward.  Returns Y [N, H*d_h] (dtype of X).  Scratch is needed only
+    for small token counts (see mhffn_workspace_bytes); allocated here if not given."""
     Y = torch.empty_like(X) if out is None else out
     d = make_desc(X, W_gate, route_mode, eps, Y)
+    workspace, have = _workspace(d, OP_FORWARD, X.device, workspace)
     rc = load().mhffn_forward(ctypes.byref(d), _p(X), _p(W_gate), _p(W_up), _p(W_down),
-                              _p(route), _p(Y), None, 0, _stream(stream))
+                              _p(route), _p(Y), _p(workspace), have, _stream(stream))
     if rc != OK:
         raise MhffnError(rc, "mhffn_forward")
     return Y
