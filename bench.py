@@ -195,6 +195,13 @@ def main():
     kernel_names = {"fwd": "fwd_bf16_kernel", "bwd_tok": "bwd_tok_kernel", "bwd_wgt": "bwd_wgt_kernel",
                     "bwd_route": "bwd_route_*"}
 
+    # HBM bytes per launch measured with rocprofv3 (FETCH_SIZE + WRITE_SIZE, each scaled by
+    # what the counter reads for a 256 MiB copy); from profiles/mhffn_fwd_bwd_1p3b.md and
+    # profiles/mhffn_fwd_sweep_1p3b.md.  Only valid for the workload they were taken on.
+    measured_traffic = {}
+    if w.name == "1p3b_fwdbwd" and not args.forward_only:
+        measured_traffic = {"fwd": 273.6e6, "bwd_tok": 496.6e6, "bwd_wgt": 453.5e6}
+
     def roof(k):
         if k == "fwd" and hbm_bound:
             # compulsory bytes of one forward: weights + W_r + X + Y
@@ -207,7 +214,8 @@ def main():
         ach = units[k] * unit / (avg[k] * 1e-3) / 1e12 if avg[k] > 0 else 0.0
         return {"bound": "mfma", "kernel": kernel_names[k], "achieved": round(ach, 1),
                 "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(ach / PEAK_BF16_TFLOPS, 4),
-                "traffic": None, "avg_ms": round(avg[k], 4), "algorithmic_units": units[k]}
+                "traffic": measured_traffic.get(k), "avg_ms": round(avg[k], 4),
+                "algorithmic_units": units[k]}
 
     dominant = max(avg, key=lambda k: avg[k])
     step_units = 3.0 if args.forward_only else 11.0

@@ -17,7 +17,7 @@
 // The gating weights of eq:routing are computed in the same kernel (P^T = W_r^T
 // q^T on the MFMA, sigmoid and the sum over sub-networks in fp32, the two
 // half-waves of a token combined with one cross-lane exchange) and parked in
-// LDS as R[e][token]; nothing but X, the weights and Y touches device memory.
+// LDS as 1/R[e][token]; nothing but X, the weights and Y touches device memory.
 #include "mhffn_device.h"
 #include "mhffn_internal.h"
 
@@ -34,6 +34,19 @@ constexpr int kKBytes = kBI * kKUStride;
 constexpr int kVBytes = kBI * kVStride;
 constexpr int kStageBytes = 2 * kKBytes + kVBytes;  // 27648
 constexpr int kStages = 2;
+
+// LDS keeps 1/r (clamped, so r = 0 stays finite): the weight then rides along in the
+// sigmoid's own reciprocal and costs no multiply of its own,
+//   SiLU(m) n r = m n r / (1 + 2^(-m log2 e)) = m n * rcp((1 + t) / r),   (1 + t)/r = fma(t, 1/r, 1/r)
+// four full-rate and two transcendental VALU instructions per element.
+__device__ __forceinline__ float inv_weight(float r) {
+  const float v = 1.0f / r;
+  return fminf(fmaxf(v, -1e30f), 1e30f);
+}
+__device__ __forceinline__ float gated_act(float m, float n, float rinv) {
+  const float t = __builtin_amdgcn_exp2f(-MHFFN_LOG2E * m);
+  return (m * n) * __builtin_amdgcn_rcpf(__builtin_fmaf(t, rinv, rinv));
+}
 
 struct FwdArgs {
   const uint16_t* X;
@@ -125,7 +138,7 @@ __global__ __launch_bounds__(64 * NW) void fwd_bf16_kernel(FwdArgs a) {
             if (pass == 0) {
               zsum[tb] += s;
             } else if (e < E) {
-              Rs[e * BM + wtok + 32 * tb + r] = s * inv[tb];
+              Rs[e * BM + wtok + 32 * tb + r] = inv_weight(s * inv[tb]);
             }
           }
         }
@@ -143,7 +156,7 @@ __global__ __launch_bounds__(64 * NW) void fwd_bf16_kernel(FwdArgs a) {
     for (int idx = tid; idx < BM * E; idx += THREADS) {
       const int tl = idx / E, e = idx - tl * E;
       const int64_t tok = tile_tok0 + tl;
-      Rs[e * BM + tl] = (tok < a.N) ? R[((size_t)tok * a.H + h) * E + e] : 0.f;
+      Rs[e * BM + tl] = inv_weight((tok < a.N) ? R[((size_t)tok * a.H + h) * E + e] : 0.f);
     }
   }
   __syncthreads();  // R complete; the staging area is free again
@@ -232,8 +245,8 @@ __global__ __launch_bounds__(64 * NW) void fwd_bf16_kernel(FwdArgs a) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
           const float m0 = accM[tb][8 * t2 + 2 * i], m1 = accM[tb][8 * t2 + 2 * i + 1];
-          const float a0 = m0 * accN[tb][8 * t2 + 2 * i] * rw[tb] * sigmoid_fast(m0);
-          const float a1 = m1 * accN[tb][8 * t2 + 2 * i + 1] * rw[tb] * sigmoid_fast(m1);
+          const float a0 = gated_act(m0, accN[tb][8 * t2 + 2 * i], rw[tb]);
+          const float a1 = gated_act(m1, accN[tb][8 * t2 + 2 * i + 1], rw[tb]);
           pk[i] = pack_bf16(a0, a1);
         }
         bfrag[tb][t2] = __builtin_bit_cast(bf16x8, pk);
