@@ -28,7 +28,9 @@ _lib = None
 def load():
     global _lib
     if _lib is None:
-        path = _build.build(force=False)
+        # MHFFN_ORACLE_LIB lets the mutation test point the pins at a deliberately
+        # broken build of this same source; never set otherwise
+        path = os.environ.get("MHFFN_ORACLE_LIB") or _build.build(force=False)
         lib = ctypes.CDLL(path)
         dp = ctypes.c_void_p
         lib.mhffn_oracle_forward_f64.argtypes = [ctypes.POINTER(_Desc)] + [dp] * 7

@@ -74,7 +74,53 @@ def test_status_strings():
     assert len(seen) == 7 and mhffn.status_string(99) == "unknown status"
 
 
-def test_forward_needs_no_workspace():
-    for name in ("dtype",):
-        assert mhffn.workspace_bytes(desc(n_tokens=16384, n_heads=16, n_sub=44), mhffn.OP_FORWARD) == 0
+def test_forward_needs_no_workspace_when_token_tiles_fill_the_chip():
+    for n_heads, n_sub in ((6, 16), (8, 22), (16, 44)):
+        d = desc(n_tokens=16384, n_heads=n_heads, n_sub=n_sub)
+        assert mhffn.workspace_bytes(d, mhffn.OP_FORWARD) == 0
+    assert mhffn.workspace_bytes(desc(n_tokens=32768, n_heads=16, n_sub=44), mhffn.OP_FORWARD) == 0
     assert mhffn.workspace_bytes(desc(n_heads=0), mhffn.OP_FORWARD) == 0
+
+
+def test_small_token_counts_split_the_intermediate_dimension():
+    """Decode-sized inputs: fp32 partial outputs, a few times the output, never d_ff-sized."""
+    for n in (1, 64, 1024):
+        d = desc(n_tokens=n, n_heads=16, n_sub=44)
+        ws = mhffn.workspace_bytes(d, mhffn.OP_FORWARD)
+        out_f32 = n * 16 * 128 * 4
+        assert ws > 0 and ws % out_f32 == 0
+        assert ws // out_f32 <= 88                       # at most one split per two tiles
+        assert ws < n * 16 * 44 * 128 * 2 * 3            # far below the materialised intermediate
+    # the fused forward refuses a missing workspace before launching anything
+    rc = mhffn.load().mhffn_forward(ctypes.byref(desc(n_tokens=64, n_heads=16, n_sub=44)),
+                                    *([FAKE] * 6), None, 0, None)
+    assert rc == 5
+
+
+def test_backward_and_unfused_workspace_sizes():
+    d = desc(n_tokens=16384, n_heads=16, n_sub=44)
+    inter = 16384 * 16 * 44 * 128 * 2
+    bwd = mhffn.workspace_bytes(d, mhffn.OP_BACKWARD)
+    assert 2 * 16384 * 16 * 44 * 4 <= bwd < inter // 16   # R and dp, not the intermediate
+    assert mhffn.workspace_bytes(d, mhffn.OP_UNFUSED_FORWARD) >= 3 * inter
+    assert mhffn.workspace_bytes(d, mhffn.OP_UNFUSED_BACKWARD) >= 4 * inter
+    assert mhffn.workspace_bytes(d, 99) == 0
+
+
+def test_backward_rejects_bad_arguments():
+    lib = mhffn.load()
+    d = desc(n_tokens=256)
+    args = [FAKE] * 11
+    assert lib.mhffn_backward(ctypes.byref(d), *args, None, 0, None) == 5      # no workspace
+    assert lib.mhffn_backward(ctypes.byref(desc(dtype=mhffn.F32)), *args, FAKE, 1 << 30, None) == 3
+    bad = list(args)
+    bad[5] = None                                                               # dY missing
+    assert lib.mhffn_backward(ctypes.byref(d), *bad, FAKE, 1 << 30, None) == 1
+    assert lib.mhffn_backward_phases(ctypes.byref(d), *args, FAKE, 1 << 30, None, None, 3) == 1
+
+
+def test_unfused_rejects_bad_arguments():
+    lib = mhffn.load()
+    args = [FAKE] * 12
+    assert lib.mhffn_reference_unfused(ctypes.byref(desc()), *args, None, 0, None) == 5
+    assert lib.mhffn_reference_unfused(ctypes.byref(desc(d_head=12)), *args, FAKE, 1 << 40, None) == 3
