@@ -43,10 +43,7 @@ __device__ __forceinline__ float inv_weight(float r) {
   const float v = 1.0f / r;
   return fminf(fmaxf(v, -1e30f), 1e30f);
 }
-__device__ __forceinline__ float gated_act(float m, float n, float rinv) {
-  const float t = __builtin_amdgcn_exp2f(-MHFFN_LOG2E * m);
-  return (m * n) * __builtin_amdgcn_rcpf(__builtin_fmaf(t, rinv, rinv));
-}
+#define MHFFN_SB() __builtin_amdgcn_sched_barrier(0)
 
 struct FwdArgs {
   const uint16_t* X;
@@ -241,12 +238,21 @@ __global__ __launch_bounds__(64 * NW) void fwd_bf16_kernel(FwdArgs a) {
     for (int tb = 0; tb < TB; ++tb) {
 #pragma unroll
       for (int t2 = 0; t2 < 2; ++t2) {
+        // eight elements at a time, each step for all eight before the next step:
+        // dependent VALU instructions (exp -> fma -> rcp -> mul) end up eight issue
+        // slots apart instead of back to back
+        float t[8], s[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) t[i] = __builtin_amdgcn_exp2f(-MHFFN_LOG2E * accM[tb][8 * t2 + i]);
+        MHFFN_SB();
+#pragma unroll
+        for (int i = 0; i < 8; ++i) s[i] = __builtin_amdgcn_rcpf(__builtin_fmaf(t[i], rw[tb], rw[tb]));
+        MHFFN_SB();
         u32x4 pk;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-          const float m0 = accM[tb][8 * t2 + 2 * i], m1 = accM[tb][8 * t2 + 2 * i + 1];
-          const float a0 = gated_act(m0, accN[tb][8 * t2 + 2 * i], rw[tb]);
-          const float a1 = gated_act(m1, accN[tb][8 * t2 + 2 * i + 1], rw[tb]);
+          const float a0 = (accM[tb][8 * t2 + 2 * i] * accN[tb][8 * t2 + 2 * i]) * s[2 * i];
+          const float a1 = (accM[tb][8 * t2 + 2 * i + 1] * accN[tb][8 * t2 + 2 * i + 1]) * s[2 * i + 1];
           pk[i] = pack_bf16(a0, a1);
         }
         bfrag[tb][t2] = __builtin_bit_cast(bf16x8, pk);
