@@ -31,6 +31,8 @@
 namespace mhffn {
 namespace {
 
+#define MHFFN_SB() __builtin_amdgcn_sched_barrier(0)
+
 constexpr int kDh = 128;
 constexpr int kTileBytes = 32 * kDh * 2;  // 8 KB
 
@@ -423,6 +425,8 @@ __global__ __launch_bounds__(kWgtThreads) void bwd_wgt_kernel(BwdArgs a) {
   const size_t row0 = (size_t)h * nblk * 32 + (size_t)blk_c * 32;  // first neuron row of this wave
 
   // resident weight operands: lane (neuron r, half g) holds columns 16ks + 8g ..
+  // (re-reading them from a wave-private LDS copy every step instead was measured
+  // 17 % slower: the LDS pipe is the scarcer resource)
   bf16x8 Kf[8], Uf[8], Vf[8];
   {
     const size_t off = (row0 + r) * kDh + 8 * g;
@@ -490,59 +494,100 @@ __global__ __launch_bounds__(kWgtThreads) void bwd_wgt_kernel(BwdArgs a) {
     const unsigned char* yt = st + kTileBytes;
     const float* rt = reinterpret_cast<const float*>(st + 2 * kTileBytes) + wave * 32;
 
-    // M[tok][c], N[tok][c], dA[tok][c]: lane = neuron column, registers = token rows
-    f32x16 accM = {0}, accN = {0}, accA = {0};
+    // One wave per SIMD: nothing but this wave's own instruction stream can keep the
+    // MFMA pipe and the VALU busy at the same time, so the step is written as an
+    // explicit interleave (scheduling barriers pin it):
+    //   1. M and N chains (16 MFMA)
+    //   2. dA chain (8 MFMA)            || everything that needs only m, n, r   (12 VALU / element)
+    //   3. gradient MFMAs of tokens 0-15 || dn, dm, rounding of tokens 16-31
+    //   4. gradient MFMAs of tokens 16-31
+    // M[tok][c], N[tok][c], dA[tok][c]: lane = neuron column, registers = token rows;
+    // registers 8*t2 + 4*hi + x hold tokens 16*t2 + 8*hi + 4g + x.
+    f32x4 rv[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) rv[i] = *reinterpret_cast<const f32x4*>(rt + 8 * i + 4 * g);
+    bf16x8 oa[4], ob[4];
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) oa[ks] = *reinterpret_cast<const bf16x8*>(qt + tile_off(r, 2 * ks + g));
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) ob[ks] = *reinterpret_cast<const bf16x8*>(qt + tile_off(r, 2 * (ks + 4) + g));
+    MHFFN_SB();
+    f32x16 accM, accN, accA;
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      if (ks == 0) { accM = mfma32(oa[0], Kf[0], f32x16{0}); accN = mfma32(oa[0], Uf[0], f32x16{0}); }
+      else { accM = mfma32(oa[ks], Kf[ks], accM); accN = mfma32(oa[ks], Uf[ks], accN); }
+    }
+    MHFFN_SB();
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) oa[ks] = *reinterpret_cast<const bf16x8*>(yt + tile_off(r, 2 * ks + g));
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) { accM = mfma32(ob[ks], Kf[ks + 4], accM); accN = mfma32(ob[ks], Uf[ks + 4], accN); }
+    MHFFN_SB();
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) ob[ks] = *reinterpret_cast<const bf16x8*>(yt + tile_off(r, 2 * (ks + 4) + g));
+    // transposed operands of tokens 0-15, fetched under the arithmetic below
+    bf16x8 yT[4], qT[4];
+#pragma unroll
+    for (int jb = 0; jb < 4; ++jb) {
+      yT[jb] = tile_read_tr(yt, 4 * g, 32 * jb, lane);
+      qT[jb] = tile_read_tr(qt, 4 * g, 32 * jb, lane);
+    }
+    MHFFN_SB();
+    float Pw[16], Qw[16];   // r silu(m)  and  r n silu'(m)
+    u32x4 pa[2];
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) {
-      const int off = tile_off(r, 2 * ks + g);
-      const bf16x8 aq = *reinterpret_cast<const bf16x8*>(qt + off);
-      const bf16x8 ay = *reinterpret_cast<const bf16x8*>(yt + off);
-      accM = mfma32(aq, Kf[ks], accM);
-      accN = mfma32(aq, Uf[ks], accN);
-      accA = mfma32(ay, Vf[ks], accA);
-    }
-    bf16x8 agf[2], dmf[2], dnf[2];
+      if (ks == 0) accA = mfma32(oa[0], Vf[0], f32x16{0});
+      else accA = mfma32(ks < 4 ? oa[ks] : ob[ks - 4], Vf[ks], accA);
+      float av[2];
 #pragma unroll
-    for (int t2 = 0; t2 < 2; ++t2) {
-      // registers 8*t2 + 4*i' + x hold tokens 16*t2 + 8*i' + 4g + x
-      const f32x4 r0 = *reinterpret_cast<const f32x4*>(rt + 16 * t2 + 4 * g);
-      const f32x4 r1 = *reinterpret_cast<const f32x4*>(rt + 16 * t2 + 8 + 4 * g);
-      u32x4 pa, pm, pn;
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        float av[2], dmv[2], dnv[2];
-#pragma unroll
-        for (int u = 0; u < 2; ++u) {
-          const int s = 2 * i + u;  // slot 0..7
-          const int v = 8 * t2 + s;
-          const float rwv = (s < 4) ? r0[s & 3] : r1[s & 3];
-          const float m = accM[v], n = accN[v], da = accA[v];
-          const float sg = sigmoid_fast(m);
-          const float silu = m * sg;
-          const float rda = rwv * da;
-          av[u] = rwv * silu * n;
-          dnv[u] = rda * silu;
-          dmv[u] = rda * n * fmaf(silu, 1.0f - sg, sg);
-        }
-        pa[i] = pack_bf16(av[0], av[1]);
-        pm[i] = pack_bf16(dmv[0], dmv[1]);
-        pn[i] = pack_bf16(dnv[0], dnv[1]);
+      for (int u = 0; u < 2; ++u) {
+        const int v = 2 * ks + u;
+        const float rwv = rv[v >> 2][v & 3];
+        const float m = accM[v], n = accN[v];
+        const float t = __builtin_amdgcn_exp2f(-MHFFN_LOG2E * m);
+        const float sg = __builtin_amdgcn_rcpf(1.0f + t);
+        const float sw = rwv * sg;
+        const float x = (1.0f + m) - m * sg;   // silu'(m) = sg (1 + m - silu(m))
+        Pw[v] = m * sw;
+        Qw[v] = (n * sw) * x;
+        av[u] = Pw[v] * n;
       }
-      agf[t2] = __builtin_bit_cast(bf16x8, pa);
-      dmf[t2] = __builtin_bit_cast(bf16x8, pm);
-      dnf[t2] = __builtin_bit_cast(bf16x8, pn);
+      pa[ks >> 2][ks & 3] = pack_bf16(av[0], av[1]);
+      MHFFN_SB();
     }
+    // tokens 0-15: dn = P da, dm = Q da
+    u32x4 pm, pn;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      pm[i] = pack_bf16(Qw[2 * i] * accA[2 * i], Qw[2 * i + 1] * accA[2 * i + 1]);
+      pn[i] = pack_bf16(Pw[2 * i] * accA[2 * i], Pw[2 * i + 1] * accA[2 * i + 1]);
+    }
+    bf16x8 agf = __builtin_bit_cast(bf16x8, pa[0]);
+    bf16x8 dmf = __builtin_bit_cast(bf16x8, pm), dnf = __builtin_bit_cast(bf16x8, pn);
+    MHFFN_SB();
     // dV^T[j][c] += dY^T A_g ; dK^T[j][c] += q^T dM ; dU^T[j][c] += q^T dN  (contraction over tokens)
+    u32x4 pm1, pn1;
 #pragma unroll
-    for (int t2 = 0; t2 < 2; ++t2) {
+    for (int jb = 0; jb < 4; ++jb) {
+      dV[jb] = mfma32(yT[jb], agf, dV[jb]);
+      dK[jb] = mfma32(qT[jb], dmf, dK[jb]);
+      dU[jb] = mfma32(qT[jb], dnf, dU[jb]);
+      yT[jb] = tile_read_tr(yt, 16 + 4 * g, 32 * jb, lane);   // operands of tokens 16-31
+      qT[jb] = tile_read_tr(qt, 16 + 4 * g, 32 * jb, lane);
+      pm1[jb] = pack_bf16(Qw[8 + 2 * jb] * accA[8 + 2 * jb], Qw[9 + 2 * jb] * accA[9 + 2 * jb]);
+      pn1[jb] = pack_bf16(Pw[8 + 2 * jb] * accA[8 + 2 * jb], Pw[9 + 2 * jb] * accA[9 + 2 * jb]);
+      MHFFN_SB();
+    }
+    agf = __builtin_bit_cast(bf16x8, pa[1]);
+    dmf = __builtin_bit_cast(bf16x8, pm1);
+    dnf = __builtin_bit_cast(bf16x8, pn1);
 #pragma unroll
-      for (int jb = 0; jb < 4; ++jb) {
-        const bf16x8 yT = tile_read_tr(yt, 16 * t2 + 4 * g, 32 * jb, lane);
-        const bf16x8 qT = tile_read_tr(qt, 16 * t2 + 4 * g, 32 * jb, lane);
-        dV[jb] = mfma32(yT, agf[t2], dV[jb]);
-        dK[jb] = mfma32(qT, dmf[t2], dK[jb]);
-        dU[jb] = mfma32(qT, dnf[t2], dU[jb]);
-      }
+    for (int jb = 0; jb < 4; ++jb) {
+      dV[jb] = mfma32(yT[jb], agf, dV[jb]);
+      dK[jb] = mfma32(qT[jb], dmf, dK[jb]);
+      dU[jb] = mfma32(qT[jb], dnf, dU[jb]);
     }
     if (more) lstore((b + 1) & 1);
     __syncthreads();
