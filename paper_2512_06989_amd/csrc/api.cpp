@@ -97,7 +97,11 @@ int mhffn_forward(const mhffn_desc* desc, const void* X, const void* W_gate, con
   Problem p;
   int rc = check_desc(desc, &p);
   if (rc) return rc;
-  if (!X || !W_gate || !W_up || !W_down || !route || !Y) return MHFFN_ERR_NULL;
+  // an empty batch has no rows: X and Y (and R, in weights mode) may then be NULL
+  const bool empty = (p.N == 0);
+  if (!W_gate || !W_up || !W_down) return MHFFN_ERR_NULL;
+  if (!empty && (!X || !Y || !route)) return MHFFN_ERR_NULL;
+  if (!route && p.route_mode == MHFFN_ROUTE_PARAMS) return MHFFN_ERR_NULL;
   if (!aligned16(X) || !aligned16(W_gate) || !aligned16(W_up) || !aligned16(W_down) ||
       !aligned16(route) || !aligned16(Y))
     return MHFFN_ERR_ALIGN;
@@ -133,7 +137,10 @@ int mhffn_backward_phases(const mhffn_desc* desc, const void* X, const void* W_g
   Problem p;
   int rc = check_desc(desc, &p);
   if (rc) return rc;
-  if (!X || !W_gate || !W_up || !W_down || !route || !dY) return MHFFN_ERR_NULL;
+  const bool empty = (p.N == 0);  // no rows: X, dY, dX (and R) may be NULL
+  if (!W_gate || !W_up || !W_down) return MHFFN_ERR_NULL;
+  if (!empty && (!X || !dY || !route)) return MHFFN_ERR_NULL;
+  if (!route && p.route_mode == MHFFN_ROUTE_PARAMS) return MHFFN_ERR_NULL;
   const void* ptrs[] = {X, W_gate, W_up, W_down, route, dY, dX, dW_gate, dW_up, dW_down, d_route};
   for (const void* q : ptrs)
     if (!aligned16(q)) return MHFFN_ERR_ALIGN;
@@ -156,7 +163,10 @@ int mhffn_reference_unfused(const mhffn_desc* desc, const void* X, const void* W
   Problem p;
   int rc = check_desc(desc, &p);
   if (rc) return rc;
-  if (!X || !W_gate || !W_up || !W_down || !route || !Y) return MHFFN_ERR_NULL;
+  const bool empty = (p.N == 0);
+  if (!W_gate || !W_up || !W_down) return MHFFN_ERR_NULL;
+  if (!empty && (!X || !Y || !route)) return MHFFN_ERR_NULL;
+  if (!route && p.route_mode == MHFFN_ROUTE_PARAMS) return MHFFN_ERR_NULL;
   const void* ptrs[] = {X, W_gate, W_up, W_down, route, Y, dY, dX, dW_gate, dW_up, dW_down, d_route};
   for (const void* q : ptrs)
     if (!aligned16(q)) return MHFFN_ERR_ALIGN;

@@ -737,7 +737,7 @@ size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 }  // namespace
 
 size_t bwd_workspace_bytes(const Problem& p, int dtype) {
-  if (dtype != 1) return 0;
+  if (dtype != 1 || p.N == 0) return 0;   // an empty batch only zero-fills the weight gradients
   const size_t nhe = align256((size_t)p.N * p.H * p.E * sizeof(float));
   const size_t wr = align256((size_t)p.H * kRouteParts * kDh * p.E * sizeof(float));
   return 2 * nhe + wr;

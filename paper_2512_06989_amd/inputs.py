@@ -53,8 +53,16 @@ WORKLOADS = {
     "1p3b_fwdbwd": Workload("1p3b_fwdbwd", 16384, 16, 128, 44, 128, "bf16",
                             w_std=0.02 / math.sqrt(24.0), backward=True),
     "1p3b_sweep": Workload("1p3b_sweep", 1024, 16, 128, 44, 128, "bf16", route_scale=8.0),
+    # The paper's own shapes (model table: E sub-networks of width intermediate/E; sub-network
+    # width 8/3 d_h rounded up to a multiple of 64 = 384 for d_h = 128) and the shape of its
+    # efficiency benchmark (batch 8 x sequence L, H = 16, E = 22, d_e = 384; tokens = 8 L).
+    "paper_128m": Workload("paper_128m", 16384, 6, 128, 8, 256, "bf16", backward=True),
+    "paper_370m": Workload("paper_370m", 16384, 8, 128, 7, 384, "bf16", backward=True),
+    "paper_1p3b": Workload("paper_1p3b", 16384, 16, 128, 15, 384, "bf16", backward=True),
+    "paper_bench": Workload("paper_bench", 8 * 1920, 16, 128, 22, 384, "bf16", backward=True),
 }
 SWEEP_TOKENS = (64, 1024, 32768)
+PAPER_BENCH_SEQ_LENS = (192, 384, 768, 1536, 1920, 2880, 4032, 8064, 16128)   # batch 8 each
 
 
 def _normal(seed, stream, shape, std):
