@@ -115,8 +115,9 @@ __device__ __forceinline__ void stage_tile(T* lds, const T* src, int64_t rs, int
 template <typename T>
 __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g) {
   constexpr int LD = kGK + Frag<T>::kPad;
-  __shared__ __attribute__((aligned(16))) T As[kGM * LD];
-  __shared__ __attribute__((aligned(16))) T Bs[kGN * LD];
+  __shared__ __attribute__((aligned(16))) T tiles[(kGM + kGN) * LD];
+  T* As = tiles;
+  T* Bs = tiles + kGM * LD;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r = lane & 31, gh = lane >> 5;
   const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
@@ -167,6 +168,39 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g) {
     }
   }
   T* C = static_cast<T*>(g.C) + b * g.c_bs;
+  if constexpr (sizeof(T) == 2) {
+    // bf16 output: gather the 64x128 halves of the tile in LDS (the operand tiles are
+    // dead by now) and write full 16-byte row segments instead of 2-byte scatters
+    const bool vec_ok = !g.accumulate && (g.c_ms % 8) == 0 && n0 + kGN <= g.N &&
+                        (reinterpret_cast<uintptr_t>(C) & 15u) == 0;
+    if (vec_ok) {
+      constexpr int CLD = kGN + 8;                    // row stride in elements
+      static_assert(64 * CLD <= 2 * kGM * LD, "output half-tile must fit the operand tiles");
+      T* Cs = As;                                     // As and Bs are adjacent
+      for (int half = 0; half < 2; ++half) {
+        __syncthreads();
+        if ((wave >> 1) == half) {
+#pragma unroll
+          for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+              for (int v = 0; v < 16; ++v)
+                Cs[(32 * i + 8 * (v / 4) + 4 * gh + (v % 4)) * CLD + wn + 32 * j + r] =
+                    (uint16_t)(pack_bf16(acc[i][j][v], 0.f) & 0xFFFFu);
+        }
+        __syncthreads();
+        for (int idx = tid; idx < 64 * (kGN / 8); idx += 256) {
+          const int row = idx / (kGN / 8), c8 = (idx % (kGN / 8)) * 8;
+          const int64_t m = m0 + 64 * half + row;
+          if (m < g.M)
+            *reinterpret_cast<u32x4*>(C + (size_t)m * g.c_ms + n0 + c8) =
+                *reinterpret_cast<const u32x4*>(&Cs[row * CLD + c8]);
+        }
+      }
+      return;
+    }
+  }
 #pragma unroll
   for (int i = 0; i < 2; ++i)
 #pragma unroll
@@ -208,74 +242,153 @@ struct UArgs {
   float eps;
 };
 
-// one thread per (token, head): eq:routing
+// eq:routing for 32 tokens of one head per workgroup: q tile and W_r[h] in LDS
+constexpr int kGateTok = 32;
 template <typename T>
-__global__ void gating_kernel(UArgs a) {
-  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (idx >= a.N * a.H) return;
-  const int64_t l = idx / a.H;
-  const int h = (int)(idx % a.H);
-  float* r = a.R + idx * a.E;
+__global__ __launch_bounds__(256) void gating_kernel(UArgs a) {
+  extern __shared__ __attribute__((aligned(16))) float gsm[];
+  const int dh = a.dh, E = a.E;
+  float* qs = gsm;                       // [32][dh + 1]
+  float* ws = qs + kGateTok * (dh + 1);  // [dh][E]
+  float* rs = ws + dh * E;               // [32][E]
+  float* zs = rs + kGateTok * E;         // [32]
+  const int tid = threadIdx.x;
+  const int h = blockIdx.y;
+  const int64_t l0 = (int64_t)blockIdx.x * kGateTok;
   if (a.route_mode == 1) {
     const float* Rin = static_cast<const float*>(a.route);
-    for (int e = 0; e < a.E; ++e) r[e] = Rin[idx * a.E + e];
-    a.Zinv[idx] = 0.f;
+    for (int idx = tid; idx < kGateTok * E; idx += 256) {
+      const int64_t l = l0 + idx / E;
+      if (l < a.N) {
+        const size_t o = ((size_t)l * a.H + h) * E + idx % E;
+        a.R[o] = Rin[o];
+      }
+    }
+    if (tid < kGateTok && l0 + tid < a.N) a.Zinv[(l0 + tid) * a.H + h] = 0.f;
     return;
   }
-  const T* q = static_cast<const T*>(a.X) + l * a.ldx + (size_t)h * a.dh;
-  const T* W = static_cast<const T*>(a.route) + (size_t)h * a.dh * a.E;
-  float z = 0.f;
-  for (int e = 0; e < a.E; ++e) {
-    float p = 0.f;
-    for (int j = 0; j < a.dh; ++j) p = fmaf(ldf<T>(q, j), ldf<T>(W, (size_t)j * a.E + e), p);
-    const float s = sigmoid_exact(p);
-    r[e] = s;
-    z += s;
+  const T* X = static_cast<const T*>(a.X);
+  const T* W = static_cast<const T*>(a.route) + (size_t)h * dh * E;
+  for (int idx = tid; idx < kGateTok * dh; idx += 256) {
+    const int t = idx / dh, j = idx - t * dh;
+    const int64_t l = l0 + t;
+    qs[t * (dh + 1) + j] = (l < a.N) ? ldf<T>(X, l * a.ldx + (size_t)h * dh + j) : 0.f;
   }
-  const float zi = 1.0f / (z + a.eps);
-  for (int e = 0; e < a.E; ++e) r[e] *= zi;
-  a.Zinv[idx] = zi;
+  for (int idx = tid; idx < dh * E; idx += 256) ws[idx] = ldf<T>(W, idx);
+  __syncthreads();
+  for (int idx = tid; idx < kGateTok * E; idx += 256) {
+    const int t = idx / E, e = idx - t * E;
+    float p = 0.f;
+    for (int j = 0; j < dh; ++j) p = fmaf(qs[t * (dh + 1) + j], ws[j * E + e], p);
+    rs[idx] = sigmoid_exact(p);
+  }
+  __syncthreads();
+  if (tid < kGateTok) {
+    float z = 0.f;
+    for (int e = 0; e < E; ++e) z += rs[tid * E + e];
+    zs[tid] = 1.0f / (z + a.eps);
+    if (l0 + tid < a.N) a.Zinv[(l0 + tid) * a.H + h] = zs[tid];
+  }
+  __syncthreads();
+  for (int idx = tid; idx < kGateTok * E; idx += 256) {
+    const int t = idx / E;
+    const int64_t l = l0 + t;
+    if (l < a.N) a.R[((size_t)l * a.H + h) * E + (idx - t * E)] = rs[idx] * zs[t];
+  }
+}
+size_t gating_lds_bytes(int dh, int E) {
+  return sizeof(float) * ((size_t)kGateTok * (dh + 1) + (size_t)dh * E + (size_t)kGateTok * E + kGateTok);
 }
 
-// A = SiLU(G) .* U' .* R, one thread per element of [H][N][d_ff]
+// A = SiLU(G) .* U' .* R.  Each thread owns kV consecutive neurons of one (head, token)
+// row (16 bytes when d_e is a multiple of kV, so the run stays inside one sub-network).
 template <typename T>
-__global__ void act_fwd_kernel(UArgs a) {
+__global__ void act_fwd_kernel(UArgs a, int vec) {
   const int64_t dff = (int64_t)a.E * a.de;
-  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t idx = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * vec;
   if (idx >= (int64_t)a.H * a.N * dff) return;
   const int64_t c = idx % dff;
   const int64_t l = (idx / dff) % a.N;
   const int h = (int)(idx / (dff * a.N));
-  const float gv = ldf<T>(static_cast<const T*>(a.G), idx), uv = ldf<T>(static_cast<const T*>(a.U), idx);
+  const T* G = static_cast<const T*>(a.G);
+  const T* U = static_cast<const T*>(a.U);
+  T* A = static_cast<T*>(a.A);
   const float rr = a.R[(l * a.H + h) * a.E + c / a.de];
-  stf<T>(static_cast<T*>(a.A), idx, gv * sigmoid_exact(gv) * uv * rr);
+  if (vec == 1) {
+    const float gv = ldf<T>(G, idx), uv = ldf<T>(U, idx);
+    stf<T>(A, idx, gv * sigmoid_exact(gv) * uv * rr);
+    return;
+  }
+  constexpr int V = 16 / sizeof(T);
+  T gb[V], ub[V], ab[V];
+  *reinterpret_cast<u32x4*>(gb) = *reinterpret_cast<const u32x4*>(G + idx);
+  *reinterpret_cast<u32x4*>(ub) = *reinterpret_cast<const u32x4*>(U + idx);
+#pragma unroll
+  for (int i = 0; i < V; ++i) {
+    const float gv = ldf<T>(gb, i), uv = ldf<T>(ub, i);
+    stf<T>(ab, i, gv * sigmoid_exact(gv) * uv * rr);
+  }
+  *reinterpret_cast<u32x4*>(A + idx) = *reinterpret_cast<const u32x4*>(ab);
 }
 
-// dG, dU' (in place of G, U') and dr; one workgroup of 64 threads per (head, token, sub-network)
+// dG, dU' (in place of G, U') and dr.  A group of `grp` lanes (a power of two <= 64)
+// owns one (head, token, sub-network) row of d_e neurons, `vec` neurons per lane and
+// step; dr is reduced inside the group.
 template <typename T>
-__global__ __launch_bounds__(64) void act_bwd_kernel(UArgs a) {
+__global__ __launch_bounds__(256) void act_bwd_kernel(UArgs a, int vec, int grp) {
   const int64_t dff = (int64_t)a.E * a.de;
-  const int64_t blk = blockIdx.x;                 // (h * N + l) * E + e
-  const int e = (int)(blk % a.E);
-  const int64_t hl = blk / a.E;
+  const int lane = threadIdx.x & 63;
+  const int gl = lane & (grp - 1);
+  const int64_t wave_id = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int64_t blk = wave_id * (64 / grp) + lane / grp;              // (h * N + l) * E + e
+  const bool live = blk < (int64_t)a.H * a.N * a.E;
+  const int64_t bc = live ? blk : 0;
+  const int e = (int)(bc % a.E);
+  const int64_t hl = bc / a.E;
   const int64_t l = hl % a.N;
   const int h = (int)(hl / a.N);
   const float rr = a.R[(l * a.H + h) * a.E + e];
   T* G = static_cast<T*>(a.G);
   T* U = static_cast<T*>(a.U);
   const T* dA = static_cast<const T*>(a.dA);
+  const size_t base = (size_t)hl * dff + (size_t)e * a.de;
   float dr = 0.f;
-  for (int c = threadIdx.x; c < a.de; c += 64) {
-    const size_t i = (size_t)hl * dff + (size_t)e * a.de + c;
-    const float gv = ldf<T>(G, i), uv = ldf<T>(U, i), da = ldf<T>(dA, i);
+  auto one = [&](float gv, float uv, float da, float& dg, float& du) {
     const float sg = sigmoid_exact(gv);
     const float silu = gv * sg;
     dr = fmaf(da, silu * uv, dr);
-    stf<T>(U, i, rr * da * silu);
-    stf<T>(G, i, rr * da * uv * (sg + silu * (1.0f - sg)));
+    du = rr * da * silu;
+    dg = rr * da * uv * (sg + silu * (1.0f - sg));
+  };
+  if (live) {
+    if (vec == 1) {
+      for (int c = gl; c < a.de; c += grp) {
+        float dg, du;
+        one(ldf<T>(G, base + c), ldf<T>(U, base + c), ldf<T>(dA, base + c), dg, du);
+        stf<T>(U, base + c, du);
+        stf<T>(G, base + c, dg);
+      }
+    } else {
+      constexpr int V = 16 / sizeof(T);
+      for (int c = gl * V; c < a.de; c += grp * V) {
+        T gb[V], ub[V], db[V];
+        *reinterpret_cast<u32x4*>(gb) = *reinterpret_cast<const u32x4*>(G + base + c);
+        *reinterpret_cast<u32x4*>(ub) = *reinterpret_cast<const u32x4*>(U + base + c);
+        *reinterpret_cast<u32x4*>(db) = *reinterpret_cast<const u32x4*>(dA + base + c);
+#pragma unroll
+        for (int i = 0; i < V; ++i) {
+          float dg, du;
+          one(ldf<T>(gb, i), ldf<T>(ub, i), ldf<T>(db, i), dg, du);
+          stf<T>(gb, i, dg);
+          stf<T>(ub, i, du);
+        }
+        *reinterpret_cast<u32x4*>(G + base + c) = *reinterpret_cast<const u32x4*>(gb);
+        *reinterpret_cast<u32x4*>(U + base + c) = *reinterpret_cast<const u32x4*>(ub);
+      }
+    }
   }
-  for (int off = 32; off > 0; off >>= 1) dr += __shfl_xor(dr, off);
-  if (threadIdx.x == 0) a.DR[(l * a.H + h) * a.E + e] = dr;
+  for (int off = grp >> 1; off > 0; off >>= 1) dr += __shfl_xor(dr, off);
+  if (live && gl == 0) a.DR[(l * a.H + h) * a.E + e] = dr;
 }
 
 // per (token, head): dp from dr (params mode) and dX_h += dp W_r^T; DPt[h][l][e] = dp
@@ -378,7 +491,20 @@ int run_unfused(const Problem& p, const void* X, const void* Wg, const void* Wu,
   int rc;
 
   // (i) gating weights
-  hipLaunchKernelGGL(gating_kernel<T>, dim3((unsigned)((p.N * p.H + 127) / 128)), dim3(128), 0, st, a);
+  {
+    static bool gate_attr = false;
+    if (!gate_attr) {
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gating_kernel<T>),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize,
+                                         (int)kLdsBytesPerWorkgroup);
+      if (e != hipSuccess) return (int)e;
+      gate_attr = true;
+    }
+    hipLaunchKernelGGL(gating_kernel<T>, dim3((unsigned)((p.N + kGateTok - 1) / kGateTok), p.H),
+                       dim3(256), gating_lds_bytes(p.dh, p.E), st, a);
+  }
+  // 16-byte vectors in the elementwise kernels when a run of them stays inside a sub-network
+  const int vec = (p.de % (16 / (int)sizeof(T)) == 0) ? 16 / (int)sizeof(T) : 1;
   // (ii) G = X_h K_h^T, U' = X_h U_h^T
   for (int which = 0; which < 2; ++which) {
     GemmArgs g{};
@@ -391,8 +517,8 @@ int run_unfused(const Problem& p, const void* X, const void* Wg, const void* Wu,
   }
   // (iii) activation and weighting
   {
-    const int64_t n = (int64_t)p.H * p.N * dff;
-    hipLaunchKernelGGL(act_fwd_kernel<T>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, a);
+    const int64_t n = ((int64_t)p.H * p.N * dff + vec - 1) / vec;
+    hipLaunchKernelGGL(act_fwd_kernel<T>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, a, vec);
   }
   // (iv) Y_h = A_h V_h
   {
@@ -418,7 +544,13 @@ int run_unfused(const Problem& p, const void* X, const void* Wg, const void* Wu,
     if ((rc = run_gemm<T>(g, p.H, st))) return rc;
   }
   // dG, dU' in place of G, U'; dr
-  hipLaunchKernelGGL(act_bwd_kernel<T>, dim3((unsigned)((int64_t)p.H * p.N * p.E)), dim3(64), 0, st, a);
+  {
+    int grp = 1;   // lanes per (head, token, sub-network) row
+    while (grp < 64 && grp * vec < p.de) grp <<= 1;
+    const int64_t rows = (int64_t)p.H * p.N * p.E, per_block = 4 * (64 / grp);
+    hipLaunchKernelGGL(act_bwd_kernel<T>, dim3((unsigned)((rows + per_block - 1) / per_block)), dim3(256),
+                       0, st, a, vec, grp);
+  }
   // dX_h = dG K_h + dU' U_h
   if (dX) {
     GemmArgs g{};
@@ -468,7 +600,8 @@ int launch_unfused(const Problem& p, int dtype, const void* X, const void* Wg, c
                    const void* Wd, const void* route, void* Y, const void* dY, void* dX,
                    void* dWg, void* dWu, void* dWd, void* d_route, void* ws, void* stream) {
   hipStream_t st = static_cast<hipStream_t>(stream);
-  if ((int64_t)p.N * p.H * p.E > 0x7fffffffLL) return -1;  // one workgroup per (token, head, sub-network)
+  if ((int64_t)p.N * p.H * p.E > 0x7fffffffLL) return -1;  // one wave per (token, head, sub-network)
+  if (gating_lds_bytes(p.dh, p.E) > kLdsBytesPerWorkgroup) return -1;  // W_r[h] must fit in LDS
   if (dtype == 1)
     return run_unfused<uint16_t>(p, X, Wg, Wu, Wd, route, Y, dY, dX, dWg, dWu, dWd, d_route, ws, st);
   return run_unfused<float>(p, X, Wg, Wu, Wd, route, Y, dY, dX, dWg, dWu, dWd, d_route, ws, st);
