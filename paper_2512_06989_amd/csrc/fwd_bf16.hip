@@ -21,7 +21,7 @@
 #include "mhffn_device.h"
 #include "mhffn_internal.h"
 
-#include <cstdlib>
+#include <type_traits>
 
 namespace mhffn {
 namespace {
@@ -97,6 +97,49 @@ __global__ __launch_bounds__(64 * NW) void fwd_bf16_kernel(FwdArgs a) {
     }
   }
 
+  // ---- weight-tile stream: global -> registers -> LDS, two tiles in flight ----
+  const int tiles_per_sub = a.de / kBI;
+  const int T_all = E * tiles_per_sub;
+  const int t_begin = split * a.tiles_per_split;          // this workgroup's share of the
+  const int T = min(T_all, t_begin + a.tiles_per_split);   // intermediate dimension
+  const size_t head_off = (size_t)h * E * a.de * kDh;
+  const uint16_t* Kh = a.Wg + head_off;
+  const uint16_t* Uh = a.Wu + head_off;
+  const uint16_t* Vh = a.Wd + head_off;
+
+  // Two register sets: while tile t is being consumed from LDS, tile t+1 sits in one
+  // set (to be stored at the end of the step) and the loads of tile t+2 are already
+  // in flight into the other.  The first two tiles are requested before the gating
+  // phase, so their memory latency hides behind it.
+  u32x4 kreg[2][CH], ureg[2][CH], vreg[2][CH];
+  auto gload = [&](int t, auto S) {
+    constexpr int s = decltype(S)::value;
+#pragma unroll
+    for (int i = 0; i < CH; ++i) {
+      const int chunk = tid + THREADS * i;
+      const size_t off = ((size_t)t * kBI + (chunk >> 4)) * kDh + (chunk & 15) * 8;
+      kreg[s][i] = *reinterpret_cast<const u32x4*>(Kh + off);
+      ureg[s][i] = *reinterpret_cast<const u32x4*>(Uh + off);
+      vreg[s][i] = *reinterpret_cast<const u32x4*>(Vh + off);
+    }
+  };
+  auto lstore = [&](int stage, auto S) {
+    constexpr int s = decltype(S)::value;
+    unsigned char* st = stage_base + stage * kStageBytes;
+#pragma unroll
+    for (int i = 0; i < CH; ++i) {
+      const int chunk = tid + THREADS * i;
+      const int row = chunk >> 4, c16 = chunk & 15;
+      *reinterpret_cast<u32x4*>(st + row * kKUStride + c16 * 16) = kreg[s][i];
+      *reinterpret_cast<u32x4*>(st + kKBytes + row * kKUStride + c16 * 16) = ureg[s][i];
+      *reinterpret_cast<u32x4*>(st + 2 * kKBytes + row * kVStride + c16 * 16) = vreg[s][i];
+    }
+  };
+  using S0 = std::integral_constant<int, 0>;
+  using S1 = std::integral_constant<int, 1>;
+  gload(t_begin, S0{});
+  if (t_begin + 1 < T) gload(t_begin + 1, S1{});
+
   // ---- gating weights R[e][token] into LDS ---------------------------------
   if (a.route_mode == 0) {
     const int EB = (E + 31) >> 5;
@@ -158,39 +201,6 @@ __global__ __launch_bounds__(64 * NW) void fwd_bf16_kernel(FwdArgs a) {
   }
   __syncthreads();  // R complete; the staging area is free again
 
-  // ---- main loop over tiles of 32 neurons ----------------------------------
-  const int tiles_per_sub = a.de / kBI;
-  const int T_all = E * tiles_per_sub;
-  const int t_begin = split * a.tiles_per_split;          // this workgroup's share of the
-  const int T = min(T_all, t_begin + a.tiles_per_split);   // intermediate dimension
-  const size_t head_off = (size_t)h * E * a.de * kDh;
-  const uint16_t* Kh = a.Wg + head_off;
-  const uint16_t* Uh = a.Wu + head_off;
-  const uint16_t* Vh = a.Wd + head_off;
-
-  u32x4 kreg[CH], ureg[CH], vreg[CH];
-  auto gload = [&](int t) {
-#pragma unroll
-    for (int i = 0; i < CH; ++i) {
-      const int chunk = tid + THREADS * i;
-      const size_t off = ((size_t)t * kBI + (chunk >> 4)) * kDh + (chunk & 15) * 8;
-      kreg[i] = *reinterpret_cast<const u32x4*>(Kh + off);
-      ureg[i] = *reinterpret_cast<const u32x4*>(Uh + off);
-      vreg[i] = *reinterpret_cast<const u32x4*>(Vh + off);
-    }
-  };
-  auto lstore = [&](int s) {
-    unsigned char* st = stage_base + s * kStageBytes;
-#pragma unroll
-    for (int i = 0; i < CH; ++i) {
-      const int chunk = tid + THREADS * i;
-      const int row = chunk >> 4, c16 = chunk & 15;
-      *reinterpret_cast<u32x4*>(st + row * kKUStride + c16 * 16) = kreg[i];
-      *reinterpret_cast<u32x4*>(st + kKBytes + row * kKUStride + c16 * 16) = ureg[i];
-      *reinterpret_cast<u32x4*>(st + 2 * kKBytes + row * kVStride + c16 * 16) = vreg[i];
-    }
-  };
-
   f32x16 O[TB][4];
 #pragma unroll
   for (int tb = 0; tb < TB; ++tb)
@@ -203,19 +213,20 @@ __global__ __launch_bounds__(64 * NW) void fwd_bf16_kernel(FwdArgs a) {
   const int li = lane & 15;
   const int v_off = 2 * kKBytes + (4 * g + (li >> 2)) * kVStride + (16 * ((lane >> 4) & 1) + 4 * (li & 3)) * 2;
 
-  gload(t_begin);
-  lstore(t_begin & 1);
+  // ---- main loop over tiles of 32 neurons ----------------------------------
+  lstore(0, S0{});
   __syncthreads();
   float rw[TB];
-  for (int t = t_begin; t < T; ++t) {
-    const bool more = (t + 1 < T);
-    if (more) gload(t + 1);
+  // one tile: its data is in LDS stage (t - t_begin) & 1; SL = register set that is free
+  // (receives tile t+2), SS = register set holding tile t+1 (stored at the end)
+  auto tile_step = [&](int t, auto SL, auto SS) {
+    if (t + 2 < T) gload(t + 2, SL);
     if (t % tiles_per_sub == 0 || t == t_begin) {
       const int e = t / tiles_per_sub;
 #pragma unroll
       for (int tb = 0; tb < TB; ++tb) rw[tb] = Rs[e * BM + wtok + 32 * tb + r];
     }
-    const unsigned char* st = stage_base + (t & 1) * kStageBytes;
+    const unsigned char* st = stage_base + ((t - t_begin) & 1) * kStageBytes;
 
     // gate and up products
     f32x16 accM[TB], accN[TB];
@@ -275,8 +286,12 @@ __global__ __launch_bounds__(64 * NW) void fwd_bf16_kernel(FwdArgs a) {
         for (int tb = 0; tb < TB; ++tb) O[tb][jb] = mfma32(av, bfrag[tb][t2], O[tb][jb]);
       }
     }
-    if (more) lstore((t + 1) & 1);
+    if (t + 1 < T) lstore((t + 1 - t_begin) & 1, SS);
     __syncthreads();
+  };
+  for (int t = t_begin; t < T; t += 2) {
+    tile_step(t, S0{}, S1{});
+    if (t + 1 < T) tile_step(t + 1, S1{}, S0{});
   }
 
   // ---- split runs leave an fp32 partial; fwd_bf16_reduce_kernel sums them ---
