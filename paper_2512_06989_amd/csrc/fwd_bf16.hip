@@ -333,6 +333,327 @@ __global__ __launch_bounds__(64 * NW) void fwd_bf16_kernel(FwdArgs a) {
   }
 }
 
+// ---------------------------------------------------------------------------
+// Pipelined variant for the unsplit path (256 tokens per workgroup, 8 waves).
+//
+// Same arithmetic and tiling as fwd_bf16_kernel; what differs is how a wave's
+// instruction stream is laid out, because that, not the MFMA rate, bounds the
+// kernel:
+//   * weight tiles go global -> LDS directly (one 1 KB image of four swizzled
+//     rows per wave-wide load): staging costs no registers, no LDS-store
+//     instructions and no wait inside the step.  Four stages are in rotation and
+//     a tile is requested three steps before its down projection, two steps
+//     before its gate/up products;
+//   * the gate/up products of tile i+1 are issued interleaved with the
+//     activation arithmetic of tile i (two accumulator sets in alternation), so
+//     a wave keeps both the MFMA pipe and the VALU busy on its own;
+//   * the loop is unrolled over stage x accumulator set (4 bodies), which makes
+//     every LDS operand address an immediate offset from a loop-invariant
+//     per-lane register.
+// One barrier per tile: it publishes tile i+2 and retires the stage of tile i.
+// ---------------------------------------------------------------------------
+constexpr int kPipeStages = 4;
+constexpr int kPipeTile = kBI * kDh * 2;            // 8 KB, rows of 256 B, chunks swizzled
+constexpr int kPipeRing = kPipeStages * kPipeTile;  // one ring per tensor: K | U | V
+constexpr int kPipeWaves = 8;
+constexpr int kPipeBM = 32 * kPipeWaves;
+constexpr int kPipeMaxSub = (kLdsBytesPerWorkgroup - 3 * kPipeRing) / (kPipeBM * 4);
+
+typedef __attribute__((address_space(1))) const void* gptr_t;
+typedef __attribute__((address_space(3))) void* lptr_t;
+
+// Transposing LDS read issued behind the compiler's back: the compiler would make
+// every such read wait for all direct global->LDS loads in flight (it cannot tell
+// the stages apart).  The caller waits on lgkmcnt itself before using the result.
+template <int OFFSET>
+__device__ __forceinline__ s16x4 lds_read_tr16_untracked(unsigned lds_addr) {
+  s16x4 v;
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(v) : "v"(lds_addr), "n"(OFFSET));
+  return v;
+}
+
+__global__ __launch_bounds__(64 * kPipeWaves) void fwd_bf16_pipe_kernel(FwdArgs a) {
+  constexpr int BM = kPipeBM;
+  constexpr int THREADS = 64 * kPipeWaves;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  float* Rs = reinterpret_cast<float*>(smem + 3 * kPipeRing);  // [E][BM], 1/r
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int r = lane & 31, g = lane >> 5;
+  const int64_t item = xcd_work_item(blockIdx.x, a.n_items);
+  if (item >= a.n_items) return;  // whole workgroup leaves together
+  const int h = (int)(item / a.n_tiles);
+  const int64_t tile_tok0 = (item % a.n_tiles) * BM;
+  const int wtok = wave * 32;
+  const int E = a.E;
+
+  const int tiles_per_sub = a.de / kBI;
+  const int T = E * tiles_per_sub;
+  const size_t head_off = (size_t)h * E * a.de * kDh;
+  const uint16_t* Kh = a.Wg + head_off;
+  const uint16_t* Uh = a.Wu + head_off;
+  const uint16_t* Vh = a.Wd + head_off;
+
+  // ---- direct global -> LDS staging: wave w moves rows 4w..4w+3 of each tile ----
+  // lane l lands at LDS chunk position l%16 of row 4w + l/16, so it fetches the
+  // global chunk that the swizzle maps there.
+  const int drow = 4 * wave + (lane >> 4);
+  const int dma_goff = drow * kDh + (((lane & 15) ^ swz(drow)) << 3);  // elements
+  const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+  auto dma = [&](int t, int stage) {
+    const size_t off = (size_t)t * (kBI * kDh) + dma_goff;
+    unsigned char* dst = smem + stage * kPipeTile + wave_u * 1024;
+    __builtin_amdgcn_global_load_lds((gptr_t)(Kh + off), (lptr_t)dst, 16, 0, 0);
+    __builtin_amdgcn_global_load_lds((gptr_t)(Uh + off), (lptr_t)(dst + kPipeRing), 16, 0, 0);
+    __builtin_amdgcn_global_load_lds((gptr_t)(Vh + off), (lptr_t)(dst + 2 * kPipeRing), 16, 0, 0);
+  };
+  dma(0, 0);
+  if (T > 1) dma(1, 1);
+  if (T > 2) dma(2, 2);
+
+  // ---- q fragments (B operands), resident for the whole kernel -------------
+  bf16x8 q[8];
+  {
+    const int64_t tok = tile_tok0 + wtok + r;
+    const bool valid = tok < a.N;
+    const uint16_t* src = a.X + (valid ? tok : 0) * a.ldx + h * kDh + 8 * g;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+      bf16x8 v = *reinterpret_cast<const bf16x8*>(src + 16 * ks);
+      if (!valid) v = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+      q[ks] = v;
+    }
+  }
+
+  // ---- gating weights 1/R[e][token] into LDS; scratch: stage 3 of all rings ----
+  // (a [96][128] bf16 image needs 24 KB: rows 0-31 in the K ring, 32-63 U, 64-95 V)
+  if (a.route_mode == 0) {
+    const int EB = (E + 31) >> 5;
+    auto wr_off = [&](int e, int chunk) { return (e >> 5) * kPipeRing + 3 * kPipeTile + tile_off(e & 31, chunk); };
+    const uint16_t* Wr = reinterpret_cast<const uint16_t*>(a.route) + (size_t)h * kDh * E;
+    for (int idx = tid; idx < kDh * E; idx += THREADS) {
+      const int j = idx / E, e = idx - j * E;
+      *reinterpret_cast<uint16_t*>(smem + wr_off(e, j >> 3) + (j & 7) * 2) = Wr[idx];
+    }
+    for (int idx = tid; idx < (32 * EB - E) * kDh; idx += THREADS) {
+      const int e = E + idx / kDh, j = idx % kDh;
+      *reinterpret_cast<uint16_t*>(smem + wr_off(e, j >> 3) + (j & 7) * 2) = 0;
+    }
+    __syncthreads();
+    float zsum = 0.f, inv = 0.f;
+    for (int pass = 0; pass < 2; ++pass) {   // pass 0: Z = sum_e sigmoid(p_e); pass 1: r_e
+      for (int eb = 0; eb < EB; ++eb) {
+        f32x16 acc = {0};
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) {
+          const bf16x8 af = *reinterpret_cast<const bf16x8*>(smem + wr_off(32 * eb + r, 2 * ks + g));
+          acc = mfma32(af, q[ks], acc);
+        }
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int e = 32 * eb + 8 * (v / 4) + 4 * g + (v % 4);
+          const float s = (e < E) ? sigmoid_fast(acc[v]) : 0.f;
+          if (pass == 0) zsum += s;
+          else if (e < E) Rs[e * BM + wtok + r] = inv_weight(s * inv);
+        }
+      }
+      if (pass == 0) inv = 1.0f / (zsum + __shfl_xor(zsum, 32) + a.eps);
+    }
+  } else {
+    const float* R = reinterpret_cast<const float*>(a.route);
+    for (int idx = tid; idx < BM * E; idx += THREADS) {
+      const int tl = idx / E, e = idx - tl * E;
+      const int64_t tok = tile_tok0 + tl;
+      Rs[e * BM + tl] = inv_weight((tok < a.N) ? R[((size_t)tok * a.H + h) * E + e] : 0.f);
+    }
+  }
+  __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0): tiles 0..2 have landed
+  __syncthreads();
+
+  // ---- loop-invariant operand addresses inside a tile ------------------------
+  int kaddr[8];      // K/U operand of contraction step ks: row r, chunk 2ks+g
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) kaddr[ks] = tile_off(r, 2 * ks + g);
+  unsigned vaddr[4][2];  // V operand, transposing read: rows 4g + li/4 (+8), 64-byte window jb
+  {
+    const int li = lane & 15;
+    const int row = 4 * g + (li >> 2);
+    const int colb = 16 * ((lane >> 4) & 1) + 4 * (li & 3);
+    const unsigned vbase = (unsigned)(uintptr_t)(lptr_t)(smem + 2 * kPipeRing);
+#pragma unroll
+    for (int jb = 0; jb < 4; ++jb) {
+      vaddr[jb][0] = vbase + tile_off8(row, 32 * jb + colb);
+      vaddr[jb][1] = vbase + tile_off8(row + 8, 32 * jb + colb);
+    }
+  }
+
+  f32x16 O[4];
+#pragma unroll
+  for (int jb = 0; jb < 4; ++jb) O[jb] = f32x16{0};
+  f32x16 accM[2], accN[2];
+
+  // gate/up products of tile 0
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) {
+    const bf16x8 ak = *reinterpret_cast<const bf16x8*>(smem + kaddr[ks]);
+    const bf16x8 au = *reinterpret_cast<const bf16x8*>(smem + kPipeRing + kaddr[ks]);
+    if (ks == 0) { accM[0] = mfma32(ak, q[0], f32x16{0}); accN[0] = mfma32(au, q[0], f32x16{0}); }
+    else { accM[0] = mfma32(ak, q[ks], accM[0]); accN[0] = mfma32(au, q[ks], accN[0]); }
+  }
+
+  const float* rs_ptr = Rs + wtok + r;  // 1/r of the current sub-network for this lane's token
+  int sub_cnt = 0;
+
+  // step i: tile i sits in stage S with its gate/up accumulators in set P
+  auto step = [&](int i, auto S_, auto P_) {
+    constexpr int S = decltype(S_)::value, P = decltype(P_)::value, Q = 1 - P;
+    const bool more = (i + 3 < T);
+    if (more) dma(i + 3, (S + 3) % 4);
+    const float rw = *rs_ptr;
+    if (++sub_cnt == tiles_per_sub) { sub_cnt = 0; rs_ptr += BM; }
+
+    // Gate/up products of tile i+1 (stage S+1) interleaved with the activation of tile i,
+    // slot by slot.  Slot s issues the LDS reads of contraction step s+2, the two MFMAs of
+    // step s, and one stage each of three element pairs of the activation, so that
+    // dependent VALU instructions sit a slot apart:
+    //   A(pair s): t = 2^(-m log2 e)   B(pair s-1): s = rcp((1+t)/r)   C(pair s-2): m n s, rounding.
+    // The empty asm statements carry the values from slot to slot and thereby pin the order
+    // (the compiler would otherwise issue all MFMAs first and the arithmetic after them).
+    // After the last tile the products read a stale stage and are never used.
+    const unsigned char* kn = smem + ((S + 1) % 4) * kPipeTile;
+    u32x4 pk[2];
+    bf16x8 ka[3], ua[3];
+    float tt[2][2], ss[2][2];
+    s16x4 vlo[4], vhi[4], wlo[4], whi[4];
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+      ka[ks] = *reinterpret_cast<const bf16x8*>(kn + kaddr[ks]);
+      ua[ks] = *reinterpret_cast<const bf16x8*>(kn + kPipeRing + kaddr[ks]);
+    }
+    MHFFN_SB();
+#pragma unroll
+    for (int sl = 0; sl < 10; ++sl) {
+      if (sl + 2 < 8) {
+        ka[(sl + 2) % 3] = *reinterpret_cast<const bf16x8*>(kn + kaddr[sl + 2]);
+        ua[(sl + 2) % 3] = *reinterpret_cast<const bf16x8*>(kn + kPipeRing + kaddr[sl + 2]);
+      } else if (sl == 6) {
+        // operands of the first half of the down projection
+        vlo[0] = lds_read_tr16_untracked<S * kPipeTile>(vaddr[0][0]);
+        vhi[0] = lds_read_tr16_untracked<S * kPipeTile>(vaddr[0][1]);
+        vlo[1] = lds_read_tr16_untracked<S * kPipeTile>(vaddr[1][0]);
+        vhi[1] = lds_read_tr16_untracked<S * kPipeTile>(vaddr[1][1]);
+      } else if (sl == 7) {
+        vlo[2] = lds_read_tr16_untracked<S * kPipeTile>(vaddr[2][0]);
+        vhi[2] = lds_read_tr16_untracked<S * kPipeTile>(vaddr[2][1]);
+        vlo[3] = lds_read_tr16_untracked<S * kPipeTile>(vaddr[3][0]);
+        vhi[3] = lds_read_tr16_untracked<S * kPipeTile>(vaddr[3][1]);
+      }
+      const int c = sl & 1, p1 = (sl + 1) & 1;   // slots of pair sl (and sl-2), of pair sl-1
+      if (sl < 8) {
+        if (sl == 0) {
+          accM[Q] = mfma32(ka[0], q[0], f32x16{0});
+          accN[Q] = mfma32(ua[0], q[0], f32x16{0});
+        } else {
+          accM[Q] = mfma32(ka[sl % 3], q[sl], accM[Q]);
+          accN[Q] = mfma32(ua[sl % 3], q[sl], accN[Q]);
+        }
+        // the arithmetic below may not start before the two MFMAs above are issued
+        asm volatile("" : "+v"(accM[Q]), "+v"(accN[Q]), "+v"(accM[P]));
+      }
+      uint32_t pkw = 0;
+      if (sl >= 2) {   // C(pair sl-2)
+        const int e = sl - 2;
+        pkw = pack_bf16((accM[P][2 * e] * accN[P][2 * e]) * ss[c][0],
+                        (accM[P][2 * e + 1] * accN[P][2 * e + 1]) * ss[c][1]);
+      }
+      if (sl >= 1 && sl <= 8) {   // B(pair sl-1)
+        ss[p1][0] = __builtin_amdgcn_rcpf(__builtin_fmaf(tt[p1][0], rw, rw));
+        ss[p1][1] = __builtin_amdgcn_rcpf(__builtin_fmaf(tt[p1][1], rw, rw));
+      }
+      if (sl < 8) {               // A(pair sl)
+        tt[c][0] = __builtin_amdgcn_exp2f(-MHFFN_LOG2E * accM[P][2 * sl]);
+        tt[c][1] = __builtin_amdgcn_exp2f(-MHFFN_LOG2E * accM[P][2 * sl + 1]);
+      }
+      // ... and the next slot's MFMAs not before this slot's arithmetic
+      if (sl == 0)
+        asm volatile("" : "+v"(accM[Q]), "+v"(accN[Q]), "+v"(tt[c][0]), "+v"(tt[c][1]) :: "memory");
+      else if (sl == 1)
+        asm volatile("" : "+v"(accM[Q]), "+v"(accN[Q]), "+v"(tt[c][0]), "+v"(tt[c][1]),
+                          "+v"(ss[p1][0]), "+v"(ss[p1][1]) :: "memory");
+      else if (sl < 8)
+        asm volatile("" : "+v"(accM[Q]), "+v"(accN[Q]), "+v"(tt[c][0]), "+v"(tt[c][1]),
+                          "+v"(ss[p1][0]), "+v"(ss[p1][1]), "+v"(pkw) :: "memory");
+      else if (sl == 8)
+        asm volatile("" : "+v"(ss[p1][0]), "+v"(ss[p1][1]), "+v"(pkw) :: "memory");
+      else
+        asm volatile("" : "+v"(pkw) :: "memory");
+      if (sl >= 2) pk[(sl - 2) >> 2][(sl - 2) & 3] = pkw;
+      MHFFN_SB();
+    }
+
+    // down projection of tile i.  Only the 16 untracked reads can be outstanding here
+    // (every tracked read of this step has been consumed above, the next ones follow the
+    // barrier), so lgkmcnt(8) means: the first eight have returned.
+#pragma unroll
+    for (int jb = 0; jb < 4; ++jb) {
+      wlo[jb] = lds_read_tr16_untracked<S * kPipeTile + 4096>(vaddr[jb][0]);
+      whi[jb] = lds_read_tr16_untracked<S * kPipeTile + 4096>(vaddr[jb][1]);
+    }
+    asm volatile("s_waitcnt lgkmcnt(8)"
+                 : "+v"(vlo[0]), "+v"(vhi[0]), "+v"(vlo[1]), "+v"(vhi[1]), "+v"(vlo[2]), "+v"(vhi[2]),
+                   "+v"(vlo[3]), "+v"(vhi[3]));
+    const bf16x8 b0 = __builtin_bit_cast(bf16x8, pk[0]), b1 = __builtin_bit_cast(bf16x8, pk[1]);
+    typedef short s16x8 __attribute__((ext_vector_type(8)));
+#pragma unroll
+    for (int jb = 0; jb < 4; ++jb) {
+      const s16x8 both = __builtin_shufflevector(vlo[jb], vhi[jb], 0, 1, 2, 3, 4, 5, 6, 7);
+      O[jb] = mfma32(__builtin_bit_cast(bf16x8, both), b0, O[jb]);
+    }
+    asm volatile("s_waitcnt lgkmcnt(0)"
+                 : "+v"(wlo[0]), "+v"(whi[0]), "+v"(wlo[1]), "+v"(whi[1]), "+v"(wlo[2]), "+v"(whi[2]),
+                   "+v"(wlo[3]), "+v"(whi[3]));
+#pragma unroll
+    for (int jb = 0; jb < 4; ++jb) {
+      const s16x8 both = __builtin_shufflevector(wlo[jb], whi[jb], 0, 1, 2, 3, 4, 5, 6, 7);
+      O[jb] = mfma32(__builtin_bit_cast(bf16x8, both), b1, O[jb]);
+    }
+    // Publish tile i+2 (requested one step ago; the three loads issued at the top of this
+    // step may stay in flight) and retire stage S.  A bare barrier: __syncthreads() would
+    // wait for every load in flight.
+    asm volatile("" ::: "memory");
+    if (more) __builtin_amdgcn_s_waitcnt(0x0073);  // vmcnt(3) lgkmcnt(0)
+    else __builtin_amdgcn_s_waitcnt(0x0070);       // vmcnt(0) lgkmcnt(0)
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+  };
+  using C0 = std::integral_constant<int, 0>;
+  using C1 = std::integral_constant<int, 1>;
+  using C2 = std::integral_constant<int, 2>;
+  using C3 = std::integral_constant<int, 3>;
+  for (int i = 0; i < T; i += 4) {
+    step(i, C0{}, C0{});
+    if (i + 1 < T) step(i + 1, C1{}, C1{});
+    if (i + 2 < T) step(i + 2, C2{}, C0{});
+    if (i + 3 < T) step(i + 3, C3{}, C1{});
+  }
+
+  // ---- store Y (concat_H: head h owns columns h*d_h ..) --------------------
+  const int64_t tok = tile_tok0 + wtok + r;
+  if (tok < a.N) {
+    uint16_t* dst = a.Y + tok * a.ldy + h * kDh + 4 * g;
+#pragma unroll
+    for (int jb = 0; jb < 4; ++jb) {
+#pragma unroll
+      for (int vq = 0; vq < 4; ++vq) {
+        u32x2 pk;
+        pk[0] = pack_bf16(O[jb][4 * vq], O[jb][4 * vq + 1]);
+        pk[1] = pack_bf16(O[jb][4 * vq + 2], O[jb][4 * vq + 3]);
+        *reinterpret_cast<u32x2*>(dst + 32 * jb + 8 * vq) = pk;
+      }
+    }
+  }
+}
+
 // Y[tok][col] = bf16(sum_s P[s][tok][col]), fixed order
 __global__ void fwd_bf16_reduce_kernel(FwdArgs a) {
   const int64_t dm = (int64_t)a.H * kDh;
@@ -390,6 +711,25 @@ int launch_variant(const Problem& p, FwdArgs a, const SplitPlan& sp, hipStream_t
   return (int)hipGetLastError();
 }
 
+int launch_pipe(const Problem& p, FwdArgs a, hipStream_t stream) {
+  a.n_tiles = (p.N + kPipeBM - 1) / kPipeBM;
+  a.n_split = 1;
+  a.tiles_per_split = p.E * (p.de / kBI);
+  a.n_items = a.n_tiles * p.H;
+  const size_t lds = (size_t)3 * kPipeRing + (size_t)p.E * kPipeBM * sizeof(float);
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&fwd_bf16_pipe_kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)kLdsBytesPerWorkgroup);
+    if (e != hipSuccess) return (int)e;
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(fwd_bf16_pipe_kernel, dim3((unsigned)xcd_grid_size(a.n_items)),
+                     dim3(64 * kPipeWaves), lds, stream, a);
+  return (int)hipGetLastError();
+}
+
 }  // namespace
 
 size_t fwd_bf16_workspace_bytes(const Problem& p) {
@@ -416,6 +756,7 @@ int launch_fwd_bf16(const Problem& p, const void* X, const void* Wg, const void*
   // 8 waves x 32 tokens (two waves per SIMD) measured 25% faster than 4 waves x
   // 64 tokens at the 1.3B shape: the second wave hides LDS and barrier latency.
   if (sp.bm == 64) return launch_variant<1, 2>(p, a, sp, st);
+  if (sp.n_split == 1 && p.E <= kPipeMaxSub) return launch_pipe(p, a, st);
   return launch_variant<1, 8>(p, a, sp, st);
 }
 

@@ -62,6 +62,34 @@ __device__ __forceinline__ s16x4 lds_read_tr16(const void* lds_ptr) {
   return __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)lds_ptr);
 }
 
+// Swizzled LDS tile: [rows][128 bf16], 256 bytes per row, the 16-byte chunks of a
+// row permuted by swz(row).  Row-wise operand reads (one row per lane) and
+// transposing reads (4 consecutive rows, 64-byte windows) are both free of bank
+// conflicts without padding, and a tile is a contiguous image of 4-row groups of
+// 1 KB, which is what a wave-wide direct global->LDS load writes.
+__device__ __forceinline__ int swz(int row) { return ((row & 3) << 2) | ((row >> 2) & 3); }
+// byte offset of logical 16-byte chunk `chunk` of `row` inside a tile
+__device__ __forceinline__ int tile_off(int row, int chunk) {
+  return row * 256 + ((chunk ^ swz(row)) << 4);
+}
+// byte offset of the 8-byte piece starting at bf16 column `col` (multiple of 4)
+__device__ __forceinline__ int tile_off8(int row, int col) {
+  return tile_off(row, col >> 3) + ((col & 4) << 1);
+}
+
+// Transposed operand for one MFMA step: rows {r0..r0+3} and {r0+8..r0+11} of a
+// tile, columns c0 + (lane % 32); lane geometry as in lds_read_tr16.
+__device__ __forceinline__ bf16x8 tile_read_tr(const unsigned char* tile, int r0, int c0, int lane) {
+  const int li = lane & 15;
+  const int row = r0 + (li >> 2);
+  const int col = c0 + 16 * ((lane >> 4) & 1) + 4 * (li & 3);
+  const s16x4 lo = lds_read_tr16(tile + tile_off8(row, col));
+  const s16x4 hi = lds_read_tr16(tile + tile_off8(row + 8, col));
+  typedef short s16x8 __attribute__((ext_vector_type(8)));
+  const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+  return __builtin_bit_cast(bf16x8, both);
+}
+
 // XCD-aware work distribution.  Workgroups are handed to the 8 XCDs round
 // robin by blockIdx, and every XCD has a private L2.  The head-major work list
 // (item = head * n_tiles + tile) is cut into 8 contiguous chunks, one per XCD,
