@@ -14,8 +14,8 @@
 //         dX^T += W_r dp^T                                 (MFMA)
 //       R and dp are left in the workspace as [H][E][N] fp32 for the other
 //       kernels (E values per token and head, not d_ff values).
-//   bwd_wgt_kernel   (appendix algorithm "Backward (dK,dU,dV)")
-//       one wave = 32 neurons of one head, K/U/V rows resident in registers as
+//   bwd_wgt16_kernel (appendix algorithm "Backward (dK,dU,dV)")
+//       one wave = 16 neurons of one head, K/U/V rows resident in registers as
 //       MFMA operands, loop over all tokens:
 //         M, N, dA recomputed; dV^T += dY^T A_gated, dK^T += q^T dM, dU^T += q^T dN
 //       (the q / dY tiles are read from LDS both row-wise and transposed).
@@ -27,6 +27,8 @@
 // bank conflicts without padding.
 #include "mhffn_device.h"
 #include "mhffn_internal.h"
+
+#include <type_traits>
 
 namespace mhffn {
 namespace {
@@ -380,222 +382,258 @@ __global__ __launch_bounds__(64 * NW) void bwd_tok_kernel(BwdArgs a) {
 }
 
 // ---------------------------------------------------------------------------
-// weight-major kernel: dK, dU, dV
+// weight-major kernel, 16 neurons per wave (two waves per SIMD)
+//
+// One wave owns 16 neurons of one head: their K/U/V rows are resident as B
+// operands of v_mfma_f32_16x16x32_bf16 (48 VGPR) and the accumulators dK^T, dU^T,
+// dV^T take 96 VGPR, so a wave fits in 256 registers and two waves share a SIMD
+// (the fp32 VALU issues at twice the rate when it can alternate between two
+// waves, and one wave's arithmetic hides behind the other's MFMAs).
+// Eight waves share the q / dY token tiles, which go global -> LDS directly in
+// three stages.  Per 32 tokens and wave:
+//   M, N [32 tok][16]  = q K^T, q U^T          16 MFMA   (A: q rows from LDS)
+//   dA   [32 tok][16]  = dY V^T                  8 MFMA
+//   a, dn, dm                                     fp32 VALU, 8 elements per lane
+//   dV^T[j][c] += dY^T a; dK^T += q^T dm; dU^T += q^T dn   24 MFMA (A: transposing reads)
+// Token order inside a 16-token block: MFMA row 4gq+v is token 4p(gq)+v with
+// p = (0,2,1,3); the transposing reads of lane groups gq = 0,1 (served together)
+// then fall on rows 0-3 and 8-11, whose swizzles differ, and stay free of bank
+// conflicts.  All LDS reads are issued untracked with explicit waits.
+// Rows past N are read from row N-1 (finite data) and carry r = 0, so they add
+// nothing to any gradient.
 // ---------------------------------------------------------------------------
-constexpr int kWgtWaves = 4;
-constexpr int kWgtThreads = 64 * kWgtWaves;
-constexpr int kWgtStageBytes = 2 * kTileBytes + kWgtWaves * 32 * 4;  // q tile, dY tile, r per wave
+constexpr int kW16Waves = 8;
+constexpr int kW16Threads = 64 * kW16Waves;
+constexpr int kW16Stage = 2 * kTileBytes + kW16Waves * 32 * 4;  // q tile, dY tile, r per wave: 17 KB
+constexpr int kW16Stages = 3;
 
-__global__ __launch_bounds__(kWgtThreads) void bwd_wgt_kernel(BwdArgs a) {
+__global__ __launch_bounds__(kW16Threads) void bwd_wgt16_kernel(BwdArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int r = lane & 31, g = lane >> 5;
-  const int nblk = a.E * a.de / 32;              // 32-neuron blocks per head
-  const int wg_per_head = (nblk + kWgtWaves - 1) / kWgtWaves;
+  const int cn = lane & 15, gq = lane >> 4;
+  const int pg = ((gq & 1) << 1) | (gq >> 1);    // token group of MFMA row group gq
+  const int nblk = a.E * a.de / 16;              // 16-neuron blocks per head
+  const int wg_per_head = (nblk + kW16Waves - 1) / kW16Waves;
   const int64_t item = xcd_work_item(blockIdx.x, a.n_items);
   if (item >= a.n_items) return;
   const int h = (int)(item / wg_per_head);
-  const int blk = (int)(item % wg_per_head) * kWgtWaves + wave;
+  const int blk = (int)(item % wg_per_head) * kW16Waves + wave;
   const bool active = blk < nblk;
   const int blk_c = active ? blk : nblk - 1;     // idle waves shadow a valid block, store nothing
   const int64_t N = a.N;
-  const size_t row0 = (size_t)h * nblk * 32 + (size_t)blk_c * 32;  // first neuron row of this wave
+  const size_t row0 = ((size_t)h * nblk + blk_c) * 16;   // first neuron row of this wave
+  const int e_wave = blk_c / (a.de / 16);
 
-  // resident weight operands: lane (neuron r, half g) holds columns 16ks + 8g ..
-  // (re-reading them from a wave-private LDS copy every step instead was measured
-  // 17 % slower: the LDS pipe is the scarcer resource)
-  bf16x8 Kf[8], Uf[8], Vf[8];
+  // resident weight operands: lane (neuron cn, group gq) holds columns 32ks + 8gq ..
+  bf16x8 Kf[4], Uf[4], Vf[4];
   {
-    const size_t off = (row0 + r) * kDh + 8 * g;
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks) {
-      Kf[ks] = *reinterpret_cast<const bf16x8*>(a.Wg + off + 16 * ks);
-      Uf[ks] = *reinterpret_cast<const bf16x8*>(a.Wu + off + 16 * ks);
-      Vf[ks] = *reinterpret_cast<const bf16x8*>(a.Wd + off + 16 * ks);
-    }
-  }
-  f32x16 dK[4], dU[4], dV[4];
-#pragma unroll
-  for (int jb = 0; jb < 4; ++jb) { dK[jb] = f32x16{0}; dU[jb] = f32x16{0}; dV[jb] = f32x16{0}; }
-
-  // per-wave sub-network of the r values each thread stages (threads 0..127)
-  const int stage_wave = tid >> 5, stage_tok = tid & 31;
-  int e_stage = 0;
-  {
-    const int b2 = (int)(item % wg_per_head) * kWgtWaves + stage_wave;
-    e_stage = (b2 < nblk ? b2 : nblk - 1) / (a.de / 32);
-  }
-  const float* Rh = a.Rws + (size_t)h * a.E * N;
-
-  u32x4 qreg[2], yreg[2];
-  float rreg = 0.f;
-  auto gload = [&](int64_t tok0) {
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      const int chunk = tid + kWgtThreads * i;
-      const int64_t t = tok0 + (chunk >> 4);
-      if (t < N) {
-        qreg[i] = *reinterpret_cast<const u32x4*>(a.X + t * a.ldx + h * kDh + (chunk & 15) * 8);
-        yreg[i] = *reinterpret_cast<const u32x4*>(a.dY + t * a.ldy + h * kDh + (chunk & 15) * 8);
-      } else {
-        qreg[i] = u32x4{0, 0, 0, 0};
-        yreg[i] = u32x4{0, 0, 0, 0};
-      }
-    }
-    if (tid < 128) {
-      const int64_t t = tok0 + stage_tok;
-      rreg = (t < N) ? Rh[(size_t)e_stage * N + t] : 0.f;
-    }
-  };
-  auto lstore = [&](int s) {
-    unsigned char* st = smem + s * kWgtStageBytes;
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      const int chunk = tid + kWgtThreads * i;
-      const int off = tile_off(chunk >> 4, chunk & 15);
-      *reinterpret_cast<u32x4*>(st + off) = qreg[i];
-      *reinterpret_cast<u32x4*>(st + kTileBytes + off) = yreg[i];
-    }
-    if (tid < 128) reinterpret_cast<float*>(st + 2 * kTileBytes)[tid] = rreg;
-  };
-
-  const int64_t nb = (N + 31) / 32;
-  gload(0);
-  lstore(0);
-  __syncthreads();
-  for (int64_t b = 0; b < nb; ++b) {
-    const bool more = (b + 1 < nb);
-    if (more) gload((b + 1) * 32);
-    const unsigned char* st = smem + (b & 1) * kWgtStageBytes;
-    const unsigned char* qt = st;
-    const unsigned char* yt = st + kTileBytes;
-    const float* rt = reinterpret_cast<const float*>(st + 2 * kTileBytes) + wave * 32;
-
-    // One wave per SIMD: nothing but this wave's own instruction stream can keep the
-    // MFMA pipe and the VALU busy at the same time, so the step is written as an
-    // explicit interleave (scheduling barriers pin it):
-    //   1. M and N chains (16 MFMA)
-    //   2. dA chain (8 MFMA)            || everything that needs only m, n, r   (12 VALU / element)
-    //   3. gradient MFMAs of tokens 0-15 || dn, dm, rounding of tokens 16-31
-    //   4. gradient MFMAs of tokens 16-31
-    // M[tok][c], N[tok][c], dA[tok][c]: lane = neuron column, registers = token rows;
-    // registers 8*t2 + 4*hi + x hold tokens 16*t2 + 8*hi + 4g + x.
-    f32x4 rv[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) rv[i] = *reinterpret_cast<const f32x4*>(rt + 8 * i + 4 * g);
-    bf16x8 oa[4], ob[4];
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks) oa[ks] = *reinterpret_cast<const bf16x8*>(qt + tile_off(r, 2 * ks + g));
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks) ob[ks] = *reinterpret_cast<const bf16x8*>(qt + tile_off(r, 2 * (ks + 4) + g));
-    MHFFN_SB();
-    f32x16 accM, accN, accA;
+    const size_t off = (row0 + cn) * kDh + 8 * gq;
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
-      if (ks == 0) { accM = mfma32(oa[0], Kf[0], f32x16{0}); accN = mfma32(oa[0], Uf[0], f32x16{0}); }
-      else { accM = mfma32(oa[ks], Kf[ks], accM); accN = mfma32(oa[ks], Uf[ks], accN); }
+      Kf[ks] = *reinterpret_cast<const bf16x8*>(a.Wg + off + 32 * ks);
+      Uf[ks] = *reinterpret_cast<const bf16x8*>(a.Wu + off + 32 * ks);
+      Vf[ks] = *reinterpret_cast<const bf16x8*>(a.Wd + off + 32 * ks);
     }
-    MHFFN_SB();
+  }
+  f32x4 dK[8], dU[8], dV[8];
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) oa[ks] = *reinterpret_cast<const bf16x8*>(yt + tile_off(r, 2 * ks + g));
+  for (int jb = 0; jb < 8; ++jb) { dK[jb] = f32x4{0, 0, 0, 0}; dU[jb] = dK[jb]; dV[jb] = dK[jb]; }
+
+  // ---- staging -----------------------------------------------------------------
+  // wave w moves rows 4w..4w+3 of the q and dY tiles (one 1 KB swizzled image each)
+  // and the 32 r values of its own sub-network.
+  const int drow = 4 * wave + (lane >> 4);
+  const int dcol = h * kDh + (((lane & 15) ^ swz(drow)) << 3);   // element column in X / dY
+  const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+  const float* Rw = a.Rws + ((size_t)h * a.E + e_wave) * N;
+  auto dma = [&](int64_t blkidx, int stage) {
+    int64_t t = blkidx * 32 + drow;
+    t = t < N ? t : N - 1;
+    unsigned char* dst = smem + stage * kW16Stage + wave_u * 1024;
+    global_to_lds_16B(a.X + t * a.ldx + dcol, dst);
+    global_to_lds_16B(a.dY + t * a.ldy + dcol, dst + kTileBytes);
+  };
+  auto rload = [&](int64_t blkidx) -> float {
+    const int64_t t = blkidx * 32 + (lane & 31);
+    return (lane < 32 && t < N) ? Rw[t] : 0.f;
+  };
+  auto rstore = [&](int stage, float v) {
+    if (lane < 32)
+      reinterpret_cast<float*>(smem + stage * kW16Stage + 2 * kTileBytes)[wave * 32 + lane] = v;
+  };
+  const int64_t nb = (N + 31) / 32;
+  {
+    const float r0 = rload(0);
+    dma(0, 0);
+    if (nb > 1) dma(1, 1);
+    rstore(0, r0);
+  }
+  __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0)
+  __syncthreads();
+
+  // ---- loop-invariant LDS addresses -----------------------------------------------
+  const unsigned lbase = lds_addr_of(smem);
+  unsigned qaddr[4];   // A operand of M/N/dA: token row p(cn), 16-byte chunk 4ks + gq
+  {
+    const int row = ((cn & 3) | ((cn & 4) << 1) | ((cn & 8) >> 1));
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) { accM = mfma32(ob[ks], Kf[ks + 4], accM); accN = mfma32(ob[ks], Uf[ks + 4], accN); }
-    MHFFN_SB();
+    for (int ks = 0; ks < 4; ++ks) qaddr[ks] = lbase + tile_off(row, 4 * ks + gq);
+  }
+  unsigned taddr[8];   // transposed operand: rows 4 pg + cn/4 (+16), columns 16jb + 4(cn%4)
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) ob[ks] = *reinterpret_cast<const bf16x8*>(yt + tile_off(r, 2 * (ks + 4) + g));
-    // transposed operands of tokens 0-15, fetched under the arithmetic below
-    bf16x8 yT[4], qT[4];
+  for (int jb = 0; jb < 8; ++jb) taddr[jb] = lbase + tile_off8(4 * pg + (cn >> 2), 16 * jb + 4 * (cn & 3));
+  const unsigned raddr = lbase + 2 * kTileBytes + wave * 128 + 16 * pg;  // r of tokens 4pg.. (+64: 16+4pg..)
+
+  auto step = [&](int64_t b, auto S_) {
+    constexpr int S = decltype(S_)::value;
+    constexpr int SO = S * kW16Stage;                 // this step's stage
+    const bool more1 = (b + 1 < nb), more2 = (b + 2 < nb);
+    float rnext = 0.f;
+    if (more1) rnext = rload(b + 1);
+    if (more2) dma(b + 2, (S + 2) % 3);
+
+    // ---- operand stream: R, Q0..7, Y0..7, then X0..15 = yT0, qT0, yT1, qT1, ... ---------
+    f32x4 rv[2];
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(rv[0]) : "v"(raddr), "n"(SO));
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(rv[1]) : "v"(raddr), "n"(SO + 64));
+    bf16x8 op[16];     // b128 operands, index = position in the stream (Q: 0..7, Y: 8..15)
+#define MHFFN_W16_LOAD(i)                                                                       \
+    op[i] = lds_read_b128_untracked<SO + ((i) >= 8 ? kTileBytes : 0) + (((i) >> 2) & 1) * 4096>(qaddr[(i) & 3])
+    MHFFN_W16_LOAD(0); MHFFN_W16_LOAD(1); MHFFN_W16_LOAD(2); MHFFN_W16_LOAD(3);
+    s16x4 xlo[16], xhi[16];
+    // transposed operand j of the stream: even = dY^T window j/2, odd = q^T window j/2
+#define MHFFN_W16_LOADX(j)                                                                      \
+    xlo[j] = lds_read_tr16_untracked<SO + (((j) & 1) ? 0 : kTileBytes)>(taddr[(j) >> 1]);       \
+    xhi[j] = lds_read_tr16_untracked<SO + (((j) & 1) ? 0 : kTileBytes) + 4096>(taddr[(j) >> 1])
+
+    f32x4 M[2], Nn[2], Ad[2];
 #pragma unroll
-    for (int jb = 0; jb < 4; ++jb) {
-      yT[jb] = tile_read_tr(yt, 4 * g, 32 * jb, lane);
-      qT[jb] = tile_read_tr(qt, 4 * g, 32 * jb, lane);
+    for (int tb = 0; tb < 2; ++tb) { M[tb] = f32x4{0, 0, 0, 0}; Nn[tb] = M[tb]; Ad[tb] = M[tb]; }
+    // gate / up products; four loads stay ahead of the one being consumed
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      switch (i + 4) {
+        case 4: MHFFN_W16_LOAD(4); break;   case 5: MHFFN_W16_LOAD(5); break;
+        case 6: MHFFN_W16_LOAD(6); break;   case 7: MHFFN_W16_LOAD(7); break;
+        case 8: MHFFN_W16_LOAD(8); break;   case 9: MHFFN_W16_LOAD(9); break;
+        case 10: MHFFN_W16_LOAD(10); break; default: MHFFN_W16_LOAD(11); break;
+      }
+      lds_wait<4>(op[i]);
+      const int tb = i >> 2, ks = i & 3;
+      M[tb] = mfma16(op[i], Kf[ks], M[tb]);
+      Nn[tb] = mfma16(op[i], Uf[ks], Nn[tb]);
     }
-    MHFFN_SB();
-    float Pw[16], Qw[16];   // r silu(m)  and  r n silu'(m)
-    u32x4 pa[2];
+    // dA products, with everything that needs only m, n, r computed under them
+    float Pw[8], Qw[8];   // r silu(m)  and  r n silu'(m)
+    u32x4 pa;
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) {
-      if (ks == 0) accA = mfma32(oa[0], Vf[0], f32x16{0});
-      else accA = mfma32(ks < 4 ? oa[ks] : ob[ks - 4], Vf[ks], accA);
-      float av[2];
-#pragma unroll
-      for (int u = 0; u < 2; ++u) {
-        const int v = 2 * ks + u;
-        const float rwv = rv[v >> 2][v & 3];
-        const float m = accM[v], n = accN[v];
+    for (int i = 0; i < 8; ++i) {
+      switch (i + 4) {
+        case 4: MHFFN_W16_LOAD(12); break;  case 5: MHFFN_W16_LOAD(13); break;
+        case 6: MHFFN_W16_LOAD(14); break;  case 7: MHFFN_W16_LOAD(15); break;
+        case 8: MHFFN_W16_LOADX(0); break;  case 9: MHFFN_W16_LOADX(1); break;
+        case 10: MHFFN_W16_LOADX(2); break; default: MHFFN_W16_LOADX(3); break;
+      }
+      // instructions newer than operand Y_i: 4 for i < 4, then 5, 6, 7, 8
+      switch (i) {
+        case 0: case 1: case 2: case 3: lds_wait<4>(op[8 + i]); break;
+        case 4: lds_wait<5>(op[8 + i]); break;
+        case 5: lds_wait<6>(op[8 + i]); break;
+        case 6: lds_wait<7>(op[8 + i]); break;
+        default: lds_wait<8>(op[8 + i]); break;
+      }
+      const int tb = i >> 2, ks = i & 3;
+      Ad[tb] = mfma16(op[8 + i], Vf[ks], Ad[tb]);
+      {
+        const int v = i & 3;
+        const float rwv = rv[tb][v];
+        const float m = M[tb][v], n = Nn[tb][v];
         const float t = __builtin_amdgcn_exp2f(-MHFFN_LOG2E * m);
         const float sg = __builtin_amdgcn_rcpf(1.0f + t);
         const float sw = rwv * sg;
         const float x = (1.0f + m) - m * sg;   // silu'(m) = sg (1 + m - silu(m))
-        Pw[v] = m * sw;
-        Qw[v] = (n * sw) * x;
-        av[u] = Pw[v] * n;
+        Pw[i] = m * sw;
+        Qw[i] = (n * sw) * x;
       }
-      pa[ks >> 2][ks & 3] = pack_bf16(av[0], av[1]);
-      MHFFN_SB();
     }
-    // tokens 0-15: dn = P da, dm = Q da
+    // tokens of this lane: k-slot s = 4tb + v of every gradient product
     u32x4 pm, pn;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      pm[i] = pack_bf16(Qw[2 * i] * accA[2 * i], Qw[2 * i + 1] * accA[2 * i + 1]);
-      pn[i] = pack_bf16(Pw[2 * i] * accA[2 * i], Pw[2 * i + 1] * accA[2 * i + 1]);
+    for (int s2 = 0; s2 < 4; ++s2) {
+      const int s0 = 2 * s2, s1 = 2 * s2 + 1;
+      const float d0 = Ad[s0 >> 2][s0 & 3], d1 = Ad[s1 >> 2][s1 & 3];
+      pa[s2] = pack_bf16(Pw[s0] * Nn[s0 >> 2][s0 & 3], Pw[s1] * Nn[s1 >> 2][s1 & 3]);
+      pn[s2] = pack_bf16(Pw[s0] * d0, Pw[s1] * d1);
+      pm[s2] = pack_bf16(Qw[s0] * d0, Qw[s1] * d1);
     }
-    bf16x8 agf = __builtin_bit_cast(bf16x8, pa[0]);
-    bf16x8 dmf = __builtin_bit_cast(bf16x8, pm), dnf = __builtin_bit_cast(bf16x8, pn);
-    MHFFN_SB();
-    // dV^T[j][c] += dY^T A_g ; dK^T[j][c] += q^T dM ; dU^T[j][c] += q^T dN  (contraction over tokens)
-    u32x4 pm1, pn1;
+    const bf16x8 agf = __builtin_bit_cast(bf16x8, pa);
+    const bf16x8 dmf = __builtin_bit_cast(bf16x8, pm), dnf = __builtin_bit_cast(bf16x8, pn);
+    // dV^T[j][c] += dY^T a ; dK^T[j][c] += q^T dM ; dU^T[j][c] += q^T dN  (contraction over tokens)
 #pragma unroll
-    for (int jb = 0; jb < 4; ++jb) {
-      dV[jb] = mfma32(yT[jb], agf, dV[jb]);
-      dK[jb] = mfma32(qT[jb], dmf, dK[jb]);
-      dU[jb] = mfma32(qT[jb], dnf, dU[jb]);
-      yT[jb] = tile_read_tr(yt, 16 + 4 * g, 32 * jb, lane);   // operands of tokens 16-31
-      qT[jb] = tile_read_tr(qt, 16 + 4 * g, 32 * jb, lane);
-      pm1[jb] = pack_bf16(Qw[8 + 2 * jb] * accA[8 + 2 * jb], Qw[9 + 2 * jb] * accA[9 + 2 * jb]);
-      pn1[jb] = pack_bf16(Pw[8 + 2 * jb] * accA[8 + 2 * jb], Pw[9 + 2 * jb] * accA[9 + 2 * jb]);
-      MHFFN_SB();
+    for (int j = 0; j < 16; ++j) {
+      switch (j + 4) {
+        case 4: MHFFN_W16_LOADX(4); break;   case 5: MHFFN_W16_LOADX(5); break;
+        case 6: MHFFN_W16_LOADX(6); break;   case 7: MHFFN_W16_LOADX(7); break;
+        case 8: MHFFN_W16_LOADX(8); break;   case 9: MHFFN_W16_LOADX(9); break;
+        case 10: MHFFN_W16_LOADX(10); break; case 11: MHFFN_W16_LOADX(11); break;
+        case 12: MHFFN_W16_LOADX(12); break; case 13: MHFFN_W16_LOADX(13); break;
+        case 14: MHFFN_W16_LOADX(14); break; case 15: MHFFN_W16_LOADX(15); break;
+        default: break;
+      }
+      // instructions newer than operand X_j: two per operand still ahead of it
+      switch (j) {
+        case 12: lds_wait<6>(xlo[j], xhi[j]); break;
+        case 13: lds_wait<4>(xlo[j], xhi[j]); break;
+        case 14: lds_wait<2>(xlo[j], xhi[j]); break;
+        case 15: lds_wait<0>(xlo[j], xhi[j]); break;
+        default: lds_wait<8>(xlo[j], xhi[j]); break;
+      }
+      const bf16x8 xt = join_tr(xlo[j], xhi[j]);
+      const int jb = j >> 1;
+      if ((j & 1) == 0) {
+        dV[jb] = mfma16(xt, agf, dV[jb]);
+      } else {
+        dK[jb] = mfma16(xt, dmf, dK[jb]);
+        dU[jb] = mfma16(xt, dnf, dU[jb]);
+      }
     }
-    agf = __builtin_bit_cast(bf16x8, pa[1]);
-    dmf = __builtin_bit_cast(bf16x8, pm1);
-    dnf = __builtin_bit_cast(bf16x8, pn1);
-#pragma unroll
-    for (int jb = 0; jb < 4; ++jb) {
-      dV[jb] = mfma32(yT[jb], agf, dV[jb]);
-      dK[jb] = mfma32(qT[jb], dmf, dK[jb]);
-      dU[jb] = mfma32(qT[jb], dnf, dU[jb]);
-    }
-    if (more) lstore((b + 1) & 1);
-    __syncthreads();
+#undef MHFFN_W16_LOAD
+#undef MHFFN_W16_LOADX
+    // publish block b+1 (its tiles were requested one step ago, the two loads issued at
+    // the top of this step may stay in flight) and retire this stage
+    if (more1) rstore((S + 1) % 3, rnext);
+    asm volatile("" ::: "memory");
+    if (more2) __builtin_amdgcn_s_waitcnt(0x0072);  // vmcnt(2) lgkmcnt(0)
+    else __builtin_amdgcn_s_waitcnt(0x0070);        // vmcnt(0) lgkmcnt(0)
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+  };
+  using C0 = std::integral_constant<int, 0>;
+  using C1 = std::integral_constant<int, 1>;
+  using C2 = std::integral_constant<int, 2>;
+  for (int64_t b = 0; b < nb; b += 3) {
+    step(b, C0{});
+    if (b + 1 < nb) step(b + 1, C1{});
+    if (b + 2 < nb) step(b + 2, C2{});
   }
 
   if (active) {
-    // accumulators are [j][c]: lane = neuron column r, register v = row 32jb + 8(v/4) + 4g + v%4
-    const size_t off = (row0 + r) * kDh + 4 * g;
+    // accumulators are [j][c]: lane = neuron column cn, register v = row 16jb + 4gq + v
+    const size_t off = (row0 + cn) * kDh + 4 * gq;
 #pragma unroll
-    for (int jb = 0; jb < 4; ++jb) {
-#pragma unroll
-      for (int vq = 0; vq < 4; ++vq) {
-        const size_t o = off + 32 * jb + 8 * vq;
-        if (a.dWg) {
-          u32x2 pk;
-          pk[0] = pack_bf16(dK[jb][4 * vq], dK[jb][4 * vq + 1]);
-          pk[1] = pack_bf16(dK[jb][4 * vq + 2], dK[jb][4 * vq + 3]);
-          *reinterpret_cast<u32x2*>(a.dWg + o) = pk;
-        }
-        if (a.dWu) {
-          u32x2 pk;
-          pk[0] = pack_bf16(dU[jb][4 * vq], dU[jb][4 * vq + 1]);
-          pk[1] = pack_bf16(dU[jb][4 * vq + 2], dU[jb][4 * vq + 3]);
-          *reinterpret_cast<u32x2*>(a.dWu + o) = pk;
-        }
-        if (a.dWd) {
-          u32x2 pk;
-          pk[0] = pack_bf16(dV[jb][4 * vq], dV[jb][4 * vq + 1]);
-          pk[1] = pack_bf16(dV[jb][4 * vq + 2], dV[jb][4 * vq + 3]);
-          *reinterpret_cast<u32x2*>(a.dWd + o) = pk;
-        }
+    for (int jb = 0; jb < 8; ++jb) {
+      const size_t o = off + 16 * jb;
+      if (a.dWg) {
+        u32x2 pk = {pack_bf16(dK[jb][0], dK[jb][1]), pack_bf16(dK[jb][2], dK[jb][3])};
+        *reinterpret_cast<u32x2*>(a.dWg + o) = pk;
+      }
+      if (a.dWu) {
+        u32x2 pk = {pack_bf16(dU[jb][0], dU[jb][1]), pack_bf16(dU[jb][2], dU[jb][3])};
+        *reinterpret_cast<u32x2*>(a.dWu + o) = pk;
+      }
+      if (a.dWd) {
+        u32x2 pk = {pack_bf16(dV[jb][0], dV[jb][1]), pack_bf16(dV[jb][2], dV[jb][3])};
+        *reinterpret_cast<u32x2*>(a.dWd + o) = pk;
       }
     }
   }
@@ -786,11 +824,11 @@ int launch_bwd(const Problem& p, int dtype, const void* X, const void* Wg, const
   }
   if (mark(1) != hipSuccess) return (int)hipErrorInvalidHandle;
   if (dWg || dWu || dWd) {
-    const int nblk = p.E * p.de / 32;
-    const int wg_per_head = (nblk + kWgtWaves - 1) / kWgtWaves;
+    const int nblk = p.E * p.de / 16;
+    const int wg_per_head = (nblk + kW16Waves - 1) / kW16Waves;
     a.n_items = (int64_t)wg_per_head * p.H;
-    hipLaunchKernelGGL(bwd_wgt_kernel, dim3((unsigned)xcd_grid_size(a.n_items)), dim3(kWgtThreads),
-                       2 * kWgtStageBytes, stream, a);
+    hipLaunchKernelGGL(bwd_wgt16_kernel, dim3((unsigned)xcd_grid_size(a.n_items)),
+                       dim3(kW16Threads), kW16Stages * kW16Stage, stream, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return (int)e;
   }

@@ -359,19 +359,6 @@ constexpr int kPipeWaves = 8;
 constexpr int kPipeBM = 32 * kPipeWaves;
 constexpr int kPipeMaxSub = (kLdsBytesPerWorkgroup - 3 * kPipeRing) / (kPipeBM * 4);
 
-typedef __attribute__((address_space(1))) const void* gptr_t;
-typedef __attribute__((address_space(3))) void* lptr_t;
-
-// Transposing LDS read issued behind the compiler's back: the compiler would make
-// every such read wait for all direct global->LDS loads in flight (it cannot tell
-// the stages apart).  The caller waits on lgkmcnt itself before using the result.
-template <int OFFSET>
-__device__ __forceinline__ s16x4 lds_read_tr16_untracked(unsigned lds_addr) {
-  s16x4 v;
-  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(v) : "v"(lds_addr), "n"(OFFSET));
-  return v;
-}
-
 __global__ __launch_bounds__(64 * kPipeWaves) void fwd_bf16_pipe_kernel(FwdArgs a) {
   constexpr int BM = kPipeBM;
   constexpr int THREADS = 64 * kPipeWaves;
@@ -403,9 +390,9 @@ __global__ __launch_bounds__(64 * kPipeWaves) void fwd_bf16_pipe_kernel(FwdArgs 
   auto dma = [&](int t, int stage) {
     const size_t off = (size_t)t * (kBI * kDh) + dma_goff;
     unsigned char* dst = smem + stage * kPipeTile + wave_u * 1024;
-    __builtin_amdgcn_global_load_lds((gptr_t)(Kh + off), (lptr_t)dst, 16, 0, 0);
-    __builtin_amdgcn_global_load_lds((gptr_t)(Uh + off), (lptr_t)(dst + kPipeRing), 16, 0, 0);
-    __builtin_amdgcn_global_load_lds((gptr_t)(Vh + off), (lptr_t)(dst + 2 * kPipeRing), 16, 0, 0);
+    global_to_lds_16B(Kh + off, dst);
+    global_to_lds_16B(Uh + off, dst + kPipeRing);
+    global_to_lds_16B(Vh + off, dst + 2 * kPipeRing);
   };
   dma(0, 0);
   if (T > 1) dma(1, 1);
@@ -479,7 +466,7 @@ __global__ __launch_bounds__(64 * kPipeWaves) void fwd_bf16_pipe_kernel(FwdArgs 
     const int li = lane & 15;
     const int row = 4 * g + (li >> 2);
     const int colb = 16 * ((lane >> 4) & 1) + 4 * (li & 3);
-    const unsigned vbase = (unsigned)(uintptr_t)(lptr_t)(smem + 2 * kPipeRing);
+    const unsigned vbase = lds_addr_of(smem + 2 * kPipeRing);
 #pragma unroll
     for (int jb = 0; jb < 4; ++jb) {
       vaddr[jb][0] = vbase + tile_off8(row, 32 * jb + colb);

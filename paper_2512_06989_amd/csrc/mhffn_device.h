@@ -30,6 +30,12 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
+//   v_mfma_f32_16x16x32_bf16  D[16x16] += A[16x32] * B[32x16]   (lane l, i = l % 16, gq = l / 16)
+//     A operand: row i,    k = 8gq .. 8gq+7;   B operand: column i, k = 8gq .. 8gq+7
+//     D / C    : column i, register v (0..3) is row 4gq + v
+__device__ __forceinline__ f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+}
 
 // 1 / (1 + 2^(-x*log2e)): one v_exp_f32 and one v_rcp_f32 (1 ulp each), safe
 // for either sign: exp2 overflows to +inf for very negative x and rcp(inf) = 0.
@@ -88,6 +94,53 @@ __device__ __forceinline__ bf16x8 tile_read_tr(const unsigned char* tile, int r0
   typedef short s16x8 __attribute__((ext_vector_type(8)));
   const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
   return __builtin_bit_cast(bf16x8, both);
+}
+
+// Direct global -> LDS load, 16 bytes per lane: lane l of the wave writes LDS bytes
+// [lds_wave_base + 16 l, +16) with the 16 bytes at its own global address.
+// lds_wave_base must be wave-uniform.  Completion is counted by vmcnt.
+__device__ __forceinline__ void global_to_lds_16B(const void* gptr, void* lds_wave_base) {
+  __builtin_amdgcn_global_load_lds((__attribute__((address_space(1))) const void*)gptr,
+                                   (__attribute__((address_space(3))) void*)lds_wave_base, 16, 0, 0);
+}
+
+// ---- LDS reads issued behind the compiler's back -----------------------------
+// Kernels that stage tiles with direct global->LDS loads read their operands
+// through these: the compiler makes every transposing read wait for all such
+// loads in flight (it cannot tell the stages apart), and once some reads are
+// invisible to its counters, its own waits for the visible ones would be too
+// early or too late to reason about.  The caller counts: LDS operations return in
+// order, so "lgkmcnt(n)" before a use means all but the n newest have landed.
+// lds_wait<N>(regs...) also ties the registers to the wait, so that no consumer
+// can be scheduled ahead of it.
+template <int OFFSET>
+__device__ __forceinline__ bf16x8 lds_read_b128_untracked(unsigned lds_addr) {
+  bf16x8 v;
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(lds_addr), "n"(OFFSET));
+  return v;
+}
+template <int OFFSET>
+__device__ __forceinline__ s16x4 lds_read_tr16_untracked(unsigned lds_addr) {
+  s16x4 v;
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(v) : "v"(lds_addr), "n"(OFFSET));
+  return v;
+}
+template <int N, typename T0>
+__device__ __forceinline__ void lds_wait(T0& a) {
+  asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(a) : "n"(N));
+}
+template <int N, typename T0, typename T1>
+__device__ __forceinline__ void lds_wait(T0& a, T1& b) {
+  asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(a), "+v"(b) : "n"(N));
+}
+__device__ __forceinline__ bf16x8 join_tr(s16x4 lo, s16x4 hi) {
+  typedef short s16x8 __attribute__((ext_vector_type(8)));
+  const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+  return __builtin_bit_cast(bf16x8, both);
+}
+// LDS byte address of a pointer into the workgroup's shared memory
+__device__ __forceinline__ unsigned lds_addr_of(const void* p) {
+  return (unsigned)(uintptr_t)(__attribute__((address_space(3))) const void*)p;
 }
 
 // XCD-aware work distribution.  Workgroups are handed to the 8 XCDs round
