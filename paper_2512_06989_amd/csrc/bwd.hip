@@ -390,7 +390,7 @@ __global__ __launch_bounds__(64 * NW) void bwd_tok_kernel(BwdArgs a) {
 // (the fp32 VALU issues at twice the rate when it can alternate between two
 // waves, and one wave's arithmetic hides behind the other's MFMAs).
 // Eight waves share the q / dY token tiles, which go global -> LDS directly in
-// three stages.  Per 32 tokens and wave:
+// four stages, requested two steps ahead.  Per 32 tokens and wave:
 //   M, N [32 tok][16]  = q K^T, q U^T          16 MFMA   (A: q rows from LDS)
 //   dA   [32 tok][16]  = dY V^T                  8 MFMA
 //   a, dn, dm                                     fp32 VALU, 8 elements per lane
@@ -399,13 +399,37 @@ __global__ __launch_bounds__(64 * NW) void bwd_tok_kernel(BwdArgs a) {
 // p = (0,2,1,3); the transposing reads of lane groups gq = 0,1 (served together)
 // then fall on rows 0-3 and 8-11, whose swizzles differ, and stay free of bank
 // conflicts.  All LDS reads are issued untracked with explicit waits.
-// Rows past N are read from row N-1 (finite data) and carry r = 0, so they add
-// nothing to any gradient.
+// Rows past N are read from row N-1 (finite data) and get r = 0 in the last block,
+// so they add nothing to any gradient.
 // ---------------------------------------------------------------------------
 constexpr int kW16Waves = 8;
 constexpr int kW16Threads = 64 * kW16Waves;
-constexpr int kW16Stage = 2 * kTileBytes + kW16Waves * 32 * 4;  // q tile, dY tile, r per wave: 17 KB
-constexpr int kW16Stages = 3;
+// LDS: one ring per tensor, so that every operand address is a 16-bit immediate offset
+// from a per-lane register: q tiles | dY tiles | r (64 floats per wave, 32 used)
+constexpr int kW16RSlot = kW16Waves * 64 * 4;
+constexpr int kW16Stages = 4;
+constexpr int kW16YRing = kW16Stages * kTileBytes;        // start of the dY ring
+constexpr int kW16RRing = 2 * kW16Stages * kTileBytes;    // start of the r ring
+constexpr int kW16LdsBytes = kW16RRing + kW16Stages * kW16RSlot;
+static_assert(kW16YRing + (kW16Stages - 1) * kTileBytes + 4096 < 65536, "LDS read offsets are 16-bit");
+constexpr int kW16Window = 6;   // operands kept in flight ahead of the one being consumed
+// LDS read instructions behind issue position p of a step's operand stream (see the kernel)
+constexpr int w16_instrs(int p) { return (p >= 12 && p < 28) ? 2 : 1; }
+// last position that has been issued when item c is consumed (item c sits at position c - 4)
+constexpr int w16_issued_before(int c) { return c - 4 + kW16Window > 33 ? 33 : c - 4 + kW16Window; }
+// read instructions issued after item c when it is consumed
+constexpr int w16_pending(int c) {
+  int n = 0;
+  for (int p = c - 4 + 1; p <= w16_issued_before(c); ++p) n += w16_instrs(p);
+  return n;
+}
+template <int B, int E, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (B < E) {
+    f(std::integral_constant<int, B>{});
+    static_for<B + 1, E>(f);
+  }
+}
 
 __global__ __launch_bounds__(kW16Threads) void bwd_wgt16_kernel(BwdArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -446,28 +470,25 @@ __global__ __launch_bounds__(kW16Threads) void bwd_wgt16_kernel(BwdArgs a) {
   const int dcol = h * kDh + (((lane & 15) ^ swz(drow)) << 3);   // element column in X / dY
   const int wave_u = __builtin_amdgcn_readfirstlane(wave);
   const float* Rw = a.Rws + ((size_t)h * a.E + e_wave) * N;
+  // (three loads per wave and block; the r load is a full wave wide, its upper half
+  // repeats the lower one into the unused half of the wave's slot)
   auto dma = [&](int64_t blkidx, int stage) {
     int64_t t = blkidx * 32 + drow;
     t = t < N ? t : N - 1;
-    unsigned char* dst = smem + stage * kW16Stage + wave_u * 1024;
+    int64_t tr = blkidx * 32 + (lane & 31);
+    tr = tr < N ? tr : N - 1;
+    unsigned char* dst = smem + stage * kTileBytes + wave_u * 1024;
     global_to_lds_16B(a.X + t * a.ldx + dcol, dst);
-    global_to_lds_16B(a.dY + t * a.ldy + dcol, dst + kTileBytes);
-  };
-  auto rload = [&](int64_t blkidx) -> float {
-    const int64_t t = blkidx * 32 + (lane & 31);
-    return (lane < 32 && t < N) ? Rw[t] : 0.f;
-  };
-  auto rstore = [&](int stage, float v) {
-    if (lane < 32)
-      reinterpret_cast<float*>(smem + stage * kW16Stage + 2 * kTileBytes)[wave * 32 + lane] = v;
+    global_to_lds_16B(a.dY + t * a.ldy + dcol, dst + kW16YRing);
+    __builtin_amdgcn_global_load_lds(
+        (__attribute__((address_space(1))) const void*)(Rw + tr),
+        (__attribute__((address_space(3))) void*)(smem + kW16RRing + stage * kW16RSlot + wave_u * 256),
+        4, 0, 0);
   };
   const int64_t nb = (N + 31) / 32;
-  {
-    const float r0 = rload(0);
-    dma(0, 0);
-    if (nb > 1) dma(1, 1);
-    rstore(0, r0);
-  }
+  dma(0, 0);
+  if (nb > 1) dma(1, 1);
+  if (nb > 2) dma(2, 2);
   __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0)
   __syncthreads();
 
@@ -482,140 +503,150 @@ __global__ __launch_bounds__(kW16Threads) void bwd_wgt16_kernel(BwdArgs a) {
   unsigned taddr[8];   // transposed operand: rows 4 pg + cn/4 (+16), columns 16jb + 4(cn%4)
 #pragma unroll
   for (int jb = 0; jb < 8; ++jb) taddr[jb] = lbase + tile_off8(4 * pg + (cn >> 2), 16 * jb + 4 * (cn & 3));
-  const unsigned raddr = lbase + 2 * kTileBytes + wave * 128 + 16 * pg;  // r of tokens 4pg.. (+64: 16+4pg..)
+  const unsigned raddr = lbase + kW16RRing + wave * 256 + 16 * pg;  // r of tokens 4pg.. (+64: 16+4pg..)
+
+  // Operand stream of one step, in issue order (position p):
+  //   0..3   Q4..Q7   q rows, tokens 16..31, contraction steps 0..3        (1 LDS read each)
+  //   4..11  Y0..Y7   dY rows                                              (1)
+  //   12..27 X0..X15  transposed windows: dY^T 0, q^T 0, dY^T 1, q^T 1 ..  (2)
+  //   28,29  R', 30..33 Q0'..Q3': r and the first q rows of the NEXT block (1)
+  // and in consumption order (item c): Q0..Q7, Y0..Y7, X0..X15; Q0..Q3 and r were
+  // read by the previous step.  Before item c is consumed everything up to kW16Window
+  // positions ahead of it has been issued, and the wait names exactly the number of
+  // reads issued after it.
+  bf16x8 opc[4];   // Q0..Q3 of the current block
+  f32x4 rvc[2];    // r of this lane's tokens, current block
+  asm volatile("ds_read_b128 %0, %1" : "=v"(rvc[0]) : "v"(raddr));
+  asm volatile("ds_read_b128 %0, %1 offset:64" : "=v"(rvc[1]) : "v"(raddr));
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks) opc[ks] = lds_read_b128_untracked<0>(qaddr[ks]);
 
   auto step = [&](int64_t b, auto S_) {
     constexpr int S = decltype(S_)::value;
-    constexpr int SO = S * kW16Stage;                 // this step's stage
-    const bool more1 = (b + 1 < nb), more2 = (b + 2 < nb);
-    float rnext = 0.f;
-    if (more1) rnext = rload(b + 1);
-    if (more2) dma(b + 2, (S + 2) % 3);
+    constexpr int SN1 = (S + 1) % kW16Stages;               // next block's stage
+    constexpr int SO = S * kTileBytes, SN = SN1 * kTileBytes;   // tile offsets inside a ring
+    const bool more2 = (b + 2 < nb), more3 = (b + 3 < nb);
+    if (b == nb - 1) {   // rows past N were read from row N-1: give them r = 0
+#pragma unroll
+      for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+        for (int v = 0; v < 4; ++v)
+          if (b * 32 + 16 * tb + 4 * pg + v >= N) rvc[tb][v] = 0.f;
+    }
 
-    // ---- operand stream: R, Q0..7, Y0..7, then X0..15 = yT0, qT0, yT1, qT1, ... ---------
-    f32x4 rv[2];
-    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(rv[0]) : "v"(raddr), "n"(SO));
-    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(rv[1]) : "v"(raddr), "n"(SO + 64));
-    bf16x8 op[16];     // b128 operands, index = position in the stream (Q: 0..7, Y: 8..15)
-#define MHFFN_W16_LOAD(i)                                                                       \
-    op[i] = lds_read_b128_untracked<SO + ((i) >= 8 ? kTileBytes : 0) + (((i) >> 2) & 1) * 4096>(qaddr[(i) & 3])
-    MHFFN_W16_LOAD(0); MHFFN_W16_LOAD(1); MHFFN_W16_LOAD(2); MHFFN_W16_LOAD(3);
+    bf16x8 op[16], opn[4];
+    f32x4 rvn[2];
     s16x4 xlo[16], xhi[16];
-    // transposed operand j of the stream: even = dY^T window j/2, odd = q^T window j/2
-#define MHFFN_W16_LOADX(j)                                                                      \
-    xlo[j] = lds_read_tr16_untracked<SO + (((j) & 1) ? 0 : kTileBytes)>(taddr[(j) >> 1]);       \
-    xhi[j] = lds_read_tr16_untracked<SO + (((j) & 1) ? 0 : kTileBytes) + 4096>(taddr[(j) >> 1])
+    auto issue = [&](auto P_) {
+      constexpr int P = decltype(P_)::value;
+      if constexpr (P < 4) {
+        op[4 + P] = lds_read_b128_untracked<SO + 4096>(qaddr[P]);
+      } else if constexpr (P < 12) {
+        op[4 + P] = lds_read_b128_untracked<kW16YRing + SO + ((P - 4) >> 2) * 4096>(qaddr[(P - 4) & 3]);
+      } else if constexpr (P < 28) {
+        constexpr int J = P - 12, TO = SO + ((J & 1) ? 0 : kW16YRing);
+        xlo[J] = lds_read_tr16_untracked<TO>(taddr[J >> 1]);
+        xhi[J] = lds_read_tr16_untracked<TO + 4096>(taddr[J >> 1]);
+      } else if constexpr (P == 28) {
+        asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(rvn[0]) : "v"(raddr), "n"(SN1 * kW16RSlot));
+      } else if constexpr (P == 29) {
+        asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(rvn[1]) : "v"(raddr), "n"(SN1 * kW16RSlot + 64));
+      } else {
+        opn[P - 30] = lds_read_b128_untracked<SN>(qaddr[P - 30]);
+      }
+    };
+    // issue what item C needs to have in flight, beyond what item C-1 already required
+    auto advance = [&](auto C_) {
+      constexpr int C = decltype(C_)::value;
+      constexpr int lo = (C == 0) ? 0 : w16_issued_before(C - 1) + 1;
+      static_for<lo, w16_issued_before(C) + 1>(issue);
+    };
 
     f32x4 M[2], Nn[2], Ad[2];
 #pragma unroll
     for (int tb = 0; tb < 2; ++tb) { M[tb] = f32x4{0, 0, 0, 0}; Nn[tb] = M[tb]; Ad[tb] = M[tb]; }
-    // gate / up products; four loads stay ahead of the one being consumed
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      switch (i + 4) {
-        case 4: MHFFN_W16_LOAD(4); break;   case 5: MHFFN_W16_LOAD(5); break;
-        case 6: MHFFN_W16_LOAD(6); break;   case 7: MHFFN_W16_LOAD(7); break;
-        case 8: MHFFN_W16_LOAD(8); break;   case 9: MHFFN_W16_LOAD(9); break;
-        case 10: MHFFN_W16_LOAD(10); break; default: MHFFN_W16_LOAD(11); break;
-      }
-      lds_wait<4>(op[i]);
-      const int tb = i >> 2, ks = i & 3;
-      M[tb] = mfma16(op[i], Kf[ks], M[tb]);
-      Nn[tb] = mfma16(op[i], Uf[ks], Nn[tb]);
-    }
+    // gate / up products
+    static_for<0, 8>([&](auto C_) {
+      constexpr int C = decltype(C_)::value;
+      advance(C_);
+      bf16x8& o = (C < 4) ? opc[C & 3] : op[C];
+      lds_wait<w16_pending(C)>(o);
+      M[C >> 2] = mfma16(o, Kf[C & 3], M[C >> 2]);
+      Nn[C >> 2] = mfma16(o, Uf[C & 3], Nn[C >> 2]);
+    });
     // dA products, with everything that needs only m, n, r computed under them
     float Pw[8], Qw[8];   // r silu(m)  and  r n silu'(m)
-    u32x4 pa;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      switch (i + 4) {
-        case 4: MHFFN_W16_LOAD(12); break;  case 5: MHFFN_W16_LOAD(13); break;
-        case 6: MHFFN_W16_LOAD(14); break;  case 7: MHFFN_W16_LOAD(15); break;
-        case 8: MHFFN_W16_LOADX(0); break;  case 9: MHFFN_W16_LOADX(1); break;
-        case 10: MHFFN_W16_LOADX(2); break; default: MHFFN_W16_LOADX(3); break;
-      }
-      // instructions newer than operand Y_i: 4 for i < 4, then 5, 6, 7, 8
-      switch (i) {
-        case 0: case 1: case 2: case 3: lds_wait<4>(op[8 + i]); break;
-        case 4: lds_wait<5>(op[8 + i]); break;
-        case 5: lds_wait<6>(op[8 + i]); break;
-        case 6: lds_wait<7>(op[8 + i]); break;
-        default: lds_wait<8>(op[8 + i]); break;
-      }
-      const int tb = i >> 2, ks = i & 3;
-      Ad[tb] = mfma16(op[8 + i], Vf[ks], Ad[tb]);
-      {
-        const int v = i & 3;
-        const float rwv = rv[tb][v];
-        const float m = M[tb][v], n = Nn[tb][v];
-        const float t = __builtin_amdgcn_exp2f(-MHFFN_LOG2E * m);
-        const float sg = __builtin_amdgcn_rcpf(1.0f + t);
-        const float sw = rwv * sg;
-        const float x = (1.0f + m) - m * sg;   // silu'(m) = sg (1 + m - silu(m))
-        Pw[i] = m * sw;
-        Qw[i] = (n * sw) * x;
-      }
-    }
+    float Aw[8];          // r silu(m) n
+    static_for<8, 16>([&](auto C_) {
+      constexpr int C = decltype(C_)::value, I = C - 8, TB = I >> 2, V = I & 3;
+      advance(C_);
+      lds_wait<w16_pending(C)>(op[C]);
+      Ad[TB] = mfma16(op[C], Vf[I & 3], Ad[TB]);
+      const float rwv = rvc[TB][V];
+      const float m = M[TB][V], n = Nn[TB][V];
+      const float t = __builtin_amdgcn_exp2f(-MHFFN_LOG2E * m);
+      const float sg = __builtin_amdgcn_rcpf(1.0f + t);
+      const float sw = rwv * sg;
+      const float x = (1.0f + m) - m * sg;   // silu'(m) = sg (1 + m - silu(m))
+      Pw[I] = m * sw;
+      Qw[I] = (n * sw) * x;
+      Aw[I] = Pw[I] * n;
+    });
     // tokens of this lane: k-slot s = 4tb + v of every gradient product
-    u32x4 pm, pn;
+    u32x4 pa, pm, pn;
 #pragma unroll
     for (int s2 = 0; s2 < 4; ++s2) {
       const int s0 = 2 * s2, s1 = 2 * s2 + 1;
       const float d0 = Ad[s0 >> 2][s0 & 3], d1 = Ad[s1 >> 2][s1 & 3];
-      pa[s2] = pack_bf16(Pw[s0] * Nn[s0 >> 2][s0 & 3], Pw[s1] * Nn[s1 >> 2][s1 & 3]);
+      pa[s2] = pack_bf16(Aw[s0], Aw[s1]);
       pn[s2] = pack_bf16(Pw[s0] * d0, Pw[s1] * d1);
       pm[s2] = pack_bf16(Qw[s0] * d0, Qw[s1] * d1);
     }
     const bf16x8 agf = __builtin_bit_cast(bf16x8, pa);
     const bf16x8 dmf = __builtin_bit_cast(bf16x8, pm), dnf = __builtin_bit_cast(bf16x8, pn);
-    // dV^T[j][c] += dY^T a ; dK^T[j][c] += q^T dM ; dU^T[j][c] += q^T dN  (contraction over tokens)
-#pragma unroll
-    for (int j = 0; j < 16; ++j) {
-      switch (j + 4) {
-        case 4: MHFFN_W16_LOADX(4); break;   case 5: MHFFN_W16_LOADX(5); break;
-        case 6: MHFFN_W16_LOADX(6); break;   case 7: MHFFN_W16_LOADX(7); break;
-        case 8: MHFFN_W16_LOADX(8); break;   case 9: MHFFN_W16_LOADX(9); break;
-        case 10: MHFFN_W16_LOADX(10); break; case 11: MHFFN_W16_LOADX(11); break;
-        case 12: MHFFN_W16_LOADX(12); break; case 13: MHFFN_W16_LOADX(13); break;
-        case 14: MHFFN_W16_LOADX(14); break; case 15: MHFFN_W16_LOADX(15); break;
-        default: break;
-      }
-      // instructions newer than operand X_j: two per operand still ahead of it
-      switch (j) {
-        case 12: lds_wait<6>(xlo[j], xhi[j]); break;
-        case 13: lds_wait<4>(xlo[j], xhi[j]); break;
-        case 14: lds_wait<2>(xlo[j], xhi[j]); break;
-        case 15: lds_wait<0>(xlo[j], xhi[j]); break;
-        default: lds_wait<8>(xlo[j], xhi[j]); break;
-      }
-      const bf16x8 xt = join_tr(xlo[j], xhi[j]);
-      const int jb = j >> 1;
-      if ((j & 1) == 0) {
-        dV[jb] = mfma16(xt, agf, dV[jb]);
-      } else {
-        dK[jb] = mfma16(xt, dmf, dK[jb]);
-        dU[jb] = mfma16(xt, dnf, dU[jb]);
-      }
-    }
-#undef MHFFN_W16_LOAD
-#undef MHFFN_W16_LOADX
-    // publish block b+1 (its tiles were requested one step ago, the two loads issued at
-    // the top of this step may stay in flight) and retire this stage
-    if (more1) rstore((S + 1) % 3, rnext);
+
+    // Barrier: the next block's tiles (requested two steps ago) and r have landed for every
+    // wave, and every wave is done with the previous block's stage, which the request below
+    // overwrites.  Bare barrier, no LDS wait: transposed operands are already in flight.
     asm volatile("" ::: "memory");
-    if (more2) __builtin_amdgcn_s_waitcnt(0x0072);  // vmcnt(2) lgkmcnt(0)
-    else __builtin_amdgcn_s_waitcnt(0x0070);        // vmcnt(0) lgkmcnt(0)
+    if (more2) __builtin_amdgcn_s_waitcnt(0x0F73);  // vmcnt(3): only the newest request may be pending
+    else __builtin_amdgcn_s_waitcnt(0x0F70);        // vmcnt(0)
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
+    if (more3) dma(b + 3, (S + 3) % kW16Stages);
+
+    // dV^T[j][c] += dY^T a ; dK^T[j][c] += q^T dM ; dU^T[j][c] += q^T dN  (contraction over tokens)
+    static_for<16, 32>([&](auto C_) {
+      constexpr int C = decltype(C_)::value, J = C - 16, JB = J >> 1;
+      advance(C_);
+      lds_wait<w16_pending(C)>(xlo[J], xhi[J]);
+      const bf16x8 xt = join_tr(xlo[J], xhi[J]);
+      if constexpr ((J & 1) == 0) {
+        dV[JB] = mfma16(xt, agf, dV[JB]);
+      } else {
+        dK[JB] = mfma16(xt, dmf, dK[JB]);
+        dU[JB] = mfma16(xt, dnf, dU[JB]);
+      }
+    });
+    // the reads of the next block's first operands are in flight; hand them over
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) opc[ks] = opn[ks];
+    rvc[0] = rvn[0];
+    rvc[1] = rvn[1];
   };
   using C0 = std::integral_constant<int, 0>;
   using C1 = std::integral_constant<int, 1>;
   using C2 = std::integral_constant<int, 2>;
-  for (int64_t b = 0; b < nb; b += 3) {
+  using C3 = std::integral_constant<int, 3>;
+  for (int64_t b = 0; b < nb; b += 4) {
     step(b, C0{});
     if (b + 1 < nb) step(b + 1, C1{});
     if (b + 2 < nb) step(b + 2, C2{});
+    if (b + 3 < nb) step(b + 3, C3{});
   }
+  // drain the reads issued for a block that does not exist
+  asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(opc[0]), "+v"(opc[1]), "+v"(opc[2]), "+v"(opc[3]),
+                                        "+v"(rvc[0]), "+v"(rvc[1]));
 
   if (active) {
     // accumulators are [j][c]: lane = neuron column cn, register v = row 16jb + 4gq + v
@@ -827,8 +858,16 @@ int launch_bwd(const Problem& p, int dtype, const void* X, const void* Wg, const
     const int nblk = p.E * p.de / 16;
     const int wg_per_head = (nblk + kW16Waves - 1) / kW16Waves;
     a.n_items = (int64_t)wg_per_head * p.H;
+    static bool wgt_attr_set = false;
+    if (!wgt_attr_set) {
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&bwd_wgt16_kernel),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize,
+                                         (int)kLdsBytesPerWorkgroup);
+      if (e != hipSuccess) return (int)e;
+      wgt_attr_set = true;
+    }
     hipLaunchKernelGGL(bwd_wgt16_kernel, dim3((unsigned)xcd_grid_size(a.n_items)),
-                       dim3(kW16Threads), kW16Stages * kW16Stage, stream, a);
+                       dim3(kW16Threads), kW16LdsBytes, stream, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return (int)e;
   }
