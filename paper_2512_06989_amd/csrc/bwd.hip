@@ -477,20 +477,35 @@ __global__ __launch_bounds__(kW16Threads) void bwd_wgt16_kernel(BwdArgs a) {
   const float* Rw = a.Rws + ((size_t)h * a.E + e_wave) * N;
   // (three loads per wave and block; the r load is a full wave wide, its upper half
   // repeats the lower one into the unused half of the wave's slot)
+  // Blocks are requested in order, each once: the per-lane source pointers just advance.
+  const int64_t nb = (N + 31) / 32;
+  const int rrow = (lane & 16) + rho(lane & 15);   // r is kept in MFMA row order
+  const uint16_t* xsrc = a.X + drow * a.ldx + dcol;
+  const uint16_t* ysrc = a.dY + drow * a.ldy + dcol;
+  const float* rsrc = Rw + rrow;
   auto dma = [&](int64_t blkidx, int stage) {
-    int64_t t = blkidx * 32 + drow;
-    t = t < N ? t : N - 1;
-    int64_t tr = blkidx * 32 + (lane & 16) + rho(lane & 15);   // r is kept in MFMA row order
-    tr = tr < N ? tr : N - 1;
+    const uint16_t* xs = xsrc;
+    const uint16_t* ys = ysrc;
+    const float* rs = rsrc;
+    if (blkidx == nb - 1) {   // the last block may be ragged: rows past N read row N-1
+      int64_t t = blkidx * 32 + drow, tr = blkidx * 32 + rrow;
+      t = t < N ? t : N - 1;
+      tr = tr < N ? tr : N - 1;
+      xs = a.X + t * a.ldx + dcol;
+      ys = a.dY + t * a.ldy + dcol;
+      rs = Rw + tr;
+    }
     unsigned char* dst = smem + stage * kTileBytes + wave_u * 1024;
-    global_to_lds_16B(a.X + t * a.ldx + dcol, dst);
-    global_to_lds_16B(a.dY + t * a.ldy + dcol, dst + kW16YRing);
+    global_to_lds_16B(xs, dst);
+    global_to_lds_16B(ys, dst + kW16YRing);
     __builtin_amdgcn_global_load_lds(
-        (__attribute__((address_space(1))) const void*)(Rw + tr),
+        (__attribute__((address_space(1))) const void*)rs,
         (__attribute__((address_space(3))) void*)(smem + kW16RRing + stage * kW16RSlot + wave_u * 256),
         4, 0, 0);
+    xsrc += 32 * a.ldx;
+    ysrc += 32 * a.ldy;
+    rsrc += 32;
   };
-  const int64_t nb = (N + 31) / 32;
   dma(0, 0);
   if (nb > 1) dma(1, 1);
   if (nb > 2) dma(2, 2);
