@@ -192,15 +192,17 @@ def main():
     # algorithmic contraction units per launch: recompute inside the weight-major
     # kernel is not credited (forward 3; token-major M,N,dA,dX,dX = 5; weight-major dK,dU,dV = 3)
     units = {"fwd": 3.0, "bwd_tok": 5.0, "bwd_wgt": 3.0, "bwd_route": 0.0}
-    kernel_names = {"fwd": "fwd_bf16_kernel", "bwd_tok": "bwd_tok_kernel", "bwd_wgt": "bwd_wgt_kernel",
-                    "bwd_route": "bwd_route_*"}
+    # up to 64 sub-networks the forward runs the pipelined kernel
+    fwd_pipelined = w.n_sub <= 64
+    kernel_names = {"fwd": "fwd_bf16_pipe_kernel" if fwd_pipelined else "fwd_bf16_kernel",
+                    "bwd_tok": "bwd_tok_kernel", "bwd_wgt": "bwd_wgt16_kernel", "bwd_route": "bwd_route_*"}
 
     # HBM bytes per launch measured with rocprofv3 (FETCH_SIZE + WRITE_SIZE, each scaled by
     # what the counter reads for a 256 MiB copy); from profiles/mhffn_fwd_bwd_1p3b.md and
     # profiles/mhffn_fwd_sweep_1p3b.md.  Only valid for the workload they were taken on.
     measured_traffic = {}
     if w.name == "1p3b_fwdbwd" and not args.forward_only:
-        measured_traffic = {"fwd": 273.6e6, "bwd_tok": 496.6e6, "bwd_wgt": 453.5e6}
+        measured_traffic = {"fwd": 273.6e6, "bwd_tok": 496.3e6, "bwd_wgt": 453.1e6}
 
     def roof(k):
         if k == "fwd" and hbm_bound:

@@ -369,14 +369,20 @@ __global__ __launch_bounds__(64 * kPipeWaves) void fwd_bf16_pipe_kernel(FwdArgs 
   const int r = lane & 31, g = lane >> 5;
   const int64_t item = xcd_work_item(blockIdx.x, a.n_items);
   if (item >= a.n_items) return;  // whole workgroup leaves together
-  const int h = (int)(item / a.n_tiles);
-  const int64_t tile_tok0 = (item % a.n_tiles) * BM;
+  // item = (head * n_tiles + token tile) * n_split + split, as in fwd_bf16_kernel
+  const int split = (int)(item % a.n_split);
+  const int64_t ht = item / a.n_split;
+  const int h = (int)(ht / a.n_tiles);
+  const int64_t tile_tok0 = (ht % a.n_tiles) * BM;
   const int wtok = wave * 32;
   const int E = a.E;
+  // a wave whose 32 tokens all lie past N only helps with staging and barriers
+  const bool active = tile_tok0 + wtok < a.N;
 
   const int tiles_per_sub = a.de / kBI;
-  const int T = E * tiles_per_sub;
-  const size_t head_off = (size_t)h * E * a.de * kDh;
+  const int t_begin = split * a.tiles_per_split;   // this workgroup's share of the tiles
+  const int T = min(E * tiles_per_sub, t_begin + a.tiles_per_split) - t_begin;
+  const size_t head_off = ((size_t)h * E * a.de + (size_t)t_begin * kBI) * kDh;
   const uint16_t* Kh = a.Wg + head_off;
   const uint16_t* Uh = a.Wu + head_off;
   const uint16_t* Vh = a.Wd + head_off;
@@ -428,7 +434,7 @@ __global__ __launch_bounds__(64 * kPipeWaves) void fwd_bf16_pipe_kernel(FwdArgs 
     }
     __syncthreads();
     float zsum = 0.f, inv = 0.f;
-    for (int pass = 0; pass < 2; ++pass) {   // pass 0: Z = sum_e sigmoid(p_e); pass 1: r_e
+    for (int pass = 0; pass < (active ? 2 : 0); ++pass) {   // pass 0: Z = sum_e sigmoid(p_e); pass 1: r_e
       for (int eb = 0; eb < EB; ++eb) {
         f32x16 acc = {0};
 #pragma unroll
@@ -481,21 +487,23 @@ __global__ __launch_bounds__(64 * kPipeWaves) void fwd_bf16_pipe_kernel(FwdArgs 
 
   // gate/up products of tile 0
 #pragma unroll
-  for (int ks = 0; ks < 8; ++ks) {
+  for (int ks = 0; ks < (active ? 8 : 0); ++ks) {
     const bf16x8 ak = *reinterpret_cast<const bf16x8*>(smem + kaddr[ks]);
     const bf16x8 au = *reinterpret_cast<const bf16x8*>(smem + kPipeRing + kaddr[ks]);
     if (ks == 0) { accM[0] = mfma32(ak, q[0], f32x16{0}); accN[0] = mfma32(au, q[0], f32x16{0}); }
     else { accM[0] = mfma32(ak, q[ks], accM[0]); accN[0] = mfma32(au, q[ks], accN[0]); }
   }
 
-  const float* rs_ptr = Rs + wtok + r;  // 1/r of the current sub-network for this lane's token
-  int sub_cnt = 0;
+  // 1/r of the current sub-network for this lane's token
+  const float* rs_ptr = Rs + (t_begin / tiles_per_sub) * BM + wtok + r;
+  int sub_cnt = t_begin % tiles_per_sub;
 
   // step i: tile i sits in stage S with its gate/up accumulators in set P
   auto step = [&](int i, auto S_, auto P_) {
     constexpr int S = decltype(S_)::value, P = decltype(P_)::value, Q = 1 - P;
     const bool more = (i + 3 < T);
     if (more) dma(i + 3, (S + 3) % 4);
+    if (active) {
     const float rw = *rs_ptr;
     if (++sub_cnt == tiles_per_sub) { sub_cnt = 0; rs_ptr += BM; }
 
@@ -604,6 +612,7 @@ __global__ __launch_bounds__(64 * kPipeWaves) void fwd_bf16_pipe_kernel(FwdArgs 
       const s16x8 both = __builtin_shufflevector(wlo[jb], whi[jb], 0, 1, 2, 3, 4, 5, 6, 7);
       O[jb] = mfma32(__builtin_bit_cast(bf16x8, both), b1, O[jb]);
     }
+    }  // active
     // Publish tile i+2 (requested one step ago; the three loads issued at the top of this
     // step may stay in flight) and retire stage S.  A bare barrier: __syncthreads() would
     // wait for every load in flight.
@@ -624,8 +633,22 @@ __global__ __launch_bounds__(64 * kPipeWaves) void fwd_bf16_pipe_kernel(FwdArgs 
     if (i + 3 < T) step(i + 3, C3{}, C1{});
   }
 
-  // ---- store Y (concat_H: head h owns columns h*d_h ..) --------------------
   const int64_t tok = tile_tok0 + wtok + r;
+  // ---- split runs leave an fp32 partial; fwd_bf16_reduce_kernel sums them ---
+  if (a.n_split > 1) {
+    if (tok < a.N) {
+      float* dst = a.P + (((size_t)split * a.N + tok) * a.H + h) * kDh + 4 * g;
+#pragma unroll
+      for (int jb = 0; jb < 4; ++jb)
+#pragma unroll
+        for (int vq = 0; vq < 4; ++vq) {
+          f32x4 o = {O[jb][4 * vq], O[jb][4 * vq + 1], O[jb][4 * vq + 2], O[jb][4 * vq + 3]};
+          *reinterpret_cast<f32x4*>(dst + 32 * jb + 8 * vq) = o;
+        }
+    }
+    return;
+  }
+  // ---- store Y (concat_H: head h owns columns h*d_h ..) --------------------
   if (tok < a.N) {
     uint16_t* dst = a.Y + tok * a.ldy + h * kDh + 4 * g;
 #pragma unroll
@@ -657,15 +680,24 @@ __global__ void fwd_bf16_reduce_kernel(FwdArgs a) {
 }
 
 // How the intermediate dimension is shared out when the token tiles alone
-// cannot fill the chip (decode / short prefill): aim for >= 2 workgroups per CU.
-struct SplitPlan { int bm, n_split, tiles_per_split; };
+// cannot fill the chip (decode / short prefill).  The pipelined kernel (one workgroup of
+// 256 tokens per CU) is split down to about one workgroup per CU: with few tokens it
+// is a weight-streaming kernel, and its deep ring of direct loads is what keeps
+// enough bytes in flight.  The older kernel (more than 64 sub-networks) aims for
+// two smaller workgroups per CU.
+struct SplitPlan { int bm, n_split, tiles_per_split; bool pipe; };
 SplitPlan plan_split(const Problem& p) {
   SplitPlan s;
-  s.bm = (p.N <= 128) ? 64 : 256;
+  s.pipe = p.E <= kPipeMaxSub;
+  s.bm = (!s.pipe && p.N <= 128) ? 64 : 256;
   const int64_t base = ((p.N + s.bm - 1) / s.bm) * p.H;
   const int T = p.E * (p.de / kBI);
   int want = 1;
-  if (base < 384) want = (int)((512 + base - 1) / base);
+  if (s.pipe) {
+    if (base <= 128) want = (int)(256 / base);
+  } else if (base < 384) {
+    want = (int)((512 + base - 1) / base);
+  }
   if (want > T / 2) want = T / 2 > 0 ? T / 2 : 1;   // at least two tiles per split
   s.tiles_per_split = (T + want - 1) / want;
   s.n_split = (T + s.tiles_per_split - 1) / s.tiles_per_split;
@@ -698,11 +730,11 @@ int launch_variant(const Problem& p, FwdArgs a, const SplitPlan& sp, hipStream_t
   return (int)hipGetLastError();
 }
 
-int launch_pipe(const Problem& p, FwdArgs a, hipStream_t stream) {
+int launch_pipe(const Problem& p, FwdArgs a, const SplitPlan& sp, hipStream_t stream) {
   a.n_tiles = (p.N + kPipeBM - 1) / kPipeBM;
-  a.n_split = 1;
-  a.tiles_per_split = p.E * (p.de / kBI);
-  a.n_items = a.n_tiles * p.H;
+  a.n_split = sp.n_split;
+  a.tiles_per_split = sp.tiles_per_split;
+  a.n_items = a.n_tiles * p.H * sp.n_split;
   const size_t lds = (size_t)3 * kPipeRing + (size_t)p.E * kPipeBM * sizeof(float);
   static bool attr_set = false;
   if (!attr_set) {
@@ -714,6 +746,11 @@ int launch_pipe(const Problem& p, FwdArgs a, hipStream_t stream) {
   }
   hipLaunchKernelGGL(fwd_bf16_pipe_kernel, dim3((unsigned)xcd_grid_size(a.n_items)),
                      dim3(64 * kPipeWaves), lds, stream, a);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess || sp.n_split == 1) return (int)e;
+  const int64_t n4 = p.N * p.H * kDh / 4;
+  hipLaunchKernelGGL(fwd_bf16_reduce_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0,
+                     stream, a);
   return (int)hipGetLastError();
 }
 
@@ -742,8 +779,8 @@ int launch_fwd_bf16(const Problem& p, const void* X, const void* Wg, const void*
   hipStream_t st = static_cast<hipStream_t>(stream);
   // 8 waves x 32 tokens (two waves per SIMD) measured 25% faster than 4 waves x
   // 64 tokens at the 1.3B shape: the second wave hides LDS and barrier latency.
+  if (sp.pipe) return launch_pipe(p, a, sp, st);
   if (sp.bm == 64) return launch_variant<1, 2>(p, a, sp, st);
-  if (sp.n_split == 1 && p.E <= kPipeMaxSub) return launch_pipe(p, a, st);
   return launch_variant<1, 8>(p, a, sp, st);
 }
 
