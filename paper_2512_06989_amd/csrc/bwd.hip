@@ -38,6 +38,14 @@ namespace {
 constexpr int kDh = 128;
 constexpr int kTileBytes = 32 * kDh * 2;  // 8 KB
 
+template <int B, int E, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (B < E) {
+    f(std::integral_constant<int, B>{});
+    static_for<B + 1, E>(f);
+  }
+}
+
 struct BwdArgs {
   const uint16_t* X;
   const uint16_t* Wg;
@@ -231,18 +239,29 @@ __global__ __launch_bounds__(64 * NW) void bwd_tok_kernel(BwdArgs a) {
     f32x16 accM[TB], accN[TB], accA[TB];
 #pragma unroll
     for (int tb = 0; tb < TB; ++tb) { accM[tb] = f32x16{0}; accN[tb] = f32x16{0}; accA[tb] = f32x16{0}; }
+    // K/U/V row operands, item c = 3 ks + {0: K, 1: U, 2: V}: each is read six items (two
+    // contraction steps) ahead of its use, with counted waits.  Left to the compiler, each
+    // step's three reads are issued and waited for back to back, and every step pays the
+    // full LDS latency.
+    {
+      const unsigned sto = lds_addr_of(st);
+      bf16x8 op[24];
+      auto issue = [&](auto C_) {
+        constexpr int c = decltype(C_)::value, ks = c / 3, which = c % 3;
+        op[c] = lds_read_b128_untracked<which * kTileBytes>(sto + tile_off(r, 2 * ks + g));
+      };
+      static_for<0, 6>(issue);
+      static_for<0, 24>([&](auto C_) {
+        constexpr int c = decltype(C_)::value, ks = c / 3, which = c % 3;
+        if constexpr (c + 6 < 24) issue(std::integral_constant<int, c + 6>{});
+        lds_wait<(23 - c) < 6 ? (23 - c) : 6>(op[c]);
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) {
-      const int off = tile_off(r, 2 * ks + g);
-      const bf16x8 ak = *reinterpret_cast<const bf16x8*>(st + off);
-      const bf16x8 au = *reinterpret_cast<const bf16x8*>(st + kTileBytes + off);
-      const bf16x8 av = *reinterpret_cast<const bf16x8*>(st + 2 * kTileBytes + off);
-#pragma unroll
-      for (int tb = 0; tb < TB; ++tb) {
-        accM[tb] = mfma32(ak, q[tb][ks], accM[tb]);
-        accN[tb] = mfma32(au, q[tb][ks], accN[tb]);
-        accA[tb] = mfma32(av, dy[tb][ks], accA[tb]);
-      }
+        for (int tb = 0; tb < TB; ++tb) {
+          if constexpr (which == 0) accM[tb] = mfma32(op[c], q[tb][ks], accM[tb]);
+          if constexpr (which == 1) accN[tb] = mfma32(op[c], q[tb][ks], accN[tb]);
+          if constexpr (which == 2) accA[tb] = mfma32(op[c], dy[tb][ks], accA[tb]);
+        }
+      });
     }
     bf16x8 dmf[TB][2], dnf[TB][2];
 #pragma unroll
@@ -427,13 +446,7 @@ constexpr int w16_pending(int c) {
   for (int p = c - 4 + 1; p <= w16_issued_before(c); ++p) n += w16_instrs(p);
   return n;
 }
-template <int B, int E, typename F>
-__device__ __forceinline__ void static_for(F&& f) {
-  if constexpr (B < E) {
-    f(std::integral_constant<int, B>{});
-    static_for<B + 1, E>(f);
-  }
-}
+
 
 __global__ __launch_bounds__(kW16Threads) void bwd_wgt16_kernel(BwdArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
