@@ -42,7 +42,10 @@ def check_all(got, ref, tol, single_subnetwork=False):
 
 @pytest.mark.parametrize("N,H,E,de", [(256, 2, 4, 128), (1, 1, 1, 32), (63, 2, 3, 64),
                                        (65, 1, 5, 32), (257, 3, 2, 96), (1000, 2, 33, 32),
-                                       (700, 1, 7, 160)])
+                                       (700, 1, 7, 160),
+                                       # many sub-networks (three 32-wide blocks of gating logits),
+                                       # token counts that leave the last 32-token block ragged
+                                       (300, 1, 80, 32), (97, 2, 96, 32)])
 def test_bf16_small_shapes_params_mode(N, H, E, de):
     w = small_workload("bwd_small", N, H, E, de, "bf16", backward=True)
     d, got = run_backward(w, seed=N + E)

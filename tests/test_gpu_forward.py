@@ -45,7 +45,9 @@ def test_f32_ragged_and_generic_shapes(N):
 
 @pytest.mark.parametrize("N,H,E,de", [(256, 2, 4, 128), (1, 1, 1, 32), (63, 2, 3, 64),
                                        (65, 1, 5, 32), (257, 3, 2, 96), (1000, 2, 33, 32),
-                                       (300, 1, 64, 32)])
+                                       (300, 1, 64, 32),
+                                       # more than 64 sub-networks: the non-pipelined kernels
+                                       (300, 1, 80, 32), (100, 2, 96, 32), (1500, 1, 70, 64)])
 def test_bf16_small_shapes_params_mode(N, H, E, de):
     w = small_workload("bf16_small", N, H, E, de, "bf16")
     d, Y = run_forward(w, seed=N + E)
