@@ -236,6 +236,7 @@ __global__ __launch_bounds__(64 * NW) void bwd_tok_kernel(BwdArgs a) {
     }
     const unsigned char* st = stage_base + (t & 1) * kTokStageBytes;
 
+    __builtin_amdgcn_s_setprio(1);
     f32x16 accM[TB], accN[TB], accA[TB];
 #pragma unroll
     for (int tb = 0; tb < TB; ++tb) { accM[tb] = f32x16{0}; accN[tb] = f32x16{0}; accA[tb] = f32x16{0}; }
@@ -290,6 +291,7 @@ __global__ __launch_bounds__(64 * NW) void bwd_tok_kernel(BwdArgs a) {
         dnf[tb][t2] = __builtin_bit_cast(bf16x8, pn);
       }
     }
+    __builtin_amdgcn_s_setprio(0);
 #pragma unroll
     for (int t2 = 0; t2 < 2; ++t2) {
 #pragma unroll
@@ -593,6 +595,7 @@ __global__ __launch_bounds__(kW16Threads) void bwd_wgt16_kernel(BwdArgs a) {
       static_for<lo, w16_issued_before(C) + 1>(issue);
     };
 
+    __builtin_amdgcn_s_setprio(1);
     f32x4 M[2], Nn[2], Ad[2];
 #pragma unroll
     for (int tb = 0; tb < 2; ++tb) { M[tb] = f32x4{0, 0, 0, 0}; Nn[tb] = M[tb]; Ad[tb] = M[tb]; }
@@ -645,6 +648,7 @@ __global__ __launch_bounds__(kW16Threads) void bwd_wgt16_kernel(BwdArgs a) {
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
     if (more3) dma(b + 3, (S + 3) % kW16Stages);
+    __builtin_amdgcn_s_setprio(0);
 
     // dV^T[j][c] += dY^T a ; dK^T[j][c] += q^T dM ; dU^T[j][c] += q^T dN  (contraction over tokens)
     static_for<16, 32>([&](auto C_) {

@@ -504,6 +504,9 @@ __global__ __launch_bounds__(64 * kPipeWaves) void fwd_bf16_pipe_kernel(FwdArgs 
     const bool more = (i + 3 < T);
     if (more) dma(i + 3, (S + 3) % 4);
     if (active) {
+    // the wave that is further behind in its step gets the issue slots: both waves of a
+    // SIMD then reach the barrier closer together (measured: 2 % faster)
+    __builtin_amdgcn_s_setprio(1);
     const float rw = *rs_ptr;
     if (++sub_cnt == tiles_per_sub) { sub_cnt = 0; rs_ptr += BM; }
 
@@ -586,6 +589,7 @@ __global__ __launch_bounds__(64 * kPipeWaves) void fwd_bf16_pipe_kernel(FwdArgs 
       MHFFN_SB();
     }
 
+    __builtin_amdgcn_s_setprio(0);
     // down projection of tile i.  Only the 16 untracked reads can be outstanding here
     // (every tracked read of this step has been consumed above, the next ones follow the
     // barrier), so lgkmcnt(8) means: the first eight have returned.
