@@ -92,7 +92,8 @@ typedef struct {
  * Shape support.
  *   bf16: the fused kernels need d_head == 128, d_sub % 32 == 0 and
  *         n_sub <= 96; other shapes return MHFFN_ERR_UNSUPPORTED.
- *   fp32: the fused kernels take d_head % 4 == 0, d_head <= 256, any n_sub, d_sub.
+ *   fp32: the fused kernels take d_head % 4 == 0, d_head <= 256, any n_sub, d_sub, as long
+ *         as their LDS tiles fit (the backward, with d_head = 256, up to about 40 sub-networks).
  *   mhffn_reference_unfused takes any shape with d_head % 8 == 0.
  *   Row strides must keep every row 16-byte aligned.
  */

@@ -39,12 +39,13 @@ int check_desc(const mhffn_desc* d, Problem* p) {
 }
 
 // Can the fused kernels run this shape?
-int check_fused_shape(const mhffn_desc* d, const Problem& p) {
+int check_fused_shape(const mhffn_desc* d, const Problem& p, bool backward = false) {
   if (d->dtype == MHFFN_BF16) {
     if (p.dh != 128 || p.de % 32 != 0 || p.E > mhffn::kFwdBf16MaxSub) return MHFFN_ERR_UNSUPPORTED;
   } else {
     if (p.dh % 4 != 0 || p.dh > 256) return MHFFN_ERR_UNSUPPORTED;
-    if (mhffn::fwd_f32_lds_bytes(p) > mhffn::kLdsBytesPerWorkgroup) return MHFFN_ERR_UNSUPPORTED;
+    const size_t lds = backward ? mhffn::bwd_f32_lds_bytes(p) : mhffn::fwd_f32_lds_bytes(p);
+    if (lds > mhffn::kLdsBytesPerWorkgroup) return MHFFN_ERR_UNSUPPORTED;
   }
   return MHFFN_OK;
 }
@@ -83,7 +84,7 @@ size_t mhffn_workspace_bytes(const mhffn_desc* desc, int op) {
       if (desc->dtype != MHFFN_BF16 || check_fused_shape(desc, p) != MHFFN_OK) return 0;
       return mhffn::fwd_bf16_workspace_bytes(p);
     case MHFFN_OP_BACKWARD:
-      if (check_fused_shape(desc, p) != MHFFN_OK) return 0;
+      if (check_fused_shape(desc, p, true) != MHFFN_OK) return 0;
       return mhffn::bwd_workspace_bytes(p, desc->dtype);
     case MHFFN_OP_UNFUSED_FORWARD: return mhffn::unfused_workspace_bytes(p, desc->dtype, false);
     case MHFFN_OP_UNFUSED_BACKWARD: return mhffn::unfused_workspace_bytes(p, desc->dtype, true);
@@ -144,7 +145,7 @@ int mhffn_backward_phases(const mhffn_desc* desc, const void* X, const void* W_g
   const void* ptrs[] = {X, W_gate, W_up, W_down, route, dY, dX, dW_gate, dW_up, dW_down, d_route};
   for (const void* q : ptrs)
     if (!aligned16(q)) return MHFFN_ERR_ALIGN;
-  rc = check_fused_shape(desc, p);
+  rc = check_fused_shape(desc, p, true);
   if (rc) return rc;
   rc = check_workspace(mhffn::bwd_workspace_bytes(p, desc->dtype), workspace, workspace_bytes);
   if (rc) return rc;

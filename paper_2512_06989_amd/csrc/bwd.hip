@@ -818,7 +818,8 @@ size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 }  // namespace
 
 size_t bwd_workspace_bytes(const Problem& p, int dtype) {
-  if (dtype != 1 || p.N == 0) return 0;   // an empty batch only zero-fills the weight gradients
+  if (dtype != 1) return bwd_f32_workspace_bytes(p);
+  if (p.N == 0) return 0;   // an empty batch only zero-fills the weight gradients
   const size_t nhe = align256((size_t)p.N * p.H * p.E * sizeof(float));
   const size_t wr = align256((size_t)p.H * kRouteParts * kDh * p.E * sizeof(float));
   return 2 * nhe + wr;
@@ -828,8 +829,6 @@ int launch_bwd(const Problem& p, int dtype, const void* X, const void* Wg, const
                const void* Wd, const void* route, const void* dY, void* dX, void* dWg,
                void* dWu, void* dWd, void* d_route, void* ws, void* stream_,
                void* const* phase_events, int n_phase_events) {
-  if (dtype != 1) return -1;        // fp32 fused backward: not built
-  if (p.E > kRouteMaxSub) return -1;
   hipStream_t stream = static_cast<hipStream_t>(stream_);
   // event i is recorded after phase i-1 (event 0: before anything is launched)
   auto mark = [&](int i) -> hipError_t {
@@ -838,6 +837,14 @@ int launch_bwd(const Problem& p, int dtype, const void* X, const void* Wg, const
     return hipSuccess;
   };
   if (mark(0) != hipSuccess) return (int)hipErrorInvalidHandle;
+  if (dtype != 1) {   // fp32 companion kernels; its phases are not timed separately
+    const int e = launch_bwd_f32(p, X, Wg, Wu, Wd, route, dY, dX, dWg, dWu, dWd, d_route, ws, stream_);
+    if (e != 0) return e;
+    for (int i = 1; i <= kBwdPhases; ++i)
+      if (mark(i) != hipSuccess) return (int)hipErrorInvalidHandle;
+    return 0;
+  }
+  if (p.E > kRouteMaxSub) return -1;
   const size_t wcount = (size_t)p.H * p.E * p.de * kDh;
   if (p.N == 0) {
     void* outs[4] = {dWg, dWu, dWd, p.route_mode == 0 ? d_route : nullptr};

@@ -39,6 +39,12 @@ int launch_bwd(const Problem& p, int dtype, const void* X, const void* Wg, const
                void* const* phase_events = nullptr, int n_phase_events = 0);
 // Phases of the fused backward, in launch order (see mhffn_backward_phases).
 constexpr int kBwdPhases = 3;
+// fp32 companion (d_h % 4 == 0, d_h <= 256, tiles must fit in LDS)
+size_t bwd_f32_lds_bytes(const Problem& p);
+size_t bwd_f32_workspace_bytes(const Problem& p);
+int launch_bwd_f32(const Problem& p, const void* X, const void* Wg, const void* Wu,
+                   const void* Wd, const void* route, const void* dY, void* dX, void* dWg,
+                   void* dWu, void* dWd, void* d_route, void* ws, void* stream);
 
 // ---- unfused baseline ------------------------------------------------------
 size_t unfused_workspace_bytes(const Problem& p, int dtype, bool backward);

@@ -61,6 +61,32 @@ def test_bf16_weights_mode_returns_dr():
     check_all(got, ref, TOL["bf16"])
 
 
+def test_f32_tiny_config_backward():
+    """fp32 companion kernels at the fp32 tolerance (the tiny configuration's shape)."""
+    from dataclasses import replace
+    w = replace(inputs.WORKLOADS["tiny_f32"], backward=True)
+    d, got = run_backward(w)
+    ref = orc.backward(d["X"], d["W_gate"], d["W_up"], d["W_down"], d["W_r"], d["dY"], w.eps)
+    check_all(got, ref, TOL["f32"])
+
+
+@pytest.mark.parametrize("N", [1, 31, 65, 300])
+def test_f32_ragged_and_generic_shapes(N):
+    w = inputs.Workload("f32_bwd_generic", N, 3, 72, 5, 40, "f32", w_std=0.1, route_scale=3.0,
+                        backward=True)
+    d, got = run_backward(w, seed=N)
+    ref = orc.backward(d["X"], d["W_gate"], d["W_up"], d["W_down"], d["W_r"], d["dY"], w.eps)
+    check_all(got, ref, TOL["f32"])
+
+
+def test_f32_weights_mode_returns_dr():
+    w = small_workload("bwd_weights_f32", 200, 2, 6, 64, "f32", backward=True)
+    d, got = run_backward(w, seed=4, route_weights=True)
+    ref = orc.backward(d["X"], d["W_gate"], d["W_up"], d["W_down"], d["R"], d["dY"], w.eps,
+                       orc.ROUTE_WEIGHTS)
+    check_all(got, ref, TOL["f32"])
+
+
 def test_partial_gradient_requests():
     w = small_workload("bwd_partial", 300, 2, 3, 64, "bf16", backward=True)
     d, full = run_backward(w, seed=8)
