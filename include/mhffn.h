@@ -92,8 +92,10 @@ typedef struct {
  * Shape support.
  *   bf16: the fused kernels need d_head == 128, d_sub % 32 == 0 and
  *         n_sub <= 96; other shapes return MHFFN_ERR_UNSUPPORTED.
- *   fp32: the fused kernels take d_head % 4 == 0, d_head <= 256, any n_sub, d_sub, as long
- *         as their LDS tiles fit (the backward, with d_head = 256, up to about 40 sub-networks).
+ *   fp32: the fused kernels take d_head % 4 == 0, any n_sub, d_sub, as long as their LDS
+ *         tiles fit: the forward up to d_head = 256, the backward (which keeps whole
+ *         d_head-wide token and weight tiles resident) up to d_head = 232 with few
+ *         sub-networks and d_head = 128 with several hundred.
  *   mhffn_reference_unfused takes any shape with d_head % 8 == 0.
  *   Row strides must keep every row 16-byte aligned.
  */

@@ -79,6 +79,31 @@ def test_f32_ragged_and_generic_shapes(N):
     check_all(got, ref, TOL["f32"])
 
 
+@pytest.mark.parametrize("dh,E,de", [(64, 6, 192), (256, 3, 704)])
+def test_f32_other_head_widths(dh, E, de):
+    """The paper's head-width variants (d_h = 64, 256 with d_e = 8/3 d_h rounded up to a
+    multiple of 64) through the shape-generic fp32 kernels.  The forward takes both; the
+    fp32 backward keeps whole d_h-wide tiles in LDS and takes d_h up to 128, beyond which it
+    has to refuse rather than compute."""
+    import torch
+    w = inputs.Workload("f32_head_width", 150, 2, dh, E, de, "f32", w_std=0.05, route_scale=2.0,
+                        backward=True)
+    d = inputs.make_inputs(w, seed=dh, with_dy=True)
+    g = device_inputs(d, w.dtype)
+    Y = mhffn.forward(g["X"], g["W_gate"], g["W_up"], g["W_down"], g["W_r"], w.eps)
+    torch.cuda.synchronize()
+    ref_y = orc.forward(d["X"], d["W_gate"], d["W_up"], d["W_down"], d["W_r"], w.eps)
+    assert relerr(to_host(Y), ref_y) <= TOL["f32"]
+    if dh > 128:
+        with pytest.raises(mhffn.MhffnError) as err:
+            run_backward(w, seed=dh)
+        assert err.value.status == 3   # MHFFN_ERR_UNSUPPORTED
+        return
+    _, got = run_backward(w, seed=dh)
+    ref = orc.backward(d["X"], d["W_gate"], d["W_up"], d["W_down"], d["W_r"], d["dY"], w.eps)
+    check_all(got, ref, TOL["f32"])
+
+
 def test_f32_weights_mode_returns_dr():
     w = small_workload("bwd_weights_f32", 200, 2, 6, 64, "f32", backward=True)
     d, got = run_backward(w, seed=4, route_weights=True)
