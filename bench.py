@@ -193,9 +193,12 @@ def main():
     # kernel is not credited (forward 3; token-major M,N,dA,dX,dX = 5; weight-major dK,dU,dV = 3)
     units = {"fwd": 3.0, "bwd_tok": 5.0, "bwd_wgt": 3.0, "bwd_route": 0.0}
     # up to 64 sub-networks the forward runs the pipelined kernel
-    fwd_pipelined = w.n_sub <= 64
+    # (d_h = 128; the other head widths run the plainer kernels)
+    fwd_pipelined = w.d_head == 128 and w.n_sub <= 64
     kernel_names = {"fwd": "fwd_bf16_pipe_kernel" if fwd_pipelined else "fwd_bf16_kernel",
-                    "bwd_tok": "bwd_tok_kernel", "bwd_wgt": "bwd_wgt16_kernel", "bwd_route": "bwd_route_*"}
+                    "bwd_tok": "bwd_tok_kernel",
+                    "bwd_wgt": "bwd_wgt16_kernel" if w.d_head == 128 else "bwd_wgt_dh_kernel",
+                    "bwd_route": "bwd_route_*"}
 
     # HBM bytes per launch measured with rocprofv3 (FETCH_SIZE + WRITE_SIZE, each scaled by
     # what the counter reads for a 256 MiB copy); from profiles/mhffn_fwd_bwd_1p3b.md and

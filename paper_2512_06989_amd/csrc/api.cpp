@@ -41,7 +41,11 @@ int check_desc(const mhffn_desc* d, Problem* p) {
 // Can the fused kernels run this shape?
 int check_fused_shape(const mhffn_desc* d, const Problem& p, bool backward = false) {
   if (d->dtype == MHFFN_BF16) {
-    if (p.dh != 128 || p.de % 32 != 0 || p.E > mhffn::kFwdBf16MaxSub) return MHFFN_ERR_UNSUPPORTED;
+    if ((p.dh != 64 && p.dh != 128 && p.dh != 256) || p.de % 32 != 0 || p.E > mhffn::kFwdBf16MaxSub)
+      return MHFFN_ERR_UNSUPPORTED;
+    if (backward && p.E > mhffn::bwd_bf16_max_sub(p)) return MHFFN_ERR_UNSUPPORTED;
+    const size_t lds = backward ? mhffn::bwd_bf16_lds_bytes(p) : mhffn::fwd_bf16_lds_bytes(p);
+    if (lds > mhffn::kLdsBytesPerWorkgroup) return MHFFN_ERR_UNSUPPORTED;
   } else {
     if (p.dh % 4 != 0 || p.dh > 256) return MHFFN_ERR_UNSUPPORTED;
     const size_t lds = backward ? mhffn::bwd_f32_lds_bytes(p) : mhffn::fwd_f32_lds_bytes(p);

@@ -62,22 +62,28 @@ struct BwdArgs {
   float* DPws;  // [H][E][N]  dp (params mode) or dr (weights mode)
   float* WRws;  // [H][S][128][E] partial dW_r
   int64_t N, ldx, ldy, n_tiles, n_items;
-  int H, E, de, route_mode, n_split;
+  int H, E, de, dh, route_mode, n_split;
   float eps;
 };
 
 // ---------------------------------------------------------------------------
 // token-major kernel: dX, R, dp
 // ---------------------------------------------------------------------------
-constexpr int kTokStageBytes = 3 * kTileBytes;  // K, U, V
+constexpr int tok_stage_bytes(int dh) { return 3 * 32 * dh * 2; }  // K, U, V tiles of 32 rows
 constexpr int kTokStages = 2;
 
-template <int TB, int NW>
+template <int DH, int TB, int NW>
 __global__ __launch_bounds__(64 * NW) void bwd_tok_kernel(BwdArgs a) {
   constexpr int BM = 32 * TB * NW;
   constexpr int THREADS = 64 * NW;
-  constexpr int CH = 512 / THREADS;
-  static_assert(CH >= 1, "");
+  constexpr int KS = DH / 16;              // contraction steps over the head width
+  constexpr int JB = DH / 32;              // 32-row output tiles over the head width
+  constexpr int CPR = DH / 8;              // 16-byte chunks per row
+  constexpr int kTileBytes = 32 * DH * 2;
+  constexpr int kTokStageBytes = tok_stage_bytes(DH);
+  constexpr int CHUNKS = 32 * CPR;
+  constexpr int CH = (CHUNKS + THREADS - 1) / THREADS;
+  constexpr bool kAllLoad = (CHUNKS % THREADS == 0);   // else the upper threads carry none
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   unsigned char* stage_base = smem;
   float* DRs = reinterpret_cast<float*>(smem + kTokStages * kTokStageBytes);  // [E][BM]
@@ -94,7 +100,7 @@ __global__ __launch_bounds__(64 * NW) void bwd_tok_kernel(BwdArgs a) {
   float* Rh = a.Rws + (size_t)h * E * N;
   float* DPh = a.DPws + (size_t)h * E * N;
 
-  bf16x8 q[TB][8], dy[TB][8];
+  bf16x8 q[TB][KS], dy[TB][KS];
   int64_t tok[TB];
   bool valid[TB];
 #pragma unroll
@@ -102,10 +108,10 @@ __global__ __launch_bounds__(64 * NW) void bwd_tok_kernel(BwdArgs a) {
     tok[tb] = tile_tok0 + wtok + 32 * tb + r;
     valid[tb] = tok[tb] < N;
     const int64_t t = valid[tb] ? tok[tb] : 0;
-    const uint16_t* sx = a.X + t * a.ldx + h * kDh + 8 * g;
-    const uint16_t* sy = a.dY + t * a.ldy + h * kDh + 8 * g;
+    const uint16_t* sx = a.X + t * a.ldx + h * DH + 8 * g;
+    const uint16_t* sy = a.dY + t * a.ldy + h * DH + 8 * g;
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) {
+    for (int ks = 0; ks < KS; ++ks) {
       bf16x8 vx = *reinterpret_cast<const bf16x8*>(sx + 16 * ks);
       bf16x8 vy = *reinterpret_cast<const bf16x8*>(sy + 16 * ks);
       if (!valid[tb]) { vx = bf16x8{0, 0, 0, 0, 0, 0, 0, 0}; vy = vx; }
@@ -120,17 +126,16 @@ __global__ __launch_bounds__(64 * NW) void bwd_tok_kernel(BwdArgs a) {
   for (int tb = 0; tb < TB; ++tb) inv[tb] = 0.f;
   if (a.route_mode == 0) {
     const int EB = (E + 31) >> 5;
-    uint16_t* WrT = reinterpret_cast<uint16_t*>(stage_base);  // [32*EB][128] bf16, swizzled rows
-    const uint16_t* Wr = reinterpret_cast<const uint16_t*>(a.route) + (size_t)h * kDh * E;
-    for (int idx = tid; idx < kDh * E; idx += THREADS) {
+    // W_r^T as [32*EB][DH] bf16, swizzled rows
+    const uint16_t* Wr = reinterpret_cast<const uint16_t*>(a.route) + (size_t)h * DH * E;
+    for (int idx = tid; idx < DH * E; idx += THREADS) {
       const int j = idx / E, e = idx - j * E;
-      *reinterpret_cast<uint16_t*>(stage_base + tile_off(e, j >> 3) + (j & 7) * 2) = Wr[idx];
+      *reinterpret_cast<uint16_t*>(stage_base + tile_off_dh<DH>(e, j >> 3) + (j & 7) * 2) = Wr[idx];
     }
-    for (int idx = tid; idx < (32 * EB - E) * kDh; idx += THREADS) {
-      const int e = E + idx / kDh, j = idx % kDh;
-      *reinterpret_cast<uint16_t*>(stage_base + tile_off(e, j >> 3) + (j & 7) * 2) = 0;
+    for (int idx = tid; idx < (32 * EB - E) * DH; idx += THREADS) {
+      const int e = E + idx / DH, j = idx % DH;
+      *reinterpret_cast<uint16_t*>(stage_base + tile_off_dh<DH>(e, j >> 3) + (j & 7) * 2) = 0;
     }
-    (void)WrT;
     __syncthreads();
     float zsum[TB];
 #pragma unroll
@@ -141,8 +146,8 @@ __global__ __launch_bounds__(64 * NW) void bwd_tok_kernel(BwdArgs a) {
         for (int tb = 0; tb < TB; ++tb) {
           f32x16 acc = {0};
 #pragma unroll
-          for (int ks = 0; ks < 8; ++ks) {
-            const bf16x8 af = *reinterpret_cast<const bf16x8*>(stage_base + tile_off(32 * eb + r, 2 * ks + g));
+          for (int ks = 0; ks < KS; ++ks) {
+            const bf16x8 af = *reinterpret_cast<const bf16x8*>(stage_base + tile_off_dh<DH>(32 * eb + r, 2 * ks + g));
             acc = mfma32(af, q[tb][ks], acc);
           }
 #pragma unroll
@@ -179,7 +184,7 @@ __global__ __launch_bounds__(64 * NW) void bwd_tok_kernel(BwdArgs a) {
   // ---- main loop -------------------------------------------------------------
   const int tiles_per_sub = a.de / 32;
   const int T = E * tiles_per_sub;
-  const size_t head_off = (size_t)h * E * a.de * kDh;
+  const size_t head_off = (size_t)h * E * a.de * DH;
   const uint16_t* Kh = a.Wg + head_off;
   const uint16_t* Uh = a.Wu + head_off;
   const uint16_t* Vh = a.Wd + head_off;
@@ -189,7 +194,8 @@ __global__ __launch_bounds__(64 * NW) void bwd_tok_kernel(BwdArgs a) {
 #pragma unroll
     for (int i = 0; i < CH; ++i) {
       const int chunk = tid + THREADS * i;
-      const size_t off = ((size_t)t * 32 + (chunk >> 4)) * kDh + (chunk & 15) * 8;
+      if (!kAllLoad && chunk >= CHUNKS) continue;
+      const size_t off = ((size_t)t * 32 + chunk / CPR) * DH + (chunk % CPR) * 8;
       kreg[i] = *reinterpret_cast<const u32x4*>(Kh + off);
       ureg[i] = *reinterpret_cast<const u32x4*>(Uh + off);
       vreg[i] = *reinterpret_cast<const u32x4*>(Vh + off);
@@ -200,18 +206,19 @@ __global__ __launch_bounds__(64 * NW) void bwd_tok_kernel(BwdArgs a) {
 #pragma unroll
     for (int i = 0; i < CH; ++i) {
       const int chunk = tid + THREADS * i;
-      const int off = tile_off(chunk >> 4, chunk & 15);
+      if (!kAllLoad && chunk >= CHUNKS) continue;
+      const int off = tile_off_dh<DH>(chunk / CPR, chunk % CPR);
       *reinterpret_cast<u32x4*>(st + off) = kreg[i];
       *reinterpret_cast<u32x4*>(st + kTileBytes + off) = ureg[i];
       *reinterpret_cast<u32x4*>(st + 2 * kTileBytes + off) = vreg[i];
     }
   };
 
-  f32x16 dXa[TB][4];
+  f32x16 dXa[TB][JB];
 #pragma unroll
   for (int tb = 0; tb < TB; ++tb)
 #pragma unroll
-    for (int jb = 0; jb < 4; ++jb) dXa[tb][jb] = f32x16{0};
+    for (int jb = 0; jb < JB; ++jb) dXa[tb][jb] = f32x16{0};
 
   float rw[TB], rw_next[TB], drp[TB];
 #pragma unroll
@@ -246,16 +253,17 @@ __global__ __launch_bounds__(64 * NW) void bwd_tok_kernel(BwdArgs a) {
     // full LDS latency.
     {
       const unsigned sto = lds_addr_of(st);
-      bf16x8 op[24];
+      constexpr int NOP = 3 * KS;
+      bf16x8 op[NOP];
       auto issue = [&](auto C_) {
         constexpr int c = decltype(C_)::value, ks = c / 3, which = c % 3;
-        op[c] = lds_read_b128_untracked<which * kTileBytes>(sto + tile_off(r, 2 * ks + g));
+        op[c] = lds_read_b128_untracked<which * kTileBytes>(sto + tile_off_dh<DH>(r, 2 * ks + g));
       };
       static_for<0, 6>(issue);
-      static_for<0, 24>([&](auto C_) {
+      static_for<0, NOP>([&](auto C_) {
         constexpr int c = decltype(C_)::value, ks = c / 3, which = c % 3;
-        if constexpr (c + 6 < 24) issue(std::integral_constant<int, c + 6>{});
-        lds_wait<(23 - c) < 6 ? (23 - c) : 6>(op[c]);
+        if constexpr (c + 6 < NOP) issue(std::integral_constant<int, c + 6>{});
+        lds_wait<(NOP - 1 - c) < 6 ? (NOP - 1 - c) : 6>(op[c]);
 #pragma unroll
         for (int tb = 0; tb < TB; ++tb) {
           if constexpr (which == 0) accM[tb] = mfma32(op[c], q[tb][ks], accM[tb]);
@@ -295,9 +303,9 @@ __global__ __launch_bounds__(64 * NW) void bwd_tok_kernel(BwdArgs a) {
 #pragma unroll
     for (int t2 = 0; t2 < 2; ++t2) {
 #pragma unroll
-      for (int jb = 0; jb < 4; ++jb) {
-        const bf16x8 kt = tile_read_tr(st, 16 * t2 + 4 * g, 32 * jb, lane);
-        const bf16x8 ut = tile_read_tr(st + kTileBytes, 16 * t2 + 4 * g, 32 * jb, lane);
+      for (int jb = 0; jb < JB; ++jb) {
+        const bf16x8 kt = tile_read_tr_dh<DH>(st, 16 * t2 + 4 * g, 32 * jb, lane);
+        const bf16x8 ut = tile_read_tr_dh<DH>(st + kTileBytes, 16 * t2 + 4 * g, 32 * jb, lane);
 #pragma unroll
         for (int tb = 0; tb < TB; ++tb) {
           dXa[tb][jb] = mfma32(kt, dmf[tb][t2], dXa[tb][jb]);
@@ -322,8 +330,8 @@ __global__ __launch_bounds__(64 * NW) void bwd_tok_kernel(BwdArgs a) {
     // stage W_r[h] as rows j, columns e (zero padded to 32*EB), for the A operand
     const int EB = (E + 31) >> 5;
     const int wr_stride = 64 * EB + 16;  // bytes per row; +16 keeps rows off the same banks
-    const uint16_t* Wr = reinterpret_cast<const uint16_t*>(a.route) + (size_t)h * kDh * E;
-    for (int idx = tid; idx < kDh * 32 * EB; idx += THREADS) {
+    const uint16_t* Wr = reinterpret_cast<const uint16_t*>(a.route) + (size_t)h * DH * E;
+    for (int idx = tid; idx < DH * 32 * EB; idx += THREADS) {
       const int j = idx / (32 * EB), e = idx - j * (32 * EB);
       *reinterpret_cast<uint16_t*>(stage_base + j * wr_stride + e * 2) = (e < E) ? Wr[j * E + e] : 0;
     }
@@ -361,7 +369,7 @@ __global__ __launch_bounds__(64 * NW) void bwd_tok_kernel(BwdArgs a) {
         }
         const bf16x8 bp = __builtin_bit_cast(bf16x8, pk);
 #pragma unroll
-        for (int jb = 0; jb < 4; ++jb) {
+        for (int jb = 0; jb < JB; ++jb) {
           const bf16x8 aw = *reinterpret_cast<const bf16x8*>(stage_base + (32 * jb + r) * wr_stride +
                                                              (16 * ks + 8 * g) * 2);
           dXa[tb][jb] = mfma32(aw, bp, dXa[tb][jb]);
@@ -386,9 +394,9 @@ __global__ __launch_bounds__(64 * NW) void bwd_tok_kernel(BwdArgs a) {
 #pragma unroll
     for (int tb = 0; tb < TB; ++tb) {
       if (valid[tb]) {
-        uint16_t* dst = a.dX + tok[tb] * a.ldx + h * kDh + 4 * g;
+        uint16_t* dst = a.dX + tok[tb] * a.ldx + h * DH + 4 * g;
 #pragma unroll
-        for (int jb = 0; jb < 4; ++jb) {
+        for (int jb = 0; jb < JB; ++jb) {
 #pragma unroll
           for (int vq = 0; vq < 4; ++vq) {
             u32x2 pk;
@@ -706,6 +714,188 @@ __global__ __launch_bounds__(kW16Threads) void bwd_wgt16_kernel(BwdArgs a) {
 }
 
 // ---------------------------------------------------------------------------
+// weight-major kernel for the other head widths (d_h = 64, 256)
+//
+// Same decomposition as bwd_wgt16_kernel (one wave = 16 neurons, K/U/V rows resident as
+// operands of the 16x16x32 product, loop over all tokens in blocks of 32, transposed
+// tiles for the gradient products), written plainly: the q / dY tiles go through
+// registers into two alternating LDS buffers, one barrier per block, and the compiler
+// schedules the reads.  At d_h = 256 the resident operands (96) and the accumulators
+// (192 registers) leave room for one wave per SIMD only; the launcher then uses
+// workgroups of 4 waves.  MFMA row m of a 16-token block is token m.
+// ---------------------------------------------------------------------------
+template <int DH, int NW>
+__global__ __launch_bounds__(64 * NW) void bwd_wgt_dh_kernel(BwdArgs a) {
+  constexpr int THREADS = 64 * NW;
+  constexpr int KS = DH / 32;              // contraction steps of the 16x16x32 products over d_h
+  constexpr int JB = DH / 16;              // 16-row output tiles over d_h
+  constexpr int CPR = DH / 8;              // 16-byte chunks per row
+  constexpr int kTileBytes = 32 * DH * 2;
+  constexpr int CHUNKS = 32 * CPR;
+  constexpr int CH = (CHUNKS + THREADS - 1) / THREADS;
+  constexpr bool kAllLoad = (CHUNKS % THREADS == 0);
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];   // 2 x (q tile | dY tile)
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int cn = lane & 15, gq = lane >> 4;
+  const int nblk = a.E * a.de / 16;              // 16-neuron blocks per head
+  const int wg_per_head = (nblk + NW - 1) / NW;
+  const int64_t item = xcd_work_item(blockIdx.x, a.n_items);
+  if (item >= a.n_items) return;
+  const int h = (int)(item / wg_per_head);
+  const int blk = (int)(item % wg_per_head) * NW + wave;
+  const bool active = blk < nblk;
+  const int blk_c = active ? blk : nblk - 1;     // idle waves shadow a valid block, store nothing
+  const int64_t N = a.N;
+  const size_t row0 = ((size_t)h * nblk + blk_c) * 16;
+  const int e_wave = blk_c / (a.de / 16);
+  const float* Rw = a.Rws + ((size_t)h * a.E + e_wave) * N;
+
+  bf16x8 Kf[KS], Uf[KS], Vf[KS];
+  {
+    const size_t off = (row0 + cn) * DH + 8 * gq;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      Kf[ks] = *reinterpret_cast<const bf16x8*>(a.Wg + off + 32 * ks);
+      Uf[ks] = *reinterpret_cast<const bf16x8*>(a.Wu + off + 32 * ks);
+      Vf[ks] = *reinterpret_cast<const bf16x8*>(a.Wd + off + 32 * ks);
+    }
+  }
+  f32x4 dK[JB], dU[JB], dV[JB];
+#pragma unroll
+  for (int jb = 0; jb < JB; ++jb) { dK[jb] = f32x4{0, 0, 0, 0}; dU[jb] = dK[jb]; dV[jb] = dK[jb]; }
+
+  // ---- staging: rows past N are zero (and get r = 0), so they add nothing ----------
+  const int64_t nb = (N + 31) / 32;
+  u32x4 xreg[CH], yreg[CH];
+  float rnext[2][4];
+  auto gload = [&](int64_t b) {
+#pragma unroll
+    for (int i = 0; i < CH; ++i) {
+      const int chunk = tid + THREADS * i;
+      if (!kAllLoad && chunk >= CHUNKS) continue;
+      const int64_t t = b * 32 + chunk / CPR;
+      const int col = h * DH + (chunk % CPR) * 8;
+      u32x4 vx = {0, 0, 0, 0}, vy = {0, 0, 0, 0};
+      if (t < N) {
+        vx = *reinterpret_cast<const u32x4*>(a.X + t * a.ldx + col);
+        vy = *reinterpret_cast<const u32x4*>(a.dY + t * a.ldy + col);
+      }
+      xreg[i] = vx;
+      yreg[i] = vy;
+    }
+#pragma unroll
+    for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const int64_t t = b * 32 + 16 * tb + 4 * gq + v;
+        rnext[tb][v] = (t < N) ? Rw[t] : 0.f;
+      }
+  };
+  auto lstore = [&](int buf) {
+    unsigned char* dst = smem + buf * 2 * kTileBytes;
+#pragma unroll
+    for (int i = 0; i < CH; ++i) {
+      const int chunk = tid + THREADS * i;
+      if (!kAllLoad && chunk >= CHUNKS) continue;
+      const int off = tile_off_dh<DH>(chunk / CPR, chunk % CPR);
+      *reinterpret_cast<u32x4*>(dst + off) = xreg[i];
+      *reinterpret_cast<u32x4*>(dst + kTileBytes + off) = yreg[i];
+    }
+  };
+  gload(0);
+  lstore(0);
+  float rv[2][4];
+  __syncthreads();
+
+  for (int64_t b = 0; b < nb; ++b) {
+    const bool more = (b + 1 < nb);
+#pragma unroll
+    for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) rv[tb][v] = rnext[tb][v];
+    if (more) gload(b + 1);
+    const unsigned char* qt = smem + (b & 1) * 2 * kTileBytes;
+    const unsigned char* yt = qt + kTileBytes;
+
+    // M, N, dA for the two 16-token blocks: A operand = token row cn, columns 32ks + 8gq ..
+    f32x4 M[2], Nn[2], Ad[2];
+#pragma unroll
+    for (int tb = 0; tb < 2; ++tb) {
+      M[tb] = f32x4{0, 0, 0, 0}; Nn[tb] = M[tb]; Ad[tb] = M[tb];
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        const int off = tile_off_dh<DH>(16 * tb + cn, 4 * ks + gq);
+        const bf16x8 qa = *reinterpret_cast<const bf16x8*>(qt + off);
+        const bf16x8 ya = *reinterpret_cast<const bf16x8*>(yt + off);
+        M[tb] = mfma16(qa, Kf[ks], M[tb]);
+        Nn[tb] = mfma16(qa, Uf[ks], Nn[tb]);
+        Ad[tb] = mfma16(ya, Vf[ks], Ad[tb]);
+      }
+    }
+    // element (tb, v): token 16tb + 4gq + v, neuron cn; it becomes contraction slot
+    // 4tb + v of the gradient products
+    float ag[8], dm[8], dn[8];
+#pragma unroll
+    for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const float m = M[tb][v], n = Nn[tb][v], da = Ad[tb][v], rw = rv[tb][v];
+        const float sg = sigmoid_fast(m);
+        const float silu = m * sg;
+        const float rda = rw * da;
+        ag[4 * tb + v] = rw * silu * n;
+        dn[4 * tb + v] = rda * silu;
+        dm[4 * tb + v] = rda * n * fmaf(silu, 1.0f - sg, sg);
+      }
+    u32x4 pa, pm, pn;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      pa[i] = pack_bf16(ag[2 * i], ag[2 * i + 1]);
+      pm[i] = pack_bf16(dm[2 * i], dm[2 * i + 1]);
+      pn[i] = pack_bf16(dn[2 * i], dn[2 * i + 1]);
+    }
+    const bf16x8 agf = __builtin_bit_cast(bf16x8, pa);
+    const bf16x8 dmf = __builtin_bit_cast(bf16x8, pm), dnf = __builtin_bit_cast(bf16x8, pn);
+
+    // dV^T[j][c] += dY^T a ; dK^T[j][c] += q^T dM ; dU^T[j][c] += q^T dN.  Transposed operand:
+    // lane (cn, gq) points at token row 4gq + cn/4 (and + 16), columns 16jb + 4(cn%4) ..
+#pragma unroll
+    for (int jb = 0; jb < JB; ++jb) {
+      const int row = 4 * gq + (cn >> 2), col = 16 * jb + 4 * (cn & 3);
+      const int o_lo = tile_off8_dh<DH>(row, col), o_hi = tile_off8_dh<DH>(row + 16, col);
+      const bf16x8 yT = join_tr(lds_read_tr16(yt + o_lo), lds_read_tr16(yt + o_hi));
+      const bf16x8 qT = join_tr(lds_read_tr16(qt + o_lo), lds_read_tr16(qt + o_hi));
+      dV[jb] = mfma16(yT, agf, dV[jb]);
+      dK[jb] = mfma16(qT, dmf, dK[jb]);
+      dU[jb] = mfma16(qT, dnf, dU[jb]);
+    }
+    if (more) lstore((b + 1) & 1);
+    __syncthreads();
+  }
+
+  if (active) {
+    // accumulators are [j][c]: lane = neuron column cn, register v = row 16jb + 4gq + v
+    const size_t off = (row0 + cn) * DH + 4 * gq;
+#pragma unroll
+    for (int jb = 0; jb < JB; ++jb) {
+      const size_t o = off + 16 * jb;
+      if (a.dWg) {
+        u32x2 pk = {pack_bf16(dK[jb][0], dK[jb][1]), pack_bf16(dK[jb][2], dK[jb][3])};
+        *reinterpret_cast<u32x2*>(a.dWg + o) = pk;
+      }
+      if (a.dWu) {
+        u32x2 pk = {pack_bf16(dU[jb][0], dU[jb][1]), pack_bf16(dU[jb][2], dU[jb][3])};
+        *reinterpret_cast<u32x2*>(a.dWu + o) = pk;
+      }
+      if (a.dWd) {
+        u32x2 pk = {pack_bf16(dV[jb][0], dV[jb][1]), pack_bf16(dV[jb][2], dV[jb][3])};
+        *reinterpret_cast<u32x2*>(a.dWd + o) = pk;
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
 // dW_r[h][j][e] = sum_tok q[tok][j] dp[tok][e]: partial sums per token split,
 // then a fixed-order reduction (deterministic).
 // ---------------------------------------------------------------------------
@@ -714,12 +904,13 @@ constexpr int kRouteParts = kRouteSplit * 4;    // one partial per wave
 constexpr int kRouteMaxSub = 96;
 
 // D[j][e] += sum_tok q^T[j][tok] dp[tok][e] on the MFMA: the A operand is the
-// transposing LDS read of a [32 tok][128] tile of X, the B operand (contraction
+// transposing LDS read of a [32 tok][d_h] tile of X, the B operand (contraction
 // slot s <-> token 16*t2 + 8*(s/4) + 4g + s%4, column e) comes straight from
 // the [H][E][N] dp array.  Each wave walks its own token blocks and leaves its
 // own partial [128][E] in the workspace.
-template <int EB>
+template <int DH, int EB>
 __global__ __launch_bounds__(256) void bwd_route_partial_kernel(BwdArgs a) {
+  constexpr int JB = DH / 32, CPR = DH / 8, kTileBytes = 32 * DH * 2;
   __shared__ __attribute__((aligned(16))) unsigned char tiles[4 * kTileBytes];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r = lane & 31, g = lane >> 5;
@@ -731,23 +922,23 @@ __global__ __launch_bounds__(256) void bwd_route_partial_kernel(BwdArgs a) {
   const int64_t iters = (nb + kRouteParts - 1) / kRouteParts;  // same for every wave
   const float* DPh = a.DPws + (size_t)h * E * N;
   unsigned char* tile = tiles + wave * kTileBytes;
-  f32x16 acc[EB][4];
+  f32x16 acc[EB][JB];
 #pragma unroll
   for (int eb = 0; eb < EB; ++eb)
 #pragma unroll
-    for (int jb = 0; jb < 4; ++jb) acc[eb][jb] = f32x16{0};
+    for (int jb = 0; jb < JB; ++jb) acc[eb][jb] = f32x16{0};
 
   for (int64_t it = 0; it < iters; ++it) {
     const int64_t b = it * kRouteParts + part;
     const int64_t tok0 = b * 32;   // may lie beyond N: then everything loaded is zero
-    // X tile -> this wave's LDS tile (8 chunks per lane)
+    // X tile -> this wave's LDS tile
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
+    for (int i = 0; i < 32 * CPR / 64; ++i) {
       const int chunk = lane + 64 * i;
-      const int64_t t = tok0 + (chunk >> 4);
+      const int64_t t = tok0 + chunk / CPR;
       u32x4 v = {0, 0, 0, 0};
-      if (t < N) v = *reinterpret_cast<const u32x4*>(a.X + t * a.ldx + h * kDh + (chunk & 15) * 8);
-      *reinterpret_cast<u32x4*>(tile + tile_off(chunk >> 4, chunk & 15)) = v;
+      if (t < N) v = *reinterpret_cast<const u32x4*>(a.X + t * a.ldx + h * DH + (chunk % CPR) * 8);
+      *reinterpret_cast<u32x4*>(tile + tile_off_dh<DH>(chunk / CPR, chunk % CPR)) = v;
     }
     // dp operands
     bf16x8 bp[EB][2];
@@ -772,21 +963,21 @@ __global__ __launch_bounds__(256) void bwd_route_partial_kernel(BwdArgs a) {
 #pragma unroll
     for (int t2 = 0; t2 < 2; ++t2) {
 #pragma unroll
-      for (int jb = 0; jb < 4; ++jb) {
-        const bf16x8 qT = tile_read_tr(tile, 16 * t2 + 4 * g, 32 * jb, lane);
+      for (int jb = 0; jb < JB; ++jb) {
+        const bf16x8 qT = tile_read_tr_dh<DH>(tile, 16 * t2 + 4 * g, 32 * jb, lane);
 #pragma unroll
         for (int eb = 0; eb < EB; ++eb) acc[eb][jb] = mfma32(qT, bp[eb][t2], acc[eb][jb]);
       }
     }
     __syncthreads();
   }
-  float* out = a.WRws + ((size_t)h * kRouteParts + part) * kDh * E;
+  float* out = a.WRws + ((size_t)h * kRouteParts + part) * DH * E;
 #pragma unroll
   for (int eb = 0; eb < EB; ++eb) {
     const int e = 32 * eb + r;
     if (e < E) {
 #pragma unroll
-      for (int jb = 0; jb < 4; ++jb)
+      for (int jb = 0; jb < JB; ++jb)
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
           const int j = 32 * jb + 8 * (v / 4) + 4 * g + (v % 4);
@@ -798,7 +989,7 @@ __global__ __launch_bounds__(256) void bwd_route_partial_kernel(BwdArgs a) {
 
 __global__ void bwd_route_reduce_kernel(BwdArgs a) {
   const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  const int64_t per_head = (int64_t)kDh * a.E;
+  const int64_t per_head = (int64_t)a.dh * a.E;
   if (idx >= per_head * a.H) return;
   const int h = (int)(idx / per_head);
   const int64_t o = idx % per_head;
@@ -815,13 +1006,92 @@ __global__ void fill_zero_kernel(uint32_t* p, size_t n_words) {
 
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
+template <typename K>
+hipError_t allow_full_lds(K kernel) {
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBytesPerWorkgroup);
+}
+
+constexpr int tok_block_tokens(int dh) { return dh == 256 ? 128 : 256; }
+
+template <int DH, int TB, int NW>
+int launch_tok(const Problem& p, BwdArgs a, hipStream_t stream) {
+  constexpr int BM = 32 * TB * NW;
+  static_assert(BM == tok_block_tokens(DH), "bwd_tok_lds_bytes assumes this block size");
+  a.n_tiles = (p.N + BM - 1) / BM;
+  a.n_items = a.n_tiles * p.H;
+  const size_t lds = (size_t)kTokStages * tok_stage_bytes(DH) + (size_t)p.E * BM * sizeof(float);
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = allow_full_lds(&bwd_tok_kernel<DH, TB, NW>);
+    if (e != hipSuccess) return (int)e;
+    attr_set = true;
+  }
+  hipLaunchKernelGGL((bwd_tok_kernel<DH, TB, NW>), dim3((unsigned)xcd_grid_size(a.n_items)),
+                     dim3(64 * NW), lds, stream, a);
+  return (int)hipGetLastError();
+}
+
+int launch_wgt16(const Problem& p, BwdArgs a, hipStream_t stream) {
+  const int nblk = p.E * p.de / 16;
+  const int wg_per_head = (nblk + kW16Waves - 1) / kW16Waves;
+  a.n_items = (int64_t)wg_per_head * p.H;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = allow_full_lds(&bwd_wgt16_kernel);
+    if (e != hipSuccess) return (int)e;
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(bwd_wgt16_kernel, dim3((unsigned)xcd_grid_size(a.n_items)),
+                     dim3(kW16Threads), kW16LdsBytes, stream, a);
+  return (int)hipGetLastError();
+}
+
+template <int DH, int NW>
+int launch_wgt_dh(const Problem& p, BwdArgs a, hipStream_t stream) {
+  const int nblk = p.E * p.de / 16;
+  const int wg_per_head = (nblk + NW - 1) / NW;
+  a.n_items = (int64_t)wg_per_head * p.H;
+  constexpr size_t lds = 2 * 2 * 32 * DH * 2;   // two buffers of a q and a dY tile
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = allow_full_lds(&bwd_wgt_dh_kernel<DH, NW>);
+    if (e != hipSuccess) return (int)e;
+    attr_set = true;
+  }
+  hipLaunchKernelGGL((bwd_wgt_dh_kernel<DH, NW>), dim3((unsigned)xcd_grid_size(a.n_items)),
+                     dim3(64 * NW), lds, stream, a);
+  return (int)hipGetLastError();
+}
+
+template <int DH>
+int launch_route(const Problem& p, const BwdArgs& a, hipStream_t stream) {
+  const dim3 rgrid(p.H, kRouteSplit);
+  if (p.E <= 32) hipLaunchKernelGGL((bwd_route_partial_kernel<DH, 1>), rgrid, dim3(256), 0, stream, a);
+  else if (p.E <= 64) hipLaunchKernelGGL((bwd_route_partial_kernel<DH, 2>), rgrid, dim3(256), 0, stream, a);
+  else if constexpr (DH <= 128) hipLaunchKernelGGL((bwd_route_partial_kernel<DH, 3>), rgrid, dim3(256), 0, stream, a);
+  else return -1;   // excluded by bwd_bf16_max_sub
+  const int64_t n = (int64_t)p.H * DH * p.E;
+  hipLaunchKernelGGL(bwd_route_reduce_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0,
+                     stream, a);
+  return (int)hipGetLastError();
+}
+
 }  // namespace
+
+// d_h = 256: the routing-gradient kernel keeps 8 accumulator tiles per 32 sub-networks
+int bwd_bf16_max_sub(const Problem& p) { return p.dh == 256 ? 64 : kRouteMaxSub; }
+
+size_t bwd_bf16_lds_bytes(const Problem& p) {
+  return (size_t)kTokStages * tok_stage_bytes(p.dh) +
+         (size_t)p.E * tok_block_tokens(p.dh) * sizeof(float);
+}
 
 size_t bwd_workspace_bytes(const Problem& p, int dtype) {
   if (dtype != 1) return bwd_f32_workspace_bytes(p);
   if (p.N == 0) return 0;   // an empty batch only zero-fills the weight gradients
   const size_t nhe = align256((size_t)p.N * p.H * p.E * sizeof(float));
-  const size_t wr = align256((size_t)p.H * kRouteParts * kDh * p.E * sizeof(float));
+  const size_t wr = align256((size_t)p.H * kRouteParts * p.dh * p.E * sizeof(float));
   return 2 * nhe + wr;
 }
 
@@ -844,11 +1114,11 @@ int launch_bwd(const Problem& p, int dtype, const void* X, const void* Wg, const
       if (mark(i) != hipSuccess) return (int)hipErrorInvalidHandle;
     return 0;
   }
-  if (p.E > kRouteMaxSub) return -1;
-  const size_t wcount = (size_t)p.H * p.E * p.de * kDh;
+  if (p.E > bwd_bf16_max_sub(p)) return -1;
+  const size_t wcount = (size_t)p.H * p.E * p.de * p.dh;
   if (p.N == 0) {
     void* outs[4] = {dWg, dWu, dWd, p.route_mode == 0 ? d_route : nullptr};
-    const size_t words[4] = {wcount / 2, wcount / 2, wcount / 2, (size_t)p.H * kDh * p.E / 2};
+    const size_t words[4] = {wcount / 2, wcount / 2, wcount / 2, (size_t)p.H * p.dh * p.E / 2};
     for (int i = 0; i < 4; ++i) {
       if (!outs[i] || !words[i]) continue;
       hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)((words[i] + 255) / 256)), dim3(256), 0,
@@ -873,57 +1143,28 @@ int launch_bwd(const Problem& p, int dtype, const void* X, const void* Wg, const
   a.DPws = reinterpret_cast<float*>(static_cast<unsigned char*>(ws) + nhe);
   a.WRws = reinterpret_cast<float*>(static_cast<unsigned char*>(ws) + 2 * nhe);
   a.N = p.N; a.ldx = p.ldx; a.ldy = p.ldy;
-  a.H = p.H; a.E = p.E; a.de = p.de; a.route_mode = p.route_mode; a.eps = p.eps;
+  a.H = p.H; a.E = p.E; a.de = p.de; a.dh = p.dh; a.route_mode = p.route_mode; a.eps = p.eps;
   a.n_split = kRouteParts;
 
   // token-major kernel (always: it also produces R for the weight-major kernel)
-  {
-    constexpr int TB = 1, NW = 8, BM = 32 * TB * NW;
-    a.n_tiles = (p.N + BM - 1) / BM;
-    a.n_items = a.n_tiles * p.H;
-    const size_t lds = (size_t)kTokStages * kTokStageBytes + (size_t)p.E * BM * sizeof(float);
-    static bool attr_set = false;
-    if (!attr_set) {
-      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&bwd_tok_kernel<TB, NW>),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize,
-                                         (int)kLdsBytesPerWorkgroup);
-      if (e != hipSuccess) return (int)e;
-      attr_set = true;
-    }
-    hipLaunchKernelGGL((bwd_tok_kernel<TB, NW>), dim3((unsigned)xcd_grid_size(a.n_items)),
-                       dim3(64 * NW), lds, stream, a);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return (int)e;
-  }
+  int rc;
+  if (p.dh == 64) rc = launch_tok<64, 1, 8>(p, a, stream);
+  else if (p.dh == 256) rc = launch_tok<256, 1, 4>(p, a, stream);   // needs one wave per SIMD: see the kernel
+  else rc = launch_tok<kDh, 1, 8>(p, a, stream);
+  if (rc) return rc;
   if (mark(1) != hipSuccess) return (int)hipErrorInvalidHandle;
   if (dWg || dWu || dWd) {
-    const int nblk = p.E * p.de / 16;
-    const int wg_per_head = (nblk + kW16Waves - 1) / kW16Waves;
-    a.n_items = (int64_t)wg_per_head * p.H;
-    static bool wgt_attr_set = false;
-    if (!wgt_attr_set) {
-      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&bwd_wgt16_kernel),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize,
-                                         (int)kLdsBytesPerWorkgroup);
-      if (e != hipSuccess) return (int)e;
-      wgt_attr_set = true;
-    }
-    hipLaunchKernelGGL(bwd_wgt16_kernel, dim3((unsigned)xcd_grid_size(a.n_items)),
-                       dim3(kW16Threads), kW16LdsBytes, stream, a);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return (int)e;
+    if (p.dh == 64) rc = launch_wgt_dh<64, 8>(p, a, stream);
+    else if (p.dh == 256) rc = launch_wgt_dh<256, 4>(p, a, stream);
+    else rc = launch_wgt16(p, a, stream);
+    if (rc) return rc;
   }
   if (mark(2) != hipSuccess) return (int)hipErrorInvalidHandle;
   if (d_route && p.route_mode == 0) {
-    const dim3 rgrid(p.H, kRouteSplit);
-    if (p.E <= 32) hipLaunchKernelGGL(bwd_route_partial_kernel<1>, rgrid, dim3(256), 0, stream, a);
-    else if (p.E <= 64) hipLaunchKernelGGL(bwd_route_partial_kernel<2>, rgrid, dim3(256), 0, stream, a);
-    else hipLaunchKernelGGL(bwd_route_partial_kernel<3>, rgrid, dim3(256), 0, stream, a);
-    const int64_t n = (int64_t)p.H * kDh * p.E;
-    hipLaunchKernelGGL(bwd_route_reduce_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0,
-                       stream, a);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return (int)e;
+    if (p.dh == 64) rc = launch_route<64>(p, a, stream);
+    else if (p.dh == 256) rc = launch_route<256>(p, a, stream);
+    else rc = launch_route<kDh>(p, a, stream);
+    if (rc) return rc;
   }
   if (mark(3) != hipSuccess) return (int)hipErrorInvalidHandle;
   return 0;

@@ -28,11 +28,11 @@ namespace {
 
 constexpr int kDh = 128;            // head width this kernel is built for
 constexpr int kBI = 32;             // neurons per tile
-constexpr int kKUStride = 272;      // bytes per LDS row of a K/U tile (256 + 16 pad)
-constexpr int kVStride = 320;       // bytes per LDS row of a V tile   (256 + 64 pad)
-constexpr int kKBytes = kBI * kKUStride;
-constexpr int kVBytes = kBI * kVStride;
-constexpr int kStageBytes = 2 * kKBytes + kVBytes;  // 27648
+// fwd_bf16_kernel<DH, ..>: LDS rows of a K/U tile carry 16 bytes of padding (row-wise
+// operand reads), rows of a V tile 64 (transposing reads); 27648 bytes per stage at d_h = 128
+constexpr int fwd_ku_stride(int dh) { return 2 * dh + 16; }
+constexpr int fwd_v_stride(int dh) { return 2 * dh + 64; }
+constexpr int fwd_stage_bytes(int dh) { return kBI * (2 * fwd_ku_stride(dh) + fwd_v_stride(dh)); }
 constexpr int kStages = 2;
 
 // LDS keeps 1/r (clamped, so r = 0 stays finite): the weight then rides along in the
@@ -54,17 +54,23 @@ struct FwdArgs {
   uint16_t* Y;
   float* P;     // [n_split][N][H*128] fp32 partial outputs (only when n_split > 1)
   int64_t N, ldx, ldy, n_tiles, n_items;
-  int H, E, de, route_mode;
+  int H, E, de, dh, route_mode;
   int n_split, tiles_per_split;
   float eps;
 };
 
-template <int TB, int NW>
+template <int DH, int TB, int NW>
 __global__ __launch_bounds__(64 * NW) void fwd_bf16_kernel(FwdArgs a) {
   constexpr int BM = 32 * TB * NW;
   constexpr int THREADS = 64 * NW;
-  constexpr int CH = (kBI * kDh * 2 / 16) / THREADS;  // 16-byte chunks per thread per tile
-  static_assert(CH >= 1, "tile smaller than the workgroup");
+  constexpr int KS = DH / 16;                  // contraction steps over the head width
+  constexpr int JB = DH / 32;                  // 32-row output tiles over the head width
+  constexpr int CPR = DH / 8;                  // 16-byte chunks per weight row
+  constexpr int kKUStride = fwd_ku_stride(DH), kVStride = fwd_v_stride(DH);
+  constexpr int kKBytes = kBI * kKUStride, kStageBytes = fwd_stage_bytes(DH);
+  constexpr int CHUNKS = kBI * CPR;            // 16-byte chunks per tile
+  constexpr int CH = (CHUNKS + THREADS - 1) / THREADS;   // per thread
+  constexpr bool kAllLoad = (CHUNKS % THREADS == 0);     // else the upper threads carry none
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   unsigned char* stage_base = smem;
   float* Rs = reinterpret_cast<float*>(smem + kStages * kStageBytes);  // [E][BM]
@@ -83,14 +89,14 @@ __global__ __launch_bounds__(64 * NW) void fwd_bf16_kernel(FwdArgs a) {
   const int E = a.E;
 
   // ---- q fragments (B operands), resident for the whole kernel -------------
-  bf16x8 q[TB][8];
+  bf16x8 q[TB][KS];
 #pragma unroll
   for (int tb = 0; tb < TB; ++tb) {
     const int64_t tok = tile_tok0 + wtok + 32 * tb + r;
     const bool valid = tok < a.N;
-    const uint16_t* src = a.X + (valid ? tok : 0) * a.ldx + h * kDh + 8 * g;
+    const uint16_t* src = a.X + (valid ? tok : 0) * a.ldx + h * DH + 8 * g;
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) {
+    for (int ks = 0; ks < KS; ++ks) {
       bf16x8 v = *reinterpret_cast<const bf16x8*>(src + 16 * ks);
       if (!valid) v = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
       q[tb][ks] = v;
@@ -102,7 +108,7 @@ __global__ __launch_bounds__(64 * NW) void fwd_bf16_kernel(FwdArgs a) {
   const int T_all = E * tiles_per_sub;
   const int t_begin = split * a.tiles_per_split;          // this workgroup's share of the
   const int T = min(T_all, t_begin + a.tiles_per_split);   // intermediate dimension
-  const size_t head_off = (size_t)h * E * a.de * kDh;
+  const size_t head_off = (size_t)h * E * a.de * DH;
   const uint16_t* Kh = a.Wg + head_off;
   const uint16_t* Uh = a.Wu + head_off;
   const uint16_t* Vh = a.Wd + head_off;
@@ -117,7 +123,8 @@ __global__ __launch_bounds__(64 * NW) void fwd_bf16_kernel(FwdArgs a) {
 #pragma unroll
     for (int i = 0; i < CH; ++i) {
       const int chunk = tid + THREADS * i;
-      const size_t off = ((size_t)t * kBI + (chunk >> 4)) * kDh + (chunk & 15) * 8;
+      if (!kAllLoad && chunk >= CHUNKS) continue;
+      const size_t off = ((size_t)t * kBI + chunk / CPR) * DH + (chunk % CPR) * 8;
       kreg[s][i] = *reinterpret_cast<const u32x4*>(Kh + off);
       ureg[s][i] = *reinterpret_cast<const u32x4*>(Uh + off);
       vreg[s][i] = *reinterpret_cast<const u32x4*>(Vh + off);
@@ -129,7 +136,8 @@ __global__ __launch_bounds__(64 * NW) void fwd_bf16_kernel(FwdArgs a) {
 #pragma unroll
     for (int i = 0; i < CH; ++i) {
       const int chunk = tid + THREADS * i;
-      const int row = chunk >> 4, c16 = chunk & 15;
+      if (!kAllLoad && chunk >= CHUNKS) continue;
+      const int row = chunk / CPR, c16 = chunk % CPR;
       *reinterpret_cast<u32x4*>(st + row * kKUStride + c16 * 16) = kreg[s][i];
       *reinterpret_cast<u32x4*>(st + kKBytes + row * kKUStride + c16 * 16) = ureg[s][i];
       *reinterpret_cast<u32x4*>(st + 2 * kKBytes + row * kVStride + c16 * 16) = vreg[s][i];
@@ -144,13 +152,13 @@ __global__ __launch_bounds__(64 * NW) void fwd_bf16_kernel(FwdArgs a) {
   if (a.route_mode == 0) {
     const int EB = (E + 31) >> 5;
     uint16_t* WrT = reinterpret_cast<uint16_t*>(stage_base);  // [32*EB][136] bf16
-    const uint16_t* Wr = reinterpret_cast<const uint16_t*>(a.route) + (size_t)h * kDh * E;
-    for (int idx = tid; idx < kDh * E; idx += THREADS) {
+    const uint16_t* Wr = reinterpret_cast<const uint16_t*>(a.route) + (size_t)h * DH * E;
+    for (int idx = tid; idx < DH * E; idx += THREADS) {
       const int j = idx / E, e = idx - j * E;
       WrT[e * (kKUStride / 2) + j] = Wr[idx];
     }
-    for (int idx = tid; idx < (32 * EB - E) * kDh; idx += THREADS) {
-      const int e = E + idx / kDh, j = idx % kDh;
+    for (int idx = tid; idx < (32 * EB - E) * DH; idx += THREADS) {
+      const int e = E + idx / DH, j = idx % DH;
       WrT[e * (kKUStride / 2) + j] = 0;
     }
     __syncthreads();
@@ -167,7 +175,7 @@ __global__ __launch_bounds__(64 * NW) void fwd_bf16_kernel(FwdArgs a) {
         for (int tb = 0; tb < TB; ++tb) {
           f32x16 acc = {0};
 #pragma unroll
-          for (int ks = 0; ks < 8; ++ks) {
+          for (int ks = 0; ks < KS; ++ks) {
             bf16x8 af = *reinterpret_cast<const bf16x8*>(arow + 32 * ks);
             acc = mfma32(af, q[tb][ks], acc);
           }
@@ -201,11 +209,11 @@ __global__ __launch_bounds__(64 * NW) void fwd_bf16_kernel(FwdArgs a) {
   }
   __syncthreads();  // R complete; the staging area is free again
 
-  f32x16 O[TB][4];
+  f32x16 O[TB][JB];
 #pragma unroll
   for (int tb = 0; tb < TB; ++tb)
 #pragma unroll
-    for (int jb = 0; jb < 4; ++jb) O[tb][jb] = f32x16{0};
+    for (int jb = 0; jb < JB; ++jb) O[tb][jb] = f32x16{0};
 
   // per-lane byte offsets of the operand reads inside a stage
   const int ku_off = r * kKUStride + 16 * g;
@@ -233,7 +241,7 @@ __global__ __launch_bounds__(64 * NW) void fwd_bf16_kernel(FwdArgs a) {
 #pragma unroll
     for (int tb = 0; tb < TB; ++tb) { accM[tb] = f32x16{0}; accN[tb] = f32x16{0}; }
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) {
+    for (int ks = 0; ks < KS; ++ks) {
       const bf16x8 ak = *reinterpret_cast<const bf16x8*>(st + ku_off + 32 * ks);
       const bf16x8 au = *reinterpret_cast<const bf16x8*>(st + kKBytes + ku_off + 32 * ks);
 #pragma unroll
@@ -275,7 +283,7 @@ __global__ __launch_bounds__(64 * NW) void fwd_bf16_kernel(FwdArgs a) {
 #pragma unroll
     for (int t2 = 0; t2 < 2; ++t2) {
 #pragma unroll
-      for (int jb = 0; jb < 4; ++jb) {
+      for (int jb = 0; jb < JB; ++jb) {
         const unsigned char* vp = st + v_off + (16 * t2) * kVStride + 64 * jb;
         const s16x4 lo = lds_read_tr16(vp);
         const s16x4 hi = lds_read_tr16(vp + 8 * kVStride);
@@ -300,9 +308,9 @@ __global__ __launch_bounds__(64 * NW) void fwd_bf16_kernel(FwdArgs a) {
     for (int tb = 0; tb < TB; ++tb) {
       const int64_t tok = tile_tok0 + wtok + 32 * tb + r;
       if (tok < a.N) {
-        float* dst = a.P + (((size_t)split * a.N + tok) * a.H + h) * kDh + 4 * g;
+        float* dst = a.P + (((size_t)split * a.N + tok) * a.H + h) * DH + 4 * g;
 #pragma unroll
-        for (int jb = 0; jb < 4; ++jb)
+        for (int jb = 0; jb < JB; ++jb)
 #pragma unroll
           for (int vq = 0; vq < 4; ++vq) {
             f32x4 o = {O[tb][jb][4 * vq], O[tb][jb][4 * vq + 1], O[tb][jb][4 * vq + 2],
@@ -318,9 +326,9 @@ __global__ __launch_bounds__(64 * NW) void fwd_bf16_kernel(FwdArgs a) {
   for (int tb = 0; tb < TB; ++tb) {
     const int64_t tok = tile_tok0 + wtok + 32 * tb + r;
     if (tok < a.N) {
-      uint16_t* dst = a.Y + tok * a.ldy + h * kDh + 4 * g;
+      uint16_t* dst = a.Y + tok * a.ldy + h * DH + 4 * g;
 #pragma unroll
-      for (int jb = 0; jb < 4; ++jb) {
+      for (int jb = 0; jb < JB; ++jb) {
 #pragma unroll
         for (int vq = 0; vq < 4; ++vq) {
           u32x2 pk;
@@ -670,7 +678,7 @@ __global__ __launch_bounds__(64 * kPipeWaves) void fwd_bf16_pipe_kernel(FwdArgs 
 
 // Y[tok][col] = bf16(sum_s P[s][tok][col]), fixed order
 __global__ void fwd_bf16_reduce_kernel(FwdArgs a) {
-  const int64_t dm = (int64_t)a.H * kDh;
+  const int64_t dm = (int64_t)a.H * a.dh;
   const int64_t idx = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
   if (idx >= a.N * dm) return;
   f32x4 sum = {0.f, 0.f, 0.f, 0.f};
@@ -692,8 +700,9 @@ __global__ void fwd_bf16_reduce_kernel(FwdArgs a) {
 struct SplitPlan { int bm, n_split, tiles_per_split; bool pipe; };
 SplitPlan plan_split(const Problem& p) {
   SplitPlan s;
-  s.pipe = p.E <= kPipeMaxSub;
+  s.pipe = p.dh == kDh && p.E <= kPipeMaxSub;
   s.bm = (!s.pipe && p.N <= 128) ? 64 : 256;
+  if (p.dh == 256) s.bm = 128;   // 4 waves of up to 512 registers (see launch_fwd_bf16)
   const int64_t base = ((p.N + s.bm - 1) / s.bm) * p.H;
   const int T = p.E * (p.de / kBI);
   int want = 1;
@@ -708,27 +717,27 @@ SplitPlan plan_split(const Problem& p) {
   return s;
 }
 
-template <int TB, int NW>
+template <int DH, int TB, int NW>
 int launch_variant(const Problem& p, FwdArgs a, const SplitPlan& sp, hipStream_t stream) {
   constexpr int BM = 32 * TB * NW;
   a.n_tiles = (p.N + BM - 1) / BM;
   a.n_split = sp.n_split;
   a.tiles_per_split = sp.tiles_per_split;
   a.n_items = a.n_tiles * p.H * sp.n_split;
-  const size_t lds = (size_t)kStages * kStageBytes + (size_t)p.E * BM * sizeof(float);
+  const size_t lds = (size_t)kStages * fwd_stage_bytes(DH) + (size_t)p.E * BM * sizeof(float);
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&fwd_bf16_kernel<TB, NW>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&fwd_bf16_kernel<DH, TB, NW>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize,
                                        (int)kLdsBytesPerWorkgroup);
     if (e != hipSuccess) return (int)e;
     attr_set = true;
   }
   const dim3 grid((unsigned)xcd_grid_size(a.n_items));
-  hipLaunchKernelGGL((fwd_bf16_kernel<TB, NW>), grid, dim3(64 * NW), lds, stream, a);
+  hipLaunchKernelGGL((fwd_bf16_kernel<DH, TB, NW>), grid, dim3(64 * NW), lds, stream, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || sp.n_split == 1) return (int)e;
-  const int64_t n4 = p.N * p.H * kDh / 4;
+  const int64_t n4 = p.N * p.H * DH / 4;
   hipLaunchKernelGGL(fwd_bf16_reduce_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0,
                      stream, a);
   return (int)hipGetLastError();
@@ -763,7 +772,7 @@ int launch_pipe(const Problem& p, FwdArgs a, const SplitPlan& sp, hipStream_t st
 size_t fwd_bf16_workspace_bytes(const Problem& p) {
   if (p.N == 0) return 0;
   const SplitPlan sp = plan_split(p);
-  return sp.n_split > 1 ? (size_t)sp.n_split * p.N * p.H * kDh * sizeof(float) : 0;
+  return sp.n_split > 1 ? (size_t)sp.n_split * p.N * p.H * p.dh * sizeof(float) : 0;
 }
 
 int launch_fwd_bf16(const Problem& p, const void* X, const void* Wg, const void* Wu,
@@ -777,15 +786,30 @@ int launch_fwd_bf16(const Problem& p, const void* X, const void* Wg, const void*
   a.Y = static_cast<uint16_t*>(Y);
   a.P = static_cast<float*>(ws);
   a.N = p.N; a.ldx = p.ldx; a.ldy = p.ldy;
-  a.H = p.H; a.E = p.E; a.de = p.de; a.route_mode = p.route_mode; a.eps = p.eps;
+  a.H = p.H; a.E = p.E; a.de = p.de; a.dh = p.dh; a.route_mode = p.route_mode; a.eps = p.eps;
   a.n_tiles = 0; a.n_items = 0; a.n_split = 1; a.tiles_per_split = 0;
   const SplitPlan sp = plan_split(p);
   hipStream_t st = static_cast<hipStream_t>(stream);
   // 8 waves x 32 tokens (two waves per SIMD) measured 25% faster than 4 waves x
   // 64 tokens at the 1.3B shape: the second wave hides LDS and barrier latency.
   if (sp.pipe) return launch_pipe(p, a, sp, st);
-  if (sp.bm == 64) return launch_variant<1, 2>(p, a, sp, st);
-  return launch_variant<1, 8>(p, a, sp, st);
+  if (p.dh == 64) {
+    if (sp.bm == 64) return launch_variant<64, 1, 2>(p, a, sp, st);
+    return launch_variant<64, 1, 8>(p, a, sp, st);
+  }
+  if (p.dh == 256) {
+    // the output accumulators alone are 128 registers per wave and the token operands 64:
+    // one wave per SIMD with the whole register file rather than two that spill
+    return launch_variant<256, 1, 4>(p, a, sp, st);
+  }
+  if (sp.bm == 64) return launch_variant<kDh, 1, 2>(p, a, sp, st);
+  return launch_variant<kDh, 1, 8>(p, a, sp, st);
+}
+
+size_t fwd_bf16_lds_bytes(const Problem& p) {
+  const SplitPlan sp = plan_split(p);
+  if (sp.pipe) return (size_t)3 * kPipeRing + (size_t)p.E * kPipeBM * sizeof(float);
+  return (size_t)kStages * fwd_stage_bytes(p.dh) + (size_t)p.E * sp.bm * sizeof(float);
 }
 
 }  // namespace mhffn

@@ -96,6 +96,42 @@ __device__ __forceinline__ bf16x8 tile_read_tr(const unsigned char* tile, int r0
   return __builtin_bit_cast(bf16x8, both);
 }
 
+// The same tile for other head widths DH (rows of DH bf16, no padding).  The bank of a
+// byte is its position inside a 256-byte line, so a 512-byte row (DH = 256) is two
+// lines, each swizzled like a row of the 128-wide tile, and inherits its properties.
+// A 128-byte row (DH = 64) shares its line with its neighbour; there the 8 chunks are
+// permuted by a function of row/2 chosen such that the rows one 16-byte read cycle
+// serves (see the lane groups in the weight-major kernel's notes) land on different
+// chunks, and rows r, r+2 of a transposing read on different chunk pairs.
+template <int DH>
+__device__ __forceinline__ int tile_off_dh(int row, int chunk) {
+  static_assert(DH == 64 || DH == 128 || DH == 256, "head width");
+  if constexpr (DH == 128) {
+    return tile_off(row, chunk);
+  } else if constexpr (DH == 64) {
+    const int u = row >> 1;
+    const int s = ((u & 1) << 1) | ((u & 2) << 1) | ((u >> 2) & 1);
+    return row * 128 + ((chunk ^ s) << 4);
+  } else {
+    return row * (2 * DH) + ((chunk & ~15) << 4) + (((chunk & 15) ^ swz(row)) << 4);
+  }
+}
+template <int DH>
+__device__ __forceinline__ int tile_off8_dh(int row, int col) {
+  return tile_off_dh<DH>(row, col >> 3) + ((col & 4) << 1);
+}
+template <int DH>
+__device__ __forceinline__ bf16x8 tile_read_tr_dh(const unsigned char* tile, int r0, int c0, int lane) {
+  const int li = lane & 15;
+  const int row = r0 + (li >> 2);
+  const int col = c0 + 16 * ((lane >> 4) & 1) + 4 * (li & 3);
+  const s16x4 lo = lds_read_tr16(tile + tile_off8_dh<DH>(row, col));
+  const s16x4 hi = lds_read_tr16(tile + tile_off8_dh<DH>(row + 8, col));
+  typedef short s16x8 __attribute__((ext_vector_type(8)));
+  const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+  return __builtin_bit_cast(bf16x8, both);
+}
+
 // Direct global -> LDS load, 16 bytes per lane: lane l of the wave writes LDS bytes
 // [lds_wave_base + 16 l, +16) with the 16 bytes at its own global address.
 // lds_wave_base must be wave-uniform.  Completion is counted by vmcnt.

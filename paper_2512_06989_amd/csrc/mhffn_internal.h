@@ -18,8 +18,9 @@ struct Problem {
 };
 
 // ---- fused forward ---------------------------------------------------------
-// bf16, d_h = 128, d_e % 32 == 0, E <= kFwdBf16MaxSub.
+// bf16, d_h in {64, 128, 256}, d_e % 32 == 0, E <= kFwdBf16MaxSub, LDS within the limit.
 constexpr int kFwdBf16MaxSub = 96;
+size_t fwd_bf16_lds_bytes(const Problem& p);
 // Scratch of the bf16 forward: 0 unless the token tiles cannot fill the chip and the
 // intermediate dimension is split over workgroups (fp32 partial outputs).
 size_t fwd_bf16_workspace_bytes(const Problem& p);
@@ -32,6 +33,9 @@ size_t fwd_f32_lds_bytes(const Problem& p);
 constexpr size_t kLdsBytesPerWorkgroup = 160 * 1024;
 
 // ---- fused backward --------------------------------------------------------
+// bf16 limits of the backward kernels for a shape (d_h in {64, 128, 256})
+int bwd_bf16_max_sub(const Problem& p);
+size_t bwd_bf16_lds_bytes(const Problem& p);
 size_t bwd_workspace_bytes(const Problem& p, int dtype);
 int launch_bwd(const Problem& p, int dtype, const void* X, const void* Wg, const void* Wu,
                const void* Wd, const void* route, const void* dY, void* dX, void* dWg,

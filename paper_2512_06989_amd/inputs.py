@@ -60,6 +60,13 @@ WORKLOADS = {
     "paper_370m": Workload("paper_370m", 16384, 8, 128, 7, 384, "bf16", backward=True),
     "paper_1p3b": Workload("paper_1p3b", 16384, 16, 128, 15, 384, "bf16", backward=True),
     "paper_bench": Workload("paper_bench", 8 * 1920, 16, 128, 22, 384, "bf16", backward=True),
+    # Head-width ablation of the paper (d_h = 64 and 256; sub-network width 8/3 d_h rounded up to
+    # a multiple of 64 = 192 and 704), on the 370M model's d_model = 1024 and intermediate size
+    # of about 2688, and on the 1.3B model's d_model = 2048 / about 5632.
+    "paper_370m_dh64": Workload("paper_370m_dh64", 16384, 16, 64, 14, 192, "bf16", backward=True),
+    "paper_370m_dh256": Workload("paper_370m_dh256", 16384, 4, 256, 4, 704, "bf16", backward=True),
+    "paper_1p3b_dh64": Workload("paper_1p3b_dh64", 16384, 32, 64, 29, 192, "bf16", backward=True),
+    "paper_1p3b_dh256": Workload("paper_1p3b_dh256", 16384, 8, 256, 8, 704, "bf16", backward=True),
 }
 SWEEP_TOKENS = (64, 1024, 32768)
 PAPER_BENCH_SEQ_LENS = (192, 384, 768, 1536, 1920, 2880, 4032, 8064, 16128)   # batch 8 each

@@ -46,12 +46,27 @@ def fwd(d, ptrs=None):
 @pytest.mark.parametrize("kw,status", [
     (dict(n_tokens=-1), 2), (dict(n_heads=0), 2), (dict(d_sub=0), 2), (dict(ld_x=100), 2),
     (dict(eps=-1.0), 2), (dict(eps=float("nan")), 2), (dict(dtype=7), 3), (dict(route_mode=2), 3),
-    (dict(d_head=64), 3), (dict(d_sub=48), 3), (dict(n_sub=1000), 3),
+    (dict(d_head=96), 3), (dict(d_head=512), 3), (dict(d_sub=48), 3), (dict(n_sub=1000), 3),
     (dict(ld_x=260), 4),
     (dict(dtype=mhffn.F32, d_head=130), 3), (dict(dtype=mhffn.F32, d_head=512), 3),
 ])
 def test_forward_rejects_bad_descriptors(kw, status):
     assert fwd(desc(**kw)) == status
+
+
+def test_bf16_head_widths_64_and_256_pass_validation():
+    """The fused bf16 kernels exist for d_h in {64, 128, 256}: these descriptors get as far as
+    the workspace check (64 tokens: the intermediate dimension is split)."""
+    lib = mhffn.load()
+    for dh, de in ((64, 192), (256, 704)):
+        d = desc(d_head=dh, d_sub=de)
+        assert fwd(d) == 5
+        assert lib.mhffn_backward(ctypes.byref(d), *([FAKE] * 11), None, 0, None) == 5
+        assert mhffn.workspace_bytes(d, mhffn.OP_BACKWARD) > 0
+    # d_h = 256: the backward takes at most 64 sub-networks, the forward 96
+    d = desc(d_head=256, d_sub=64, n_sub=96)
+    assert fwd(d) == 5
+    assert lib.mhffn_backward(ctypes.byref(d), *([FAKE] * 11), FAKE, 1 << 40, None) == 3
 
 
 def test_forward_rejects_null_and_misaligned_pointers():

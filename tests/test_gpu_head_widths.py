@@ -1,0 +1,66 @@
+"""GPU parity of the fused bf16 kernels for the other head widths of the paper's ablation
+(d_h = 64 and 256), forward and backward, against the fp64 oracle through the C ABI."""
+import numpy as np
+import pytest
+
+from oracle import mhffn_oracle as orc
+from paper_2512_06989_amd import inputs, mhffn
+from tests.helpers import TOL, device_inputs, relerr, small_workload, to_host
+from tests.test_gpu_backward import GRADS, check_all, head_slice, run_backward
+from tests.test_gpu_forward import oracle_forward, run_forward
+
+pytestmark = pytest.mark.gpu
+
+# (N, H, d_h, E, d_e): ragged token counts, one and several tiles, the split path of the
+# forward (few tokens), more than 32 sub-networks, the paper's sub-network widths
+SHAPES = [(1, 1, 64, 1, 32), (63, 2, 64, 3, 96), (300, 2, 64, 5, 64), (1000, 3, 64, 14, 192),
+          (257, 1, 64, 40, 32), (130, 2, 64, 70, 32),
+          (1, 1, 256, 1, 32), (63, 2, 256, 3, 96), (300, 2, 256, 3, 64), (700, 1, 256, 4, 704),
+          (257, 1, 256, 40, 32)]
+
+
+@pytest.mark.parametrize("N,H,dh,E,de", SHAPES)
+def test_forward_small_shapes(N, H, dh, E, de):
+    w = small_workload("hw_fwd", N, H, E, de, "bf16", dh=dh)
+    d, Y = run_forward(w, seed=N + dh)
+    assert relerr(Y, oracle_forward(d, w)) <= TOL["bf16"]
+
+
+@pytest.mark.parametrize("N,H,dh,E,de", SHAPES)
+def test_backward_small_shapes(N, H, dh, E, de):
+    w = small_workload("hw_bwd", N, H, E, de, "bf16", dh=dh, backward=True)
+    d, got = run_backward(w, seed=N + E + dh)
+    ref = orc.backward(d["X"], d["W_gate"], d["W_up"], d["W_down"], d["W_r"], d["dY"], w.eps)
+    check_all(got, ref, TOL["bf16"], single_subnetwork=(E == 1))
+
+
+@pytest.mark.parametrize("dh", [64, 256])
+def test_weights_mode(dh):
+    w = small_workload("hw_weights", 333, 2, 6, 64, "bf16", dh=dh, backward=True)
+    d, Y = run_forward(w, seed=5, route_weights=True)
+    assert relerr(Y, oracle_forward(d, w, route_weights=True)) <= TOL["bf16"]
+    d, got = run_backward(w, seed=5, route_weights=True)
+    ref = orc.backward(d["X"], d["W_gate"], d["W_up"], d["W_down"], d["R"], d["dY"], w.eps,
+                       orc.ROUTE_WEIGHTS)
+    check_all(got, ref, TOL["bf16"])
+
+
+@pytest.mark.parametrize("name,heads", [("paper_370m_dh64", (0, 9)), ("paper_370m_dh256", (1, 3))])
+def test_full_size_on_whole_heads(name, heads):
+    """The head-width ablation at full size: heads are independent, so the oracle evaluates
+    whole heads (all tokens) and each is compared with its slice of the GPU result."""
+    w = inputs.WORKLOADS[name]
+    d, got = run_backward(w)
+    _, Y = run_forward(w)
+    for k in GRADS:
+        assert np.all(np.isfinite(got[k])), k
+    for h in heads:
+        s = head_slice(d, w, h)
+        cols = slice(h * w.d_head, (h + 1) * w.d_head)
+        ref_y = orc.forward(s["X"], s["W_gate"], s["W_up"], s["W_down"], s["W_r"], w.eps)
+        assert relerr(Y[:, cols], ref_y) <= TOL["bf16"]
+        ref = orc.backward(s["X"], s["W_gate"], s["W_up"], s["W_down"], s["W_r"], s["dY"], w.eps)
+        mine = {"dX": got["dX"][:, cols], "dW_gate": got["dW_gate"][h:h + 1],
+                "dW_up": got["dW_up"][h:h + 1], "dW_down": got["dW_down"][h:h + 1],
+                "d_route": got["d_route"][h:h + 1]}
+        check_all(mine, ref, TOL["bf16"])
