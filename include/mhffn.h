@@ -90,8 +90,9 @@ typedef struct {
 
 /*
  * Shape support.
- *   bf16: the fused kernels need d_head == 128, d_sub % 32 == 0 and
- *         n_sub <= 96; other shapes return MHFFN_ERR_UNSUPPORTED.
+ *   bf16: the fused kernels need d_head in {64, 128, 256}, d_sub % 32 == 0 and
+ *         n_sub <= 96 (backward with d_head = 256: n_sub <= 64); other shapes
+ *         return MHFFN_ERR_UNSUPPORTED.
  *   fp32: the fused kernels take d_head % 4 == 0, any n_sub, d_sub, as long as their LDS
  *         tiles fit: the forward up to d_head = 256, the backward (which keeps whole
  *         d_head-wide token and weight tiles resident) up to d_head = 232 with few

@@ -719,13 +719,24 @@ __global__ __launch_bounds__(kW16Threads) void bwd_wgt16_kernel(BwdArgs a) {
 // Same decomposition as bwd_wgt16_kernel (one wave = 16 neurons, K/U/V rows resident as
 // operands of the 16x16x32 product, loop over all tokens in blocks of 32, transposed
 // tiles for the gradient products), written plainly: the q / dY tiles go through
-// registers into two alternating LDS buffers, one barrier per block, and the compiler
-// schedules the reads.  At d_h = 256 the resident operands (96) and the accumulators
+// registers into two alternating LDS buffers, one barrier per block.  At d_h = 256 the resident operands (96) and the accumulators
 // (192 registers) leave room for one wave per SIMD only; the launcher then uses
-// workgroups of 4 waves.  MFMA row m of a 16-token block is token m.
+// workgroups of 4 waves.  For d_h >= 128 MFMA row m of a 16-token block is token rho(m) as in
+// bwd_wgt16_kernel (conflict-free row reads); at d_h = 64, where two rows share a 256-byte
+// line, it is token m.
 // ---------------------------------------------------------------------------
+constexpr int kDhWindow = 6;   // operands in flight ahead of the one being consumed
+// last stream position issued when item c is consumed; LDS read instructions behind the
+// positions after c up to there (a row operand is one read, a transposed window two)
+constexpr int dh_issued_before(int c, int ntot) { return c + kDhWindow > ntot - 1 ? ntot - 1 : c + kDhWindow; }
+constexpr int dh_pending(int c, int na, int ntot) {
+  int n = 0;
+  for (int p = c + 1; p <= dh_issued_before(c, ntot); ++p) n += (p < na) ? 1 : 2;
+  return n;
+}
+
 template <int DH, int NW>
-__global__ __launch_bounds__(64 * NW) void bwd_wgt_dh_kernel(BwdArgs a) {
+__global__ __launch_bounds__(64 * NW, DH == 64 ? 2 : 1) void bwd_wgt_dh_kernel(BwdArgs a) {
   constexpr int THREADS = 64 * NW;
   constexpr int KS = DH / 32;              // contraction steps of the 16x16x32 products over d_h
   constexpr int JB = DH / 16;              // 16-row output tiles over d_h
@@ -737,6 +748,7 @@ __global__ __launch_bounds__(64 * NW) void bwd_wgt_dh_kernel(BwdArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];   // 2 x (q tile | dY tile)
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int cn = lane & 15, gq = lane >> 4;
+  auto rho = [](int m) { return DH >= 128 ? ((m & 9) | ((m & 2) << 1) | ((m & 4) >> 1)) : m; };
   const int nblk = a.E * a.de / 16;              // 16-neuron blocks per head
   const int wg_per_head = (nblk + NW - 1) / NW;
   const int64_t item = xcd_work_item(blockIdx.x, a.n_items);
@@ -766,9 +778,14 @@ __global__ __launch_bounds__(64 * NW) void bwd_wgt_dh_kernel(BwdArgs a) {
 
   // ---- staging: rows past N are zero (and get r = 0), so they add nothing ----------
   const int64_t nb = (N + 31) / 32;
-  u32x4 xreg[CH], yreg[CH];
-  float rnext[2][4];
-  auto gload = [&](int64_t b) {
+  // Two register sets: while block b is consumed from LDS, block b+1 sits in one set (stored
+  // at the end of the step) and the loads of block b+2 are in flight into the other.  At
+  // d_h = 256 there are no registers for a second set: one set, requested one block ahead.
+  constexpr int SETS = (DH == 256) ? 1 : 2;
+  u32x4 xreg[SETS][CH], yreg[SETS][CH];
+  float rnext[SETS][2][4];
+  auto gload = [&](int64_t b, auto S_) {
+    constexpr int S = decltype(S_)::value;
 #pragma unroll
     for (int i = 0; i < CH; ++i) {
       const int chunk = tid + THREADS * i;
@@ -780,59 +797,90 @@ __global__ __launch_bounds__(64 * NW) void bwd_wgt_dh_kernel(BwdArgs a) {
         vx = *reinterpret_cast<const u32x4*>(a.X + t * a.ldx + col);
         vy = *reinterpret_cast<const u32x4*>(a.dY + t * a.ldy + col);
       }
-      xreg[i] = vx;
-      yreg[i] = vy;
+      xreg[S][i] = vx;
+      yreg[S][i] = vy;
     }
 #pragma unroll
     for (int tb = 0; tb < 2; ++tb)
 #pragma unroll
       for (int v = 0; v < 4; ++v) {
-        const int64_t t = b * 32 + 16 * tb + 4 * gq + v;
-        rnext[tb][v] = (t < N) ? Rw[t] : 0.f;
+        const int64_t t = b * 32 + 16 * tb + rho(4 * gq + v);
+        rnext[S][tb][v] = (t < N) ? Rw[t] : 0.f;
       }
   };
-  auto lstore = [&](int buf) {
+  auto lstore = [&](int buf, auto S_) {
+    constexpr int S = decltype(S_)::value;
     unsigned char* dst = smem + buf * 2 * kTileBytes;
 #pragma unroll
     for (int i = 0; i < CH; ++i) {
       const int chunk = tid + THREADS * i;
       if (!kAllLoad && chunk >= CHUNKS) continue;
       const int off = tile_off_dh<DH>(chunk / CPR, chunk % CPR);
-      *reinterpret_cast<u32x4*>(dst + off) = xreg[i];
-      *reinterpret_cast<u32x4*>(dst + kTileBytes + off) = yreg[i];
+      *reinterpret_cast<u32x4*>(dst + off) = xreg[S][i];
+      *reinterpret_cast<u32x4*>(dst + kTileBytes + off) = yreg[S][i];
     }
   };
-  gload(0);
-  lstore(0);
+  using S0 = std::integral_constant<int, 0>;
+  using SB = std::integral_constant<int, SETS - 1>;   // the second set, if there is one
+  gload(0, S0{});
+  if (SETS == 2 && nb > 1) gload(1, SB{});
+  lstore(0, S0{});
   float rv[2][4];
   __syncthreads();
 
-  for (int64_t b = 0; b < nb; ++b) {
+  // block b: its tiles are in LDS buffer b & 1 and its r in register set SL, which is then
+  // free and receives block b+2; SS holds block b+1
+  auto step = [&](int64_t b, auto SL, auto SS) {
     const bool more = (b + 1 < nb);
 #pragma unroll
     for (int tb = 0; tb < 2; ++tb)
 #pragma unroll
-      for (int v = 0; v < 4; ++v) rv[tb][v] = rnext[tb][v];
-    if (more) gload(b + 1);
-    const unsigned char* qt = smem + (b & 1) * 2 * kTileBytes;
-    const unsigned char* yt = qt + kTileBytes;
+      for (int v = 0; v < 4; ++v) rv[tb][v] = rnext[decltype(SL)::value][tb][v];
+    if (b + SETS < nb) gload(b + SETS, SL);
+    const unsigned char* qt = smem + (b & 1) * 2 * kTileBytes;   // dY tile: + kTileBytes
 
-    // M, N, dA for the two 16-token blocks: A operand = token row cn, columns 32ks + 8gq ..
+    // All LDS operands of the step form one stream, issued untracked kDhWindow items ahead
+    // of their use with counted waits (the compiler, left alone, waits for each read right
+    // after issuing it):
+    //   items 0 .. NA-1   rows of the q / dY tiles: token row 16tb + rho(cn), columns 32ks + 8gq ..
+    //   items NA ..       transposed windows, dY^T and q^T alternating: lane (cn, gq) points at
+    //                     token row rho(4gq + cn/4) (and + 16), columns 16jb + 4(cn%4) ..
+    const unsigned qb = lds_addr_of(qt);
+    constexpr int NA = 4 * KS, NTOT = NA + 2 * JB;
+    bf16x8 opa[NA];
+    s16x4 xlo[2 * JB], xhi[2 * JB];
+    auto issue = [&](auto P_) {
+      constexpr int P = decltype(P_)::value;
+      if constexpr (P < NA) {
+        constexpr int tb = P / (2 * KS), ks = (P / 2) % KS, which = P & 1;   // 0: q, 1: dY
+        opa[P] = lds_read_b128_untracked<which * kTileBytes>(qb + tile_off_dh<DH>(16 * tb + rho(cn), 4 * ks + gq));
+      } else {
+        constexpr int J = P - NA, jb = J >> 1, TO = (J & 1) ? 0 : kTileBytes;  // even: dY^T, odd: q^T
+        const unsigned ad = qb + tile_off8_dh<DH>(rho(4 * gq + (cn >> 2)), 16 * jb + 4 * (cn & 3));
+        xlo[J] = lds_read_tr16_untracked<TO>(ad);
+        xhi[J] = lds_read_tr16_untracked<TO + 16 * 2 * DH>(ad);   // 16 rows further: same swizzle
+      }
+    };
+    auto advance = [&](auto C_) {
+      constexpr int C = decltype(C_)::value;
+      constexpr int lo = (C == 0) ? 0 : dh_issued_before(C - 1, NTOT) + 1;
+      static_for<lo, dh_issued_before(C, NTOT) + 1>(issue);
+    };
     f32x4 M[2], Nn[2], Ad[2];
 #pragma unroll
-    for (int tb = 0; tb < 2; ++tb) {
-      M[tb] = f32x4{0, 0, 0, 0}; Nn[tb] = M[tb]; Ad[tb] = M[tb];
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-        const int off = tile_off_dh<DH>(16 * tb + cn, 4 * ks + gq);
-        const bf16x8 qa = *reinterpret_cast<const bf16x8*>(qt + off);
-        const bf16x8 ya = *reinterpret_cast<const bf16x8*>(yt + off);
-        M[tb] = mfma16(qa, Kf[ks], M[tb]);
-        Nn[tb] = mfma16(qa, Uf[ks], Nn[tb]);
-        Ad[tb] = mfma16(ya, Vf[ks], Ad[tb]);
+    for (int tb = 0; tb < 2; ++tb) { M[tb] = f32x4{0, 0, 0, 0}; Nn[tb] = M[tb]; Ad[tb] = M[tb]; }
+    static_for<0, NA>([&](auto C_) {
+      constexpr int C = decltype(C_)::value, tb = C / (2 * KS), ks = (C / 2) % KS;
+      advance(C_);
+      lds_wait<dh_pending(C, NA, NTOT)>(opa[C]);
+      if constexpr ((C & 1) == 0) {
+        M[tb] = mfma16(opa[C], Kf[ks], M[tb]);
+        Nn[tb] = mfma16(opa[C], Uf[ks], Nn[tb]);
+      } else {
+        Ad[tb] = mfma16(opa[C], Vf[ks], Ad[tb]);
       }
-    }
-    // element (tb, v): token 16tb + 4gq + v, neuron cn; it becomes contraction slot
+    });
+    // element (tb, v): token 16tb + rho(4gq + v), neuron cn; it becomes contraction slot
     // 4tb + v of the gradient products
     float ag[8], dm[8], dn[8];
 #pragma unroll
@@ -857,20 +905,29 @@ __global__ __launch_bounds__(64 * NW) void bwd_wgt_dh_kernel(BwdArgs a) {
     const bf16x8 agf = __builtin_bit_cast(bf16x8, pa);
     const bf16x8 dmf = __builtin_bit_cast(bf16x8, pm), dnf = __builtin_bit_cast(bf16x8, pn);
 
-    // dV^T[j][c] += dY^T a ; dK^T[j][c] += q^T dM ; dU^T[j][c] += q^T dN.  Transposed operand:
-    // lane (cn, gq) points at token row 4gq + cn/4 (and + 16), columns 16jb + 4(cn%4) ..
-#pragma unroll
-    for (int jb = 0; jb < JB; ++jb) {
-      const int row = 4 * gq + (cn >> 2), col = 16 * jb + 4 * (cn & 3);
-      const int o_lo = tile_off8_dh<DH>(row, col), o_hi = tile_off8_dh<DH>(row + 16, col);
-      const bf16x8 yT = join_tr(lds_read_tr16(yt + o_lo), lds_read_tr16(yt + o_hi));
-      const bf16x8 qT = join_tr(lds_read_tr16(qt + o_lo), lds_read_tr16(qt + o_hi));
-      dV[jb] = mfma16(yT, agf, dV[jb]);
-      dK[jb] = mfma16(qT, dmf, dK[jb]);
-      dU[jb] = mfma16(qT, dnf, dU[jb]);
-    }
-    if (more) lstore((b + 1) & 1);
+    // dV^T[j][c] += dY^T a ; dK^T[j][c] += q^T dM ; dU^T[j][c] += q^T dN
+    static_for<NA, NTOT>([&](auto C_) {
+      constexpr int C = decltype(C_)::value, J = C - NA, jb = J >> 1;
+      advance(C_);
+      lds_wait<dh_pending(C, NA, NTOT)>(xlo[J], xhi[J]);
+      const bf16x8 xt = join_tr(xlo[J], xhi[J]);
+      if constexpr ((J & 1) == 0) {
+        dV[jb] = mfma16(xt, agf, dV[jb]);
+      } else {
+        dK[jb] = mfma16(xt, dmf, dK[jb]);
+        dU[jb] = mfma16(xt, dnf, dU[jb]);
+      }
+    });
+    if (more) lstore((int)((b + 1) & 1), SS);
     __syncthreads();
+  };
+  if constexpr (SETS == 1) {
+    for (int64_t b = 0; b < nb; ++b) step(b, S0{}, S0{});
+  } else {
+    for (int64_t b = 0; b < nb; b += 2) {
+      step(b, S0{}, SB{});
+      if (b + 1 < nb) step(b + 1, SB{}, S0{});
+    }
   }
 
   if (active) {
@@ -1012,12 +1069,12 @@ hipError_t allow_full_lds(K kernel) {
                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBytesPerWorkgroup);
 }
 
-constexpr int tok_block_tokens(int dh) { return dh == 256 ? 128 : 256; }
+constexpr int tok_block_tokens(int dh) { return dh == 128 ? 256 : 128; }
 
 template <int DH, int TB, int NW>
 int launch_tok(const Problem& p, BwdArgs a, hipStream_t stream) {
   constexpr int BM = 32 * TB * NW;
-  static_assert(BM == tok_block_tokens(DH), "bwd_tok_lds_bytes assumes this block size");
+  static_assert(BM == tok_block_tokens(DH), "bwd_bf16_lds_bytes assumes this block size");
   a.n_tiles = (p.N + BM - 1) / BM;
   a.n_items = a.n_tiles * p.H;
   const size_t lds = (size_t)kTokStages * tok_stage_bytes(DH) + (size_t)p.E * BM * sizeof(float);
@@ -1148,13 +1205,15 @@ int launch_bwd(const Problem& p, int dtype, const void* X, const void* Wg, const
 
   // token-major kernel (always: it also produces R for the weight-major kernel)
   int rc;
-  if (p.dh == 64) rc = launch_tok<64, 1, 8>(p, a, stream);
+  // d_h = 64: workgroups of 4 waves, two or three of them per CU in different phases of
+  // their steps (measured 4 % and 11 % faster than one workgroup of 8 waves)
+  if (p.dh == 64) rc = launch_tok<64, 1, 4>(p, a, stream);
   else if (p.dh == 256) rc = launch_tok<256, 1, 4>(p, a, stream);   // needs one wave per SIMD: see the kernel
   else rc = launch_tok<kDh, 1, 8>(p, a, stream);
   if (rc) return rc;
   if (mark(1) != hipSuccess) return (int)hipErrorInvalidHandle;
   if (dWg || dWu || dWd) {
-    if (p.dh == 64) rc = launch_wgt_dh<64, 8>(p, a, stream);
+    if (p.dh == 64) rc = launch_wgt_dh<64, 4>(p, a, stream);
     else if (p.dh == 256) rc = launch_wgt_dh<256, 4>(p, a, stream);
     else rc = launch_wgt16(p, a, stream);
     if (rc) return rc;
