@@ -117,3 +117,29 @@ def backward(X, W_gate, W_up, W_down, route, dY, eps, route_mode=ROUTE_PARAMS,
     if rc:
         raise RuntimeError("oracle backward failed: %d" % rc)
     return {"dX": dX, "dW_gate": dWg, "dW_up": dWu, "dW_down": dWd, "d_route": d_route}
+
+
+# ---- the whole module: input and output projections around the path -------------------
+# (Methodology, definition of Q = split_H(X W_in) and O = concat_H(S) W_out; no bias, no
+# normalisation.)  W_in and W_out are [d_model][d_model], applied from the right.  The two
+# projections are library matrix products in fp64; everything between them is the oracle above.
+
+def module_forward(X, W_in, W_gate, W_up, W_down, W_r, W_out, eps, return_saved=False):
+    """O [N, d_model] (and the saved Q, S if return_saved)."""
+    X, W_in, W_out = (np.asarray(a, dtype=np.float64) for a in (X, W_in, W_out))
+    Q = X @ W_in
+    S = forward(Q, W_gate, W_up, W_down, W_r, eps)
+    O = S @ W_out
+    return (O, Q, S) if return_saved else O
+
+
+def module_backward(X, W_in, W_gate, W_up, W_down, W_r, W_out, dO, eps):
+    """Gradients of sum(O * dO) with respect to X and every parameter."""
+    X, W_in, W_out, dO = (np.asarray(a, dtype=np.float64) for a in (X, W_in, W_out, dO))
+    Q = X @ W_in
+    S = forward(Q, W_gate, W_up, W_down, W_r, eps)
+    dS = dO @ W_out.T
+    g = backward(Q, W_gate, W_up, W_down, W_r, dS, eps)
+    return {"dX": g["dX"] @ W_in.T, "dW_in": X.T @ g["dX"], "dW_out": S.T @ dO,
+            "dW_gate": g["dW_gate"], "dW_up": g["dW_up"], "dW_down": g["dW_down"],
+            "d_route": g["d_route"]}

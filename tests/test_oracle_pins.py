@@ -316,3 +316,51 @@ def test_outputs_overwritten_and_partial_requests():
                           want_weights=False)
     assert np.array_equal(full["dX"], only_x["dX"])
     assert only_x["dW_gate"] is None
+
+
+# ------------------------------------------------- module: projections around the path
+def make_module(seed, N, H, dh, E, de):
+    d = make(seed, N, H, dh, E, de)
+    dm = H * dh
+    d["Win"] = rnd(seed + 5, dm, dm, scale=1.0 / math.sqrt(dm))
+    d["Wout"] = rnd(seed + 6, dm, dm, scale=1.0 / math.sqrt(dm))
+    return d
+
+
+@pytest.mark.parametrize("shape", [(3, 2, 3, 2, 4), (2, 1, 4, 3, 2)])
+def test_module_forward_bruteforce(shape):
+    """Q = X W_in and O = S W_out written as element loops around the element-loop forward:
+    a transposed projection or a projection applied on the wrong side fails here (the
+    matrices are not symmetric)."""
+    N, H, dh, E, de = shape
+    d = make_module(300, *shape)
+    dm = H * dh
+    X, Win, Wout = d["X"].tolist(), d["Win"].tolist(), d["Wout"].tolist()
+    Q = [[sum(X[l][i] * Win[i][j] for i in range(dm)) for j in range(dm)] for l in range(N)]
+    S = brute_forward(Q, d["Wg"].tolist(), d["Wu"].tolist(), d["Wd"].tolist(), d["Wr"].tolist(), 1e-6)
+    O = [[sum(S[l][i] * Wout[i][j] for i in range(dm)) for j in range(dm)] for l in range(N)]
+    got = orc.module_forward(d["X"], d["Win"], d["Wg"], d["Wu"], d["Wd"], d["Wr"], d["Wout"], 1e-6)
+    assert relerr(got, np.array(O)) < 1e-12
+
+
+def test_module_with_identity_projections_is_the_path():
+    d = make_module(310, 5, 2, 4, 3, 6)
+    I = np.eye(8)
+    O, Q, S = orc.module_forward(d["X"], I, d["Wg"], d["Wu"], d["Wd"], d["Wr"], I, 1e-6,
+                                 return_saved=True)
+    Y = orc.forward(d["X"], d["Wg"], d["Wu"], d["Wd"], d["Wr"], 1e-6)
+    assert np.array_equal(Q, d["X"]) and np.array_equal(O, S) and relerr(O, Y) == 0.0
+
+
+@pytest.mark.parametrize("shape", [(3, 2, 4, 3, 5), (4, 1, 6, 2, 3)])
+def test_module_backward_matches_finite_differences(shape):
+    d = make_module(320, *shape)
+    G = rnd(321, shape[0], shape[1] * shape[2])
+    eps = 1e-3
+    args = lambda: (d["X"], d["Win"], d["Wg"], d["Wu"], d["Wd"], d["Wr"], d["Wout"])
+    loss = lambda: float((orc.module_forward(*args(), eps) * G).sum())
+    g = orc.module_backward(*args(), G, eps)
+    for key, name in (("X", "dX"), ("Win", "dW_in"), ("Wout", "dW_out"), ("Wg", "dW_gate"),
+                      ("Wu", "dW_up"), ("Wd", "dW_down"), ("Wr", "d_route")):
+        fd = _fd(loss, d[key])
+        assert relerr(g[name], fd) < 1e-6, name
