@@ -91,6 +91,88 @@ def cpu_baseline(w, d, budget_heads=16, budget_tokens=6144):
     }
 
 
+def module_bench(args, w):
+    """Step = forward + backward of the whole module: Q = X W_in, the fused path, O = S W_out
+    and the four products of the backward around the fused backward.  The fused path alone is
+    timed in the same run; the difference is the time of the six d_model x d_model products."""
+    import torch
+    from paper_2512_06989_amd import inputs, mhffn
+    from tests.helpers import device_inputs
+    d = inputs.make_module_inputs(w, seed=0, with_dy=True)
+    g = device_inputs(d, w.dtype)
+    names = ("X", "W_in", "W_gate", "W_up", "W_down", "W_r", "W_out")
+    a = [g[k] for k in names]
+    core = [g[k] for k in ("X", "W_gate", "W_up", "W_down", "W_r")]
+    desc = mhffn.make_desc(g["X"], g["W_gate"], mhffn.ROUTE_PARAMS, w.eps)
+    ws = torch.empty(max(mhffn.workspace_bytes(desc, mhffn.OP_MODULE_BACKWARD), 256),
+                     dtype=torch.uint8, device="cuda")
+    fws = torch.empty(max(mhffn.workspace_bytes(desc, mhffn.OP_MODULE_FORWARD), 256),
+                      dtype=torch.uint8, device="cuda")
+    acts = {k: torch.empty_like(g["X"]) for k in ("O", "Q", "S")}
+    grads = {k: torch.empty_like(v) for k, v in zip(mhffn.MODULE_GRADS, (
+        g["X"], g["W_in"], g["W_gate"], g["W_up"], g["W_down"], g["W_r"], g["W_out"]))}
+    cgrads = {"dX": grads["dX"], "dW_gate": grads["dW_gate"], "dW_up": grads["dW_up"],
+              "dW_down": grads["dW_down"], "d_route": grads["dW_r"]}
+    stream = torch.cuda.current_stream().cuda_stream
+    hip = HipEvents()
+    K = args.steps
+
+    def mod_fwd():
+        mhffn.module_forward(*a, w.eps, out=acts, workspace=fws)
+
+    def mod_bwd():
+        mhffn.module_backward(*a, acts["Q"], acts["S"], g["dY"], w.eps, out=grads, workspace=ws)
+
+    def core_fwd():
+        mhffn.forward(*core, w.eps, out=acts["S"], workspace=fws)
+
+    def core_bwd():
+        mhffn.backward(*core, g["dY"], w.eps, workspace=ws, out=cgrads)
+
+    def timed(fn):
+        for _ in range(args.warmup):
+            fn()
+        ev = hip.create(2)
+        hip.record(ev[0], stream)
+        for _ in range(K):
+            fn()
+        hip.record(ev[1], stream)
+        torch.cuda.synchronize()
+        return hip.elapsed_ms(ev[0], ev[1]) / K
+
+    t = {"core_fwd": timed(core_fwd), "core_bwd": timed(core_bwd)}
+    # the module step itself, timed as the contract says: K steps between synchronisations
+    for _ in range(args.warmup):
+        mod_fwd(); mod_bwd()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(K):
+        mod_fwd(); mod_bwd()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / K
+    t["module_fwd"], t["module_bwd"] = timed(mod_fwd), timed(mod_bwd)
+    unit = w.unit_flops()
+    proj = 2.0 * w.n_tokens * w.d_model * w.d_model          # one projection-sized product
+    flops = 11.0 * unit + 6.0 * proj
+    gemm_ms = (t["module_fwd"] - t["core_fwd"]) + (t["module_bwd"] - t["core_bwd"])
+    value = flops / (ms_per_step * 1e-3) / 1e12
+    return {
+        "metric": "FlashMHF module fwd/bwd TFLOP/s (projections W_in, W_out around the fused path)",
+        "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": K, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": w.name + " (module)", "n_tokens": w.n_tokens, "d_model": w.d_model,
+                   "n_heads": w.n_heads, "d_head": w.d_head, "n_sub": w.n_sub, "d_sub": w.d_sub,
+                   "step": "module forward + module backward"},
+        "frac_of_bf16_peak": round(value / PEAK_BF16_TFLOPS, 4),
+        "phase_ms": {k: round(v, 4) for k, v in t.items()},
+        "projections": {"count": 6, "ms": round(gemm_ms, 4),
+                        "tflops": round(6.0 * proj / (gemm_ms * 1e-3) / 1e12, 1) if gemm_ms > 0 else None,
+                        "frac_of_bf16_peak": round(6.0 * proj / (gemm_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4)
+                        if gemm_ms > 0 else None},
+    }
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -109,6 +191,9 @@ def main():
                     help="skip the unfused GPU baseline comparison")
     ap.add_argument("--forward-only", action="store_true",
                     help="time the forward alone (step = forward); for profiling")
+    ap.add_argument("--module", action="store_true",
+                    help="time the whole module (W_in and W_out projections around the path) "
+                         "instead; prints its own JSON line")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
@@ -127,6 +212,9 @@ def main():
     w = inputs.WORKLOADS[args.workload]
     if args.tokens:
         w = w.with_tokens(args.tokens)
+    if args.module:
+        print(json.dumps(module_bench(args, w)))
+        return
     d = inputs.make_inputs(w, seed=0, with_dy=True)
     g = device_inputs(d, w.dtype)
     X, Wg, Wu, Wd, Wr, dY = (g[k] for k in ("X", "W_gate", "W_up", "W_down", "W_r", "dY"))

@@ -72,7 +72,9 @@ typedef enum {
   MHFFN_OP_FORWARD = 0,
   MHFFN_OP_BACKWARD = 1,
   MHFFN_OP_UNFUSED_FORWARD = 2,
-  MHFFN_OP_UNFUSED_BACKWARD = 3 /* mhffn_reference_unfused with dY != NULL */
+  MHFFN_OP_UNFUSED_BACKWARD = 3, /* mhffn_reference_unfused with dY != NULL */
+  MHFFN_OP_MODULE_FORWARD = 4,
+  MHFFN_OP_MODULE_BACKWARD = 5
 } mhffn_op;
 
 typedef struct {
@@ -163,6 +165,34 @@ int mhffn_reference_unfused(const mhffn_desc* desc, const void* X,
                             void* dW_up, void* dW_down, void* d_route,
                             void* workspace, size_t workspace_bytes,
                             void* hip_stream);
+
+/* The whole module around the fused path (Methodology: per-head inputs
+ * Q = split_H(X W_in), output O = concat_H(S) W_out, both projections d_model x
+ * d_model, no bias):
+ *     Q = X W_in;   S = mhffn_forward(Q);   O = S W_out.
+ * W_in, W_out: [d_model][d_model] row-major, applied from the right (row i = input
+ * feature i), dtype = desc.dtype.  desc.ld_x / ld_y are the row strides of X and O;
+ * desc.route_mode must be MHFFN_ROUTE_PARAMS.  Q and S are outputs too, dense
+ * [n_tokens][d_model], required: they are what a training step keeps for
+ * mhffn_module_backward (two d_model-wide activations; nothing d_ff-wide exists).
+ * Shape support is that of mhffn_forward. */
+int mhffn_module_forward(const mhffn_desc* desc, const void* X, const void* W_in,
+                         const void* W_gate, const void* W_up, const void* W_down,
+                         const void* W_r, const void* W_out, void* O, void* Q, void* S,
+                         void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Backward of mhffn_module_forward from X, the weights, the saved Q and S, and dO:
+ *     dS = dO W_out^T;  dW_out = S^T dO;  (dQ, dW_gate, dW_up, dW_down, dW_r) =
+ *     mhffn_backward(Q, dS);  dW_in = X^T dQ;  dX = dQ W_in^T.
+ * Any gradient pointer may be NULL => not computed.  dS and dQ pass through the
+ * workspace (MHFFN_OP_MODULE_BACKWARD: two [n_tokens][d_model] buffers plus the
+ * fused backward's own scratch).  Shape support is that of mhffn_backward. */
+int mhffn_module_backward(const mhffn_desc* desc, const void* X, const void* W_in,
+                          const void* W_gate, const void* W_up, const void* W_down,
+                          const void* W_r, const void* W_out, const void* Q, const void* S,
+                          const void* dO, void* dX, void* dW_in, void* dW_gate, void* dW_up,
+                          void* dW_down, void* dW_r, void* dW_out, void* workspace,
+                          size_t workspace_bytes, void* hip_stream);
 
 /* Static, human-readable name of a status code. */
 const char* mhffn_status_string(int status);

@@ -90,6 +90,12 @@ size_t mhffn_workspace_bytes(const mhffn_desc* desc, int op) {
     case MHFFN_OP_BACKWARD:
       if (check_fused_shape(desc, p, true) != MHFFN_OK) return 0;
       return mhffn::bwd_workspace_bytes(p, desc->dtype);
+    case MHFFN_OP_MODULE_FORWARD:
+      if (p.route_mode != MHFFN_ROUTE_PARAMS || check_fused_shape(desc, p) != MHFFN_OK) return 0;
+      return mhffn::module_workspace_bytes(p, desc->dtype, false);
+    case MHFFN_OP_MODULE_BACKWARD:
+      if (p.route_mode != MHFFN_ROUTE_PARAMS || check_fused_shape(desc, p, true) != MHFFN_OK) return 0;
+      return mhffn::module_workspace_bytes(p, desc->dtype, true);
     case MHFFN_OP_UNFUSED_FORWARD: return mhffn::unfused_workspace_bytes(p, desc->dtype, false);
     case MHFFN_OP_UNFUSED_BACKWARD: return mhffn::unfused_workspace_bytes(p, desc->dtype, true);
     default: return 0;
@@ -181,6 +187,58 @@ int mhffn_reference_unfused(const mhffn_desc* desc, const void* X, const void* W
   if (rc) return rc;
   const int e = mhffn::launch_unfused(p, desc->dtype, X, W_gate, W_up, W_down, route, Y, dY, dX,
                                       dW_gate, dW_up, dW_down, d_route, workspace, hip_stream);
+  if (e == -1) return MHFFN_ERR_UNSUPPORTED;
+  return e == 0 ? MHFFN_OK : MHFFN_ERR_LAUNCH;
+}
+
+int mhffn_module_forward(const mhffn_desc* desc, const void* X, const void* W_in,
+                         const void* W_gate, const void* W_up, const void* W_down,
+                         const void* W_r, const void* W_out, void* O, void* Q, void* S,
+                         void* workspace, size_t workspace_bytes, void* hip_stream) {
+  Problem p;
+  int rc = check_desc(desc, &p);
+  if (rc) return rc;
+  if (p.route_mode != MHFFN_ROUTE_PARAMS) return MHFFN_ERR_UNSUPPORTED;
+  const bool empty = (p.N == 0);
+  if (!W_in || !W_gate || !W_up || !W_down || !W_r || !W_out) return MHFFN_ERR_NULL;
+  if (!empty && (!X || !O || !Q || !S)) return MHFFN_ERR_NULL;
+  const void* ptrs[] = {X, W_in, W_gate, W_up, W_down, W_r, W_out, O, Q, S};
+  for (const void* q : ptrs)
+    if (!aligned16(q)) return MHFFN_ERR_ALIGN;
+  rc = check_fused_shape(desc, p);
+  if (rc) return rc;
+  if (empty) return MHFFN_OK;
+  rc = check_workspace(mhffn::module_workspace_bytes(p, desc->dtype, false), workspace, workspace_bytes);
+  if (rc) return rc;
+  const int e = mhffn::launch_module_forward(p, desc->dtype, X, W_in, W_gate, W_up, W_down, W_r,
+                                             W_out, O, Q, S, workspace, hip_stream);
+  return e == 0 ? MHFFN_OK : MHFFN_ERR_LAUNCH;
+}
+
+int mhffn_module_backward(const mhffn_desc* desc, const void* X, const void* W_in,
+                          const void* W_gate, const void* W_up, const void* W_down,
+                          const void* W_r, const void* W_out, const void* Q, const void* S,
+                          const void* dO, void* dX, void* dW_in, void* dW_gate, void* dW_up,
+                          void* dW_down, void* dW_r, void* dW_out, void* workspace,
+                          size_t workspace_bytes, void* hip_stream) {
+  Problem p;
+  int rc = check_desc(desc, &p);
+  if (rc) return rc;
+  if (p.route_mode != MHFFN_ROUTE_PARAMS) return MHFFN_ERR_UNSUPPORTED;
+  const bool empty = (p.N == 0);
+  if (!W_in || !W_gate || !W_up || !W_down || !W_r || !W_out) return MHFFN_ERR_NULL;
+  if (!empty && (!X || !Q || !S || !dO)) return MHFFN_ERR_NULL;
+  const void* ptrs[] = {X, W_in, W_gate, W_up, W_down, W_r, W_out, Q, S, dO,
+                        dX, dW_in, dW_gate, dW_up, dW_down, dW_r, dW_out};
+  for (const void* q : ptrs)
+    if (!aligned16(q)) return MHFFN_ERR_ALIGN;
+  rc = check_fused_shape(desc, p, true);
+  if (rc) return rc;
+  rc = check_workspace(mhffn::module_workspace_bytes(p, desc->dtype, true), workspace, workspace_bytes);
+  if (rc) return rc;
+  const int e = mhffn::launch_module_backward(p, desc->dtype, X, W_in, W_gate, W_up, W_down, W_r,
+                                              W_out, Q, S, dO, dX, dW_in, dW_gate, dW_up, dW_down,
+                                              dW_r, dW_out, workspace, hip_stream);
   if (e == -1) return MHFFN_ERR_UNSUPPORTED;
   return e == 0 ? MHFFN_OK : MHFFN_ERR_LAUNCH;
 }

@@ -1136,6 +1136,14 @@ int launch_route(const Problem& p, const BwdArgs& a, hipStream_t stream) {
 
 }  // namespace
 
+int launch_fill_zero(void* p, size_t bytes, void* stream) {
+  const size_t words = bytes / 4;
+  if (!p || !words) return 0;
+  hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)((words + 255) / 256)), dim3(256), 0,
+                     static_cast<hipStream_t>(stream), static_cast<uint32_t*>(p), words);
+  return (int)hipGetLastError();
+}
+
 // d_h = 256: the routing-gradient kernel keeps 8 accumulator tiles per 32 sub-networks
 int bwd_bf16_max_sub(const Problem& p) { return p.dh == 256 ? 64 : kRouteMaxSub; }
 

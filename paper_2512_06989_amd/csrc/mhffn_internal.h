@@ -57,4 +57,26 @@ int launch_unfused(const Problem& p, int dtype, const void* X, const void* Wg,
                    const void* dY, void* dX, void* dWg, void* dWu, void* dWd,
                    void* d_route, void* ws, void* stream);
 
+// Zero `bytes` (a multiple of 4) of device memory with a fill kernel (safe under graph capture).
+int launch_fill_zero(void* p, size_t bytes, void* stream);
+
+// Plain strided product C[m][n] = sum_k A(m,k) B(n,k) on the generic MFMA GEMM of the
+// unfused baseline (element strides; n is contiguous in C).  M, N or K of 0 launches nothing
+// (K = 0 leaves C untouched: callers zero-fill themselves).
+int launch_gemm(int dtype, const void* A, int64_t a_ms, int64_t a_ks, const void* B, int64_t b_ns,
+                int64_t b_ks, void* C, int64_t c_ms, int64_t M, int64_t N, int64_t K, void* stream);
+
+// ---- whole module: projections around the fused path -------------------------
+// Problem::ldx / ldy are the row strides of the module's input X (dX) and output O (dO);
+// Q and S are dense [N][H*d_h].
+size_t module_workspace_bytes(const Problem& p, int dtype, bool backward);
+int launch_module_forward(const Problem& p, int dtype, const void* X, const void* W_in,
+                          const void* Wg, const void* Wu, const void* Wd, const void* Wr,
+                          const void* W_out, void* O, void* Q, void* S, void* ws, void* stream);
+int launch_module_backward(const Problem& p, int dtype, const void* X, const void* W_in,
+                           const void* Wg, const void* Wu, const void* Wd, const void* Wr,
+                           const void* W_out, const void* Q, const void* S, const void* dO,
+                           void* dX, void* dW_in, void* dWg, void* dWu, void* dWd, void* dWr,
+                           void* dW_out, void* ws, void* stream);
+
 }  // namespace mhffn

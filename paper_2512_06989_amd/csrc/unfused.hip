@@ -596,6 +596,19 @@ size_t unfused_workspace_bytes(const Problem& p, int dtype, bool backward) {
   return make_layout(p, dtype == 1 ? 2 : 4, backward).total;
 }
 
+int launch_gemm(int dtype, const void* A, int64_t a_ms, int64_t a_ks, const void* B, int64_t b_ns,
+                int64_t b_ks, void* C, int64_t c_ms, int64_t M, int64_t N, int64_t K, void* stream) {
+  GemmArgs g{};
+  g.A = A; g.B = B; g.A2 = nullptr; g.B2 = nullptr; g.C = C;
+  g.M = M; g.N = N; g.K = K;
+  g.a_ms = a_ms; g.a_ks = a_ks; g.a_bs = 0;
+  g.b_ns = b_ns; g.b_ks = b_ks; g.b_bs = 0;
+  g.c_ms = c_ms; g.c_bs = 0;
+  g.accumulate = 0;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  return dtype == 1 ? run_gemm<uint16_t>(g, 1, st) : run_gemm<float>(g, 1, st);
+}
+
 int launch_unfused(const Problem& p, int dtype, const void* X, const void* Wg, const void* Wu,
                    const void* Wd, const void* route, void* Y, const void* dY, void* dX,
                    void* dWg, void* dWu, void* dWd, void* d_route, void* ws, void* stream) {

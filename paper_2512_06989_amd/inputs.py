@@ -14,6 +14,7 @@ import math
 import numpy as np
 
 STREAM_X, STREAM_WG, STREAM_WU, STREAM_WD, STREAM_WR, STREAM_DY, STREAM_R = range(7)
+STREAM_WIN, STREAM_WOUT = 7, 8
 
 
 @dataclass(frozen=True)
@@ -122,4 +123,15 @@ def make_inputs(w: Workload, seed: int = 0, with_dy=None, route_weights: bool = 
         g = np.random.Generator(np.random.Philox(key=[int(seed), STREAM_R]))
         r = g.random(size=(w.n_tokens, w.n_heads, w.n_sub), dtype=np.float32) + np.float32(0.05)
         out["R"] = (r / r.sum(axis=-1, keepdims=True)).astype(np.float32)
+    return out
+
+
+def make_module_inputs(w: Workload, seed: int = 0, with_dy=None):
+    """make_inputs plus the module's projections W_in, W_out [d_model, d_model] ~ N(0, 1/d_model)
+    (so that Q = X W_in has the unit scale the path's own inputs have), rounded to w.dtype.
+    X is then the module's input and dY the gradient of its output O."""
+    out = make_inputs(w, seed=seed, with_dy=with_dy)
+    std = 1.0 / math.sqrt(w.d_model)
+    out["W_in"] = round_to(_normal(seed, STREAM_WIN, (w.d_model, w.d_model), std), w.dtype)
+    out["W_out"] = round_to(_normal(seed, STREAM_WOUT, (w.d_model, w.d_model), std), w.dtype)
     return out

@@ -15,8 +15,10 @@ OK = 0
 F32, BF16 = 0, 1
 ROUTE_PARAMS, ROUTE_WEIGHTS = 0, 1
 OP_FORWARD, OP_BACKWARD, OP_UNFUSED_FORWARD, OP_UNFUSED_BACKWARD = 0, 1, 2, 3
+OP_MODULE_FORWARD, OP_MODULE_BACKWARD = 4, 5
 EXPORTS = ("mhffn_workspace_bytes", "mhffn_forward", "mhffn_backward", "mhffn_backward_phases",
-           "mhffn_reference_unfused", "mhffn_status_string", "mhffn_version")
+           "mhffn_reference_unfused", "mhffn_module_forward", "mhffn_module_backward",
+           "mhffn_status_string", "mhffn_version")
 
 
 class Desc(ctypes.Structure):
@@ -59,6 +61,10 @@ def load():
     lib.mhffn_backward_phases.restype = ctypes.c_int
     lib.mhffn_reference_unfused.argtypes = [dp] + [vp] * 12 + [vp, sz, vp]
     lib.mhffn_reference_unfused.restype = ctypes.c_int
+    lib.mhffn_module_forward.argtypes = [dp] + [vp] * 10 + [vp, sz, vp]
+    lib.mhffn_module_forward.restype = ctypes.c_int
+    lib.mhffn_module_backward.argtypes = [dp] + [vp] * 17 + [vp, sz, vp]
+    lib.mhffn_module_backward.restype = ctypes.c_int
     lib.mhffn_status_string.argtypes = [ctypes.c_int]
     lib.mhffn_status_string.restype = ctypes.c_char_p
     lib.mhffn_version.restype = ctypes.c_char_p
@@ -180,3 +186,45 @@ def reference_unfused(X, W_gate, W_up, W_down, route, eps=1e-6, route_mode=ROUTE
     if dY is None:
         return Y
     return Y, {k: out[k] for k in want}
+
+
+MODULE_GRADS = ("dX", "dW_in", "dW_gate", "dW_up", "dW_down", "dW_r", "dW_out")
+
+
+def module_forward(X, W_in, W_gate, W_up, W_down, W_r, W_out, eps=1e-6, out=None, stream=None,
+                   workspace=None):
+    """The whole module: O = fused(X W_in) W_out.  Returns (O, Q, S); Q and S are the two
+    d_model-wide activations that module_backward needs."""
+    out = dict(out or {})
+    N, dm = X.shape
+    for k in ("O", "Q", "S"):
+        if k not in out:
+            out[k] = torch.empty((N, dm), dtype=X.dtype, device=X.device)
+    d = make_desc(X, W_gate, ROUTE_PARAMS, eps, out["O"])
+    workspace, have = _workspace(d, OP_MODULE_FORWARD, X.device, workspace)
+    rc = load().mhffn_module_forward(ctypes.byref(d), _p(X), _p(W_in), _p(W_gate), _p(W_up),
+                                     _p(W_down), _p(W_r), _p(W_out), _p(out["O"]), _p(out["Q"]),
+                                     _p(out["S"]), _p(workspace), have, _stream(stream))
+    if rc != OK:
+        raise MhffnError(rc, "mhffn_module_forward")
+    return out["O"], out["Q"], out["S"]
+
+
+def module_backward(X, W_in, W_gate, W_up, W_down, W_r, W_out, Q, S, dO, eps=1e-6,
+                    want=MODULE_GRADS, out=None, stream=None, workspace=None):
+    """Backward of module_forward from the saved Q and S.  Returns a dict of gradients."""
+    out = dict(out or {})
+    like = {"dX": X, "dW_in": W_in, "dW_gate": W_gate, "dW_up": W_up, "dW_down": W_down,
+            "dW_r": W_r, "dW_out": W_out}
+    for k in want:
+        if k not in out:
+            out[k] = torch.empty_like(like[k])
+    d = make_desc(X, W_gate, ROUTE_PARAMS, eps, dO)
+    workspace, have = _workspace(d, OP_MODULE_BACKWARD, X.device, workspace)
+    rc = load().mhffn_module_backward(
+        ctypes.byref(d), _p(X), _p(W_in), _p(W_gate), _p(W_up), _p(W_down), _p(W_r), _p(W_out),
+        _p(Q), _p(S), _p(dO), *[_p(out.get(k)) for k in MODULE_GRADS], _p(workspace), have,
+        _stream(stream))
+    if rc != OK:
+        raise MhffnError(rc, "mhffn_module_backward")
+    return {k: out[k] for k in want}

@@ -142,3 +142,36 @@ def test_unfused_rejects_bad_arguments():
     args = [FAKE] * 12
     assert lib.mhffn_reference_unfused(ctypes.byref(desc()), *args, None, 0, None) == 5
     assert lib.mhffn_reference_unfused(ctypes.byref(desc(d_head=12)), *args, FAKE, 1 << 40, None) == 3
+
+
+def test_module_entry_points_validate_before_launching():
+    lib = mhffn.load()
+    d = desc(n_tokens=16384, n_heads=16, n_sub=44)
+    fwd_args, bwd_args = [FAKE] * 10, [FAKE] * 17
+    # big batch: the forward needs no scratch, the backward needs dS, dQ and the fused scratch
+    assert mhffn.workspace_bytes(d, mhffn.OP_MODULE_FORWARD) == 0
+    act = 16384 * 2048 * 2
+    need = mhffn.workspace_bytes(d, mhffn.OP_MODULE_BACKWARD)
+    assert need == 2 * act + mhffn.workspace_bytes(d, mhffn.OP_BACKWARD)
+    assert lib.mhffn_module_backward(ctypes.byref(d), *bwd_args, None, 0, None) == 5
+    assert lib.mhffn_module_backward(ctypes.byref(d), *bwd_args, FAKE, need - 1, None) == 5
+    # the module computes its gating weights itself
+    dw = desc(route_mode=mhffn.ROUTE_WEIGHTS)
+    assert lib.mhffn_module_forward(ctypes.byref(dw), *fwd_args, None, 0, None) == 3
+    assert lib.mhffn_module_backward(ctypes.byref(dw), *bwd_args, FAKE, 1 << 40, None) == 3
+    assert mhffn.workspace_bytes(dw, mhffn.OP_MODULE_BACKWARD) == 0
+    # required pointers: X, the seven weights, O, Q, S
+    for i in range(10):
+        a = list(fwd_args)
+        a[i] = None
+        assert lib.mhffn_module_forward(ctypes.byref(d), *a, None, 0, None) == 1
+        a[i] = ctypes.c_void_p(0x10008)
+        assert lib.mhffn_module_forward(ctypes.byref(d), *a, None, 0, None) == 4
+    for i in range(10):   # X .. dO are required, the gradient pointers are optional
+        a = list(bwd_args)
+        a[i] = None
+        assert lib.mhffn_module_backward(ctypes.byref(d), *a, FAKE, 1 << 40, None) == 1
+    # shapes the fused kernels do not take
+    assert lib.mhffn_module_forward(ctypes.byref(desc(d_head=96)), *fwd_args, None, 0, None) == 3
+    # empty batch: nothing to launch in the forward
+    assert lib.mhffn_module_forward(ctypes.byref(desc(n_tokens=0)), *fwd_args, None, 0, None) == 0

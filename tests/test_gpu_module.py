@@ -1,0 +1,86 @@
+"""GPU parity of the whole module (projections W_in, W_out around the fused path) against
+the fp64 oracle, through the C ABI."""
+import numpy as np
+import pytest
+
+from oracle import mhffn_oracle as orc
+from paper_2512_06989_amd import inputs, mhffn
+from tests.helpers import TOL, device_inputs, relerr, small_workload, to_host
+
+pytestmark = pytest.mark.gpu
+# Tolerance of the bf16 module: the path's own bound (5e-3) covers inputs that are exact in
+# bf16.  Here the path's input Q and its output gradient dS are themselves products rounded
+# to bf16 (relative error 2^-9 / sqrt(3) = 1.1e-3 per element, which passes through both the
+# gate and the up product and through every gradient), and S and dQ are rounded once more
+# before the outer products: four more roundings in quadrature on top of the path's measured
+# 2.5e-3..3.5e-3 give up to about 5.5e-3 (measured: 3.9e-3 to 5.2e-3).  Bound used: 8e-3.
+# The fp32 module keeps the path's fp32 bound.
+MODULE_TOL = {"f32": TOL["f32"], "bf16": 8e-3}
+ARGS = ("X", "W_in", "W_gate", "W_up", "W_down", "W_r", "W_out")
+
+
+def run_module(w, seed=0, want=mhffn.MODULE_GRADS):
+    import torch
+    d = inputs.make_module_inputs(w, seed=seed, with_dy=True)
+    g = device_inputs(d, w.dtype)
+    O, Q, S = mhffn.module_forward(*[g[k] for k in ARGS], w.eps)
+    grads = mhffn.module_backward(*[g[k] for k in ARGS], Q, S, g["dY"], w.eps, want=want)
+    torch.cuda.synchronize()
+    return d, to_host(O), {k: to_host(v) for k, v in grads.items()}
+
+
+def oracle_module(d, w):
+    a = [d[k] for k in ARGS]
+    O = orc.module_forward(*a, w.eps)
+    g = orc.module_backward(*a, d["dY"], w.eps)
+    g["dW_r"] = g.pop("d_route")
+    return O, g
+
+
+@pytest.mark.parametrize("dtype,N,H,dh,E,de", [
+    ("f32", 150, 2, 128, 3, 64), ("f32", 33, 3, 72, 5, 40),
+    ("bf16", 1, 1, 128, 2, 32), ("bf16", 257, 2, 128, 4, 128), ("bf16", 1000, 3, 128, 5, 64),
+    ("bf16", 300, 2, 64, 6, 192), ("bf16", 300, 1, 256, 3, 96), ("bf16", 64, 4, 128, 8, 128)])
+def test_module_forward_and_backward(dtype, N, H, dh, E, de):
+    w = small_workload("module", N, H, E, de, dtype, dh=dh, backward=True)
+    d, O, grads = run_module(w, seed=N + dh)
+    ref_o, ref_g = oracle_module(d, w)
+    tol = MODULE_TOL[dtype]
+    assert relerr(O, ref_o) <= tol
+    errs = {k: relerr(grads[k], ref_g[k]) for k in grads}
+    assert all(e <= tol for e in errs.values()), str(errs)
+
+
+def test_partial_gradient_requests_and_strided_rows():
+    """Only dX (no weight gradients); X, O, dO, dX rows wider than d_model."""
+    import torch
+    w = small_workload("module_strided", 200, 2, 4, 64, "bf16", backward=True)
+    d = inputs.make_module_inputs(w, seed=3, with_dy=True)
+    g = device_inputs(d, w.dtype)
+    dm = w.d_model
+    pad = lambda t, fill: torch.cat([t, torch.full((t.shape[0], 64), fill, dtype=t.dtype, device=t.device)], 1)
+    Xp, dOp = pad(g["X"], 3.0), pad(g["dY"], 5.0)
+    Op = torch.full((w.n_tokens, dm + 64), 7.0, dtype=torch.bfloat16, device="cuda")
+    dXp = torch.full((w.n_tokens, dm + 64), 9.0, dtype=torch.bfloat16, device="cuda")
+    a = [Xp[:, :dm]] + [g[k] for k in ARGS[1:]]
+    O, Q, S = mhffn.module_forward(*a, w.eps, out={"O": Op[:, :dm]})
+    grads = mhffn.module_backward(*a, Q, S, dOp[:, :dm], w.eps, want=("dX",), out={"dX": dXp[:, :dm]})
+    torch.cuda.synchronize()
+    assert torch.all(Op[:, dm:] == 7.0) and torch.all(dXp[:, dm:] == 9.0)
+    ref_o, ref_g = oracle_module(d, w)
+    assert relerr(to_host(O), ref_o) <= MODULE_TOL["bf16"]
+    assert relerr(to_host(grads["dX"]), ref_g["dX"]) <= MODULE_TOL["bf16"]
+
+
+def test_full_size_forward_on_sampled_tokens():
+    """The 1.3B shape: the module is token-wise, so the oracle evaluates sampled tokens."""
+    import torch
+    w = inputs.WORKLOADS["1p3b_fwdbwd"]
+    d = inputs.make_module_inputs(w, seed=0, with_dy=False)
+    g = device_inputs(d, w.dtype)
+    O, Q, S = mhffn.module_forward(*[g[k] for k in ARGS], w.eps)
+    torch.cuda.synchronize()
+    rows = np.array([0, 1, 255, 256, 4097, 9999, 16383])
+    ref = orc.module_forward(d["X"][rows], *[d[k] for k in ARGS[1:]], w.eps)
+    assert np.all(np.isfinite(to_host(O)))
+    assert relerr(to_host(O)[rows], ref) <= MODULE_TOL["bf16"]
