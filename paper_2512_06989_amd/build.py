@@ -15,7 +15,7 @@ LIB = os.path.join(HERE, "libmhffn.so")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 SOURCES = ["api.cpp", "module.cpp", "fwd_bf16.hip", "fwd_f32.hip", "bwd.hip", "bwd_f32.hip",
-           "unfused.hip"]
+           "unfused.hip", "gemm_bf16.hip"]
 # Packed-fp32 VALU forms are switched off for all device code.
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-x", "hip",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

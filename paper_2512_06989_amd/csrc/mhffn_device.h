@@ -161,6 +161,12 @@ __device__ __forceinline__ s16x4 lds_read_tr16_untracked(unsigned lds_addr) {
   asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(v) : "v"(lds_addr), "n"(OFFSET));
   return v;
 }
+template <int OFFSET>
+__device__ __forceinline__ s16x4 lds_read_b64_untracked(unsigned lds_addr) {
+  s16x4 v;
+  asm volatile("ds_read_b64 %0, %1 offset:%2" : "=v"(v) : "v"(lds_addr), "n"(OFFSET));
+  return v;
+}
 template <int N, typename T0>
 __device__ __forceinline__ void lds_wait(T0& a) {
   asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(a) : "n"(N));

@@ -66,6 +66,18 @@ int launch_fill_zero(void* p, size_t bytes, void* stream);
 int launch_gemm(int dtype, const void* A, int64_t a_ms, int64_t a_ks, const void* B, int64_t b_ns,
                 int64_t b_ks, void* C, int64_t c_ms, int64_t M, int64_t N, int64_t K, void* stream);
 
+// Tuned bf16 product C[m][n] = sum_k A(m,k) B(n,k) (C row-major, ldc).  a_tr / b_tr: the
+// operand is stored with its row index contiguous ([K][rows], leading dimension = row
+// stride of k) instead of k contiguous ([rows][K]).  Forms: (false,true), (false,false),
+// (true,true).  gemm_bf16_supported() says whether sizes and alignment fit the kernel.
+bool gemm_bf16_supported(bool a_tr, bool b_tr, const void* A, int64_t lda, const void* B,
+                         int64_t ldb, const void* C, int64_t ldc, int64_t M, int64_t N, int64_t K);
+// Scratch (fp32 partial outputs, 256-byte aligned) when the contraction is split over
+// workgroups because the output tiles alone cannot fill the chip; 0 otherwise.
+size_t gemm_bf16_workspace_bytes(int64_t M, int64_t N, int64_t K);
+int launch_gemm_bf16(bool a_tr, bool b_tr, const void* A, int64_t lda, const void* B, int64_t ldb,
+                     void* C, int64_t ldc, int64_t M, int64_t N, int64_t K, void* ws, void* stream);
+
 // ---- whole module: projections around the fused path -------------------------
 // Problem::ldx / ldy are the row strides of the module's input X (dX) and output O (dO);
 // Q and S are dense [N][H*d_h].

@@ -152,7 +152,10 @@ def test_module_entry_points_validate_before_launching():
     assert mhffn.workspace_bytes(d, mhffn.OP_MODULE_FORWARD) == 0
     act = 16384 * 2048 * 2
     need = mhffn.workspace_bytes(d, mhffn.OP_MODULE_BACKWARD)
-    assert need == 2 * act + mhffn.workspace_bytes(d, mhffn.OP_BACKWARD)
+    # dS, dQ, the fused scratch, and fp32 partial tiles of the two d_model x d_model weight
+    # gradients (their contraction over the tokens is split over a few workgroups)
+    partials = need - 2 * act - mhffn.workspace_bytes(d, mhffn.OP_BACKWARD)
+    assert 0 <= partials <= 16 * 2048 * 2048 * 4 and partials % (2048 * 2048 * 4) == 0
     assert lib.mhffn_module_backward(ctypes.byref(d), *bwd_args, None, 0, None) == 5
     assert lib.mhffn_module_backward(ctypes.byref(d), *bwd_args, FAKE, need - 1, None) == 5
     # the module computes its gating weights itself
