@@ -84,3 +84,25 @@ def test_full_size_forward_on_sampled_tokens():
     ref = orc.module_forward(d["X"][rows], *[d[k] for k in ARGS[1:]], w.eps)
     assert np.all(np.isfinite(to_host(O)))
     assert relerr(to_host(O)[rows], ref) <= MODULE_TOL["bf16"]
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_empty_batch_gives_zero_parameter_gradients(dtype):
+    """N = 0: nothing is read, O and dX are empty, all seven parameter gradients are zero."""
+    import torch
+    td = torch.bfloat16 if dtype == "bf16" else torch.float32
+    H, E, de, dh = 2, 3, 64, 128
+    dm = H * dh
+    X = torch.empty(0, dm, dtype=td, device="cuda")
+    W = [torch.randn(H, E, de, dh, device="cuda").to(td) for _ in range(3)]
+    Wr = torch.randn(H, dh, E, device="cuda").to(td)
+    Win, Wout = (torch.randn(dm, dm, device="cuda").to(td) for _ in range(2))
+    O, Q, S = mhffn.module_forward(X, Win, *W, Wr, Wout)
+    assert O.shape == (0, dm)
+    like = {"dW_in": Win, "dW_gate": W[0], "dW_up": W[1], "dW_down": W[2], "dW_r": Wr, "dW_out": Wout}
+    out = {k: torch.full_like(t, 3.0) for k, t in like.items()}
+    out["dX"] = torch.empty_like(X)
+    res = mhffn.module_backward(X, Win, *W, Wr, Wout, Q, S, X.clone(), out=out)
+    torch.cuda.synchronize()
+    for k in like:
+        assert torch.count_nonzero(res[k]) == 0, k
