@@ -40,7 +40,7 @@ constexpr int kStages = 2;
 //   SiLU(m) n r = m n r / (1 + 2^(-m log2 e)) = m n * rcp((1 + t) / r),   (1 + t)/r = fma(t, 1/r, 1/r)
 // four full-rate and two transcendental VALU instructions per element.
 __device__ __forceinline__ float inv_weight(float r) {
-  const float v = 1.0f / r;
+  const float v = __builtin_amdgcn_rcpf(r);   // 1 ulp; a full-precision division is ten instructions
   return fminf(fmaxf(v, -1e30f), 1e30f);
 }
 #define MHFFN_SB() __builtin_amdgcn_sched_barrier(0)
@@ -366,6 +366,8 @@ constexpr int kPipeRing = kPipeStages * kPipeTile;  // one ring per tensor: K | 
 constexpr int kPipeWaves = 8;
 constexpr int kPipeBM = 32 * kPipeWaves;
 constexpr int kPipeMaxSub = (kLdsBytesPerWorkgroup - 3 * kPipeRing) / (kPipeBM * 4);
+constexpr int kPipeMaxSubStatic = 64;   // = kPipeMaxSub, as a literal for array bounds
+static_assert(kPipeMaxSub == kPipeMaxSubStatic, "gating code is written for up to two blocks of 32");
 
 __global__ __launch_bounds__(64 * kPipeWaves) void fwd_bf16_pipe_kernel(FwdArgs a) {
   constexpr int BM = kPipeBM;
@@ -408,10 +410,10 @@ __global__ __launch_bounds__(64 * kPipeWaves) void fwd_bf16_pipe_kernel(FwdArgs 
     global_to_lds_16B(Uh + off, dst + kPipeRing);
     global_to_lds_16B(Vh + off, dst + 2 * kPipeRing);
   };
-  dma(0, 0);
-  if (T > 1) dma(1, 1);
-  if (T > 2) dma(2, 2);
-
+  // Order of the first requests: the token rows and W_r first, the weight tiles after them.
+  // Loads return in order, so the gating arithmetic below waits only for the two small ones
+  // and runs while the first tiles are still on their way (with few tokens the kernel is
+  // little more than this prologue: the first tiles take about 5 us to arrive).
   // ---- q fragments (B operands), resident for the whole kernel -------------
   bf16x8 q[8];
   {
@@ -432,35 +434,77 @@ __global__ __launch_bounds__(64 * kPipeWaves) void fwd_bf16_pipe_kernel(FwdArgs 
     const int EB = (E + 31) >> 5;
     auto wr_off = [&](int e, int chunk) { return (e >> 5) * kPipeRing + 3 * kPipeTile + tile_off(e & 31, chunk); };
     const uint16_t* Wr = reinterpret_cast<const uint16_t*>(a.route) + (size_t)h * kDh * E;
-    for (int idx = tid; idx < kDh * E; idx += THREADS) {
-      const int j = idx / E, e = idx - j * E;
-      *reinterpret_cast<uint16_t*>(smem + wr_off(e, j >> 3) + (j & 7) * 2) = Wr[idx];
+    // W_r[h] is [128][E] in memory and wanted as [E][128]: 16-byte loads (8 consecutive
+    // elements of the flat array, E need not divide 8; 16 E chunks, at most two per thread
+    // for E <= 64), then the tile requests, then 2-byte transposing stores
+    constexpr int kWrIter = (kDh * kPipeMaxSubStatic / 8 + THREADS - 1) / THREADS;
+    u32x4 wv[kWrIter];
+#pragma unroll
+    for (int it = 0; it < kWrIter; ++it) {
+      const int c = tid + it * THREADS;
+      wv[it] = u32x4{0, 0, 0, 0};
+      if (c < kDh * E / 8) wv[it] = *reinterpret_cast<const u32x4*>(Wr + 8 * c);
+    }
+    dma(0, 0);
+    if (T > 1) dma(1, 1);
+    if (T > 2) dma(2, 2);
+#pragma unroll
+    for (int it = 0; it < kWrIter; ++it) {
+      const int c = tid + it * THREADS;
+      if (c < kDh * E / 8) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const int idx = 8 * c + i;
+          const int j = idx / E, e = idx - j * E;
+          const uint16_t w = (uint16_t)(wv[it][i >> 1] >> (16 * (i & 1)));
+          *reinterpret_cast<uint16_t*>(smem + wr_off(e, j >> 3) + (j & 7) * 2) = w;
+        }
+      }
     }
     for (int idx = tid; idx < (32 * EB - E) * kDh; idx += THREADS) {
       const int e = E + idx / kDh, j = idx % kDh;
       *reinterpret_cast<uint16_t*>(smem + wr_off(e, j >> 3) + (j & 7) * 2) = 0;
     }
     __syncthreads();
-    float zsum = 0.f, inv = 0.f;
-    for (int pass = 0; pass < (active ? 2 : 0); ++pass) {   // pass 0: Z = sum_e sigmoid(p_e); pass 1: r_e
-      for (int eb = 0; eb < EB; ++eb) {
-        f32x16 acc = {0};
+    // One sweep: the logits of all sub-networks (up to two blocks of 32: this kernel takes
+    // E <= 64) on two independent accumulators, their sigmoids kept in registers, then the
+    // normalisation.
+    if (active) {
+      f32x16 acc[2] = {f32x16{0}, f32x16{0}};
+      bf16x8 af[2][8];   // all operand reads first: sixteen LDS latencies overlap instead of adding up
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks) {
-          const bf16x8 af = *reinterpret_cast<const bf16x8*>(smem + wr_off(32 * eb + r, 2 * ks + g));
-          acc = mfma32(af, q[ks], acc);
-        }
+      for (int eb = 0; eb < 2; ++eb)
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks)
+          af[eb][ks] = *reinterpret_cast<const bf16x8*>(smem + wr_off(32 * (eb < EB ? eb : 0) + r, 2 * ks + g));
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) {
+        acc[0] = mfma32(af[0][ks], q[ks], acc[0]);
+        if (EB > 1) acc[1] = mfma32(af[1][ks], q[ks], acc[1]);
+      }
+      float sg[2][16];
+      float zsum = 0.f;
+#pragma unroll
+      for (int eb = 0; eb < 2; ++eb)
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
           const int e = 32 * eb + 8 * (v / 4) + 4 * g + (v % 4);
-          const float s = (e < E) ? sigmoid_fast(acc[v]) : 0.f;
-          if (pass == 0) zsum += s;
-          else if (e < E) Rs[e * BM + wtok + r] = inv_weight(s * inv);
+          sg[eb][v] = (e < E) ? sigmoid_fast(acc[eb][v]) : 0.f;
+          zsum += sg[eb][v];
         }
-      }
-      if (pass == 0) inv = 1.0f / (zsum + __shfl_xor(zsum, 32) + a.eps);
+      const float inv = 1.0f / (zsum + __shfl_xor(zsum, 32) + a.eps);
+#pragma unroll
+      for (int eb = 0; eb < 2; ++eb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int e = 32 * eb + 8 * (v / 4) + 4 * g + (v % 4);
+          if (e < E) Rs[e * BM + wtok + r] = inv_weight(sg[eb][v] * inv);
+        }
     }
   } else {
+    dma(0, 0);
+    if (T > 1) dma(1, 1);
+    if (T > 2) dma(2, 2);
     const float* R = reinterpret_cast<const float*>(a.route);
     for (int idx = tid; idx < BM * E; idx += THREADS) {
       const int tl = idx / E, e = idx - tl * E;
