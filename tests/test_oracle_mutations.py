@@ -66,3 +66,46 @@ def test_unmutated_oracle_passes_the_same_harness():
                             os.path.join(ROOT, "tests", "test_oracle_pins.py")],
                            cwd=ROOT, env=env, capture_output=True, text=True)
     assert r.returncode == 0, r.stdout[-800:]
+
+
+# ---- the module oracle (Python around the C oracle): same idea, on a copy of the package ----
+MODULE_SRC = os.path.join(ROOT, "oracle", "mhffn_oracle.py")
+MODULE_MUTATIONS = [
+    ("w_in_transposed", "Q = X @ W_in\n", "Q = X @ W_in.T\n"),
+    ("w_out_transposed", "O = S @ W_out\n", "O = S @ W_out.T\n"),
+    ("ds_without_transpose", "dS = dO @ W_out.T", "dS = dO @ W_out"),
+    ("dw_in_from_projected_input", '"dW_in": X.T @ g["dX"]', '"dW_in": Q.T @ g["dX"]'),
+    ("dw_out_from_path_input", '"dW_out": S.T @ dO', '"dW_out": Q.T @ dO'),
+    ("dx_without_input_projection", '"dX": g["dX"] @ W_in.T', '"dX": g["dX"]'),
+]
+
+
+def _run_module_pins(tmp, py_source):
+    import shutil
+    shutil.copytree(os.path.join(ROOT, "oracle"), os.path.join(tmp, "oracle"),
+                    ignore=shutil.ignore_patterns("__pycache__"))
+    open(os.path.join(tmp, "oracle", "mhffn_oracle.py"), "w").write(py_source)
+    os.makedirs(os.path.join(tmp, "tests"))
+    for f in ("__init__.py", "conftest.py", "test_oracle_pins.py"):
+        shutil.copy(os.path.join(ROOT, "tests", f), os.path.join(tmp, "tests", f))
+    env = dict(os.environ, OMP_NUM_THREADS="2", PYTHONPATH=tmp)
+    env.pop("MHFFN_ORACLE_LIB", None)
+    return subprocess.run([sys.executable, "-m", "pytest", "-x", "-q", "-p", "no:cacheprovider",
+                           "-k", "module", os.path.join(tmp, "tests", "test_oracle_pins.py")],
+                          cwd=tmp, env=env, capture_output=True, text=True)
+
+
+@pytest.mark.parametrize("name,old,new", MODULE_MUTATIONS, ids=[m[0] for m in MODULE_MUTATIONS])
+def test_module_pins_catch_planted_mistake(name, old, new):
+    src = open(MODULE_SRC).read()
+    assert src.count(old) >= 1, "mutation target not found: %s" % name
+    with tempfile.TemporaryDirectory() as tmp:
+        r = _run_module_pins(tmp, src.replace(old, new))
+    assert r.returncode != 0, "no pin noticed the planted mistake '%s'" % name
+    assert "failed" in r.stdout, r.stdout[-500:]
+
+
+def test_unmutated_module_oracle_passes_the_same_harness():
+    with tempfile.TemporaryDirectory() as tmp:
+        r = _run_module_pins(tmp, open(MODULE_SRC).read())
+    assert r.returncode == 0 and "passed" in r.stdout, r.stdout[-800:]
