@@ -10,17 +10,20 @@
 //   dX = dY W^T  A = dY row form,  B = W row form
 //   dW = X^T dY  A = X transposed, B = dY transposed
 //
-// Workgroup = 8 waves = 256 (m) x 128 (n) output tile, wave = 64 x 64 (2 x 2 products of
-// 32 x 32), k in slices of 64: sixteen products per wave between two barriers (with
-// slices of 32 the barrier and the address arithmetic of a slice cost as much as its
-// eight products).  The n side sits on the MFMA row axis and the m side on the column
-// axis, so a lane ends up with four consecutive n of one row m and stores 8 bytes.
-// Operand slices go global -> LDS directly into a ring of three stages (six wave-wide
-// loads per wave and slice), requested two slices ahead; one bare barrier per slice.
+// Workgroup = 16 waves = 256 (m) x 256 (n) output tile, wave = 64 x 64 (2 x 2 products of
+// 32 x 32), k in slices of 64.  What sets the shape is the global -> LDS rate: measured,
+// a CU takes about 27 bytes per clock through direct loads (14 TB/s over the chip), so a
+// 256 x 128 tile (1.6 GB of operand traffic for a 16384 x 2048 x 2048 product) spends
+// 0.116 ms on loads alone; 256 x 256 needs 1.07 GB.  Four waves per SIMD at 128 registers
+// then hide each other's LDS latency without a second register set.  The n side sits on
+// the MFMA row axis and the m side on the column axis, so a lane ends up with four
+// consecutive n of one row m and stores 8 bytes.  Operand slices go global -> LDS
+// directly into two 64 KB stages (four wave-wide loads per wave and slice), requested
+// one slice ahead; one bare barrier per slice.
 // LDS images: row form [rows][64] with the eight 16-byte chunks of a row permuted,
 // transposed form the swizzled [32][128] tile of the fused kernels; both are free of
-// bank conflicts for their reads.  Operand reads are issued untracked, one slice ahead
-// of the products that consume them.
+// bank conflicts for their reads.  Operand reads are issued untracked, eight at a time,
+// and waited for by count.
 // With a transposed operand in play the contraction slots of one MFMA step follow the
 // transposing read (slot s of lane group g <-> k = 8 (s / 4) + 4 g + s % 4); a row-form
 // partner is then read as two 8-byte halves with the same mapping.
@@ -32,16 +35,16 @@
 namespace mhffn {
 namespace {
 
-constexpr int kGWaves = 8, kGThreads = 64 * kGWaves;
-constexpr int kGTileM = 256, kGTileN = 128, kGBK = 64;
+constexpr int kGWaves = 16, kGThreads = 64 * kGWaves;
+constexpr int kGTileM = 256, kGTileN = 256, kGBK = 64;
 constexpr int kGMBytes = kGTileM * kGBK * 2;   // 32 KB
-constexpr int kGNBytes = kGTileN * kGBK * 2;   // 16 KB
+constexpr int kGNBytes = kGTileN * kGBK * 2;   // 32 KB
 constexpr int kGStageBytes = kGMBytes + kGNBytes;
-constexpr int kGStages = 3;
-constexpr int kGLdsBytes = kGStages * kGStageBytes;   // 144 KB
+constexpr int kGStages = 2;
+constexpr int kGLdsBytes = kGStages * kGStageBytes;   // 128 KB
 constexpr int kGLoads = (kGStageBytes / 1024) / kGWaves;   // wave-wide 1 KB loads per wave and slice
-static_assert(kGLdsBytes <= (int)kLdsBytesPerWorkgroup, "ring must fit in LDS");
-static_assert(kGLoads == 6, "4 images of the m side and 2 of the n side per wave");
+static_assert(kGLdsBytes <= (int)kLdsBytesPerWorkgroup, "both stages must fit in LDS");
+static_assert(kGLoads == 4, "2 images of the m side and 2 of the n side per wave");
 
 struct TunedGemmArgs {
   const uint16_t* A;   // m side
@@ -64,7 +67,7 @@ __device__ __forceinline__ void static_for(F&& f) {
   }
 }
 
-// LDS image of one side of a slice (rows = 256 on the m side, 128 on the n side):
+// LDS image of one side of a slice (256 rows):
 //   row form:        [rows][64 k], 128-byte rows, chunks permuted as in the 64-wide tile
 //   transposed form: swizzled [32 k][128] tiles, tile index = (k / 32) * (rows / 128) + row / 128
 // Both are contiguous in 1 KB images (8 rows, or 4 k rows of one tile), which is what one
@@ -77,7 +80,7 @@ __global__ __launch_bounds__(kGThreads) void gemm_bf16_kernel(TunedGemmArgs a) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r = lane & 31, g = lane >> 5;
   const int wave_u = __builtin_amdgcn_readfirstlane(wave);
-  const int wm = wave_u >> 1, wn = wave_u & 1;      // 4 x 2 waves
+  const int wm = wave_u >> 2, wn = wave_u & 3;      // 4 x 4 waves
   const int64_t item = xcd_work_item(blockIdx.x, a.n_items);
   if (item >= a.n_items) return;
   const int split = (int)(item % a.splits);
@@ -89,8 +92,8 @@ __global__ __launch_bounds__(kGThreads) void gemm_bf16_kernel(TunedGemmArgs a) {
   const int64_t kend = kbase + a.slices_per_split < KT_all ? kbase + a.slices_per_split : KT_all;
   const int64_t KT = kend - kbase;                            // its number of slices (>= 1)
 
-  // ---- staging: six wave-wide 1 KB loads per wave and slice ------------------------------
-  // m side: images 4w .. 4w+3 of 32, n side: images 2w, 2w+1 of 16.
+  // ---- staging: four wave-wide 1 KB loads per wave and slice -----------------------------
+  // images 2w, 2w+1 of the 32 of the m side and of the 32 of the n side.
   // Row form: image i = rows 8i .. 8i+7, lane l -> row 8i + l/8, physical chunk l%8.
   // Transposed form: image i = k rows 4(i%8) .. +3 of tile i/8, lane l -> k row + l/16,
   // physical chunk l%16.  Rows / columns past the edge are clamped (their products are never
@@ -124,9 +127,9 @@ __global__ __launch_bounds__(kGThreads) void gemm_bf16_kernel(TunedGemmArgs a) {
     lds_img[slot] = side_off + img * 1024;
   };
 #pragma unroll
-  for (int i = 0; i < 4; ++i) setup(i, A_TR, a.A, a.lda, m0, a.M, kGTileM, 4 * wave_u + i, 0);
+  for (int i = 0; i < 2; ++i) setup(i, A_TR, a.A, a.lda, m0, a.M, kGTileM, 2 * wave_u + i, 0);
 #pragma unroll
-  for (int i = 0; i < 2; ++i) setup(4 + i, B_TR, a.B, a.ldb, n0, a.N, kGTileN, 2 * wave_u + i, kGMBytes);
+  for (int i = 0; i < 2; ++i) setup(2 + i, B_TR, a.B, a.ldb, n0, a.N, kGTileN, 2 * wave_u + i, kGMBytes);
   auto dma_one = [&](int64_t kt, int stage, int s) {
     const uint16_t* p;
     if (krow[s] < 0) {
@@ -186,24 +189,23 @@ __global__ __launch_bounds__(kGThreads) void gemm_bf16_kernel(TunedGemmArgs a) {
     for (int j = 0; j < 2; ++j) acc[i][j] = f32x16{0};
 
   // ---- main loop ----------------------------------------------------------------------------
-  // Reads run one slice ahead of the products: in iteration kt the operands of slice kt+1
-  // are requested from LDS (into the other register set) and then the sixteen products of
-  // slice kt are issued from registers filled during the previous iteration.  The stage of
-  // slice kt is therefore free as soon as every wave has passed the barrier of iteration
-  // kt, and receives slice kt + kGStages.
+  // Two stages.  Iteration kt: barrier (slice kt has landed everywhere, everyone is done with
+  // slice kt-1), request slice kt+1 into the other stage, then the slice in two halves of
+  // two contraction steps: eight operand reads issued, eight products consumed with counted
+  // waits.  Four waves share a SIMD, so one wave's LDS latency is another's MFMA time.
   constexpr bool kSplit = kTrSlots;
-  struct Frags {
-    s16x4 lo[16], hi[16];   // split reads
-    bf16x8 full[16];        // 16-byte reads
+  constexpr int kInstr = kSplit ? 2 : 1;   // LDS read instructions per operand
+  struct Half {
+    s16x4 lo[8], hi[8];   // split reads
+    bf16x8 full[8];       // 16-byte reads
   };
-  Frags fr[2];
-  auto issue = [&](Frags& f, unsigned so) {
-    static_for<0, 16>([&](auto IT_) {
-      constexpr int it = decltype(IT_)::value, t2 = it >> 2, idx = (it >> 1) & 1, side = it & 1;
+  auto issue_half = [&](Half& f, unsigned so, auto HB_) {
+    static_for<0, 8>([&](auto IT_) {
+      constexpr int it = decltype(IT_)::value, t2 = 2 * decltype(HB_)::value + (it >> 2);
+      constexpr int idx = (it >> 1) & 1, side = it & 1;
       constexpr bool tr = side ? A_TR : B_TR;
       if constexpr (tr) {
-        // tiles of one group of 32 k rows: two on the m side, one on the n side
-        constexpr int OFF = (t2 & 1) * 4096 + (t2 >> 1) * (side ? 16384 : 8192);
+        constexpr int OFF = (t2 & 1) * 4096 + (t2 >> 1) * 16384;   // two 32-row tiles per group of 32 k rows
         f.lo[it] = lds_read_tr16_untracked<OFF>(atr[side][idx] + so);
         f.hi[it] = lds_read_tr16_untracked<OFF>(atr2[side][idx] + so);
       } else if constexpr (kSplit) {
@@ -214,30 +216,22 @@ __global__ __launch_bounds__(kGThreads) void gemm_bf16_kernel(TunedGemmArgs a) {
       }
     });
   };
-  // all reads of the set have landed; ties every register of the set to the wait
-  auto settle = [&](Frags& f) {
-    static_for<0, 8>([&](auto P_) {
-      constexpr int it = 2 * decltype(P_)::value;
-      if constexpr (kSplit) {
-        lds_wait<0>(f.lo[it], f.hi[it]);
-        lds_wait<0>(f.lo[it + 1], f.hi[it + 1]);
-      } else {
-        lds_wait<0>(f.full[it], f.full[it + 1]);
-      }
-    });
-  };
-  // the products of slice kt; the loads of slice `kt_load` (if >= 0) are issued two at a time
-  // between the contraction steps: a wave stalls while the memory pipeline takes a load, and
-  // here that happens under its own products instead of in front of them
-  auto compute = [&](Frags& f, int64_t kt, int64_t kt_load, int load_stage) {
+  auto compute_half = [&](Half& f, int64_t kt, auto HB_) {
     const bool ragged_last = kTrSlots && (kt == KT_all - 1) && (K % kGBK) != 0;
-    static_for<0, 4>([&](auto T2_) {
-      constexpr int t2 = decltype(T2_)::value;
+    static_for<0, 2>([&](auto TT_) {
+      constexpr int tt = decltype(TT_)::value, t2 = 2 * decltype(HB_)::value + tt;
       bf16x8 nf[2], mf[2];
       static_for<0, 4>([&](auto Q_) {
-        constexpr int it = 4 * t2 + decltype(Q_)::value, idx = (it >> 1) & 1, side = it & 1;
+        constexpr int it = 4 * tt + decltype(Q_)::value, idx = (it >> 1) & 1, side = it & 1;
+        constexpr int pending = (7 - it) * kInstr;   // reads issued after this item
         bf16x8 v;
-        if constexpr (kSplit) v = join_tr(f.lo[it], f.hi[it]); else v = f.full[it];
+        if constexpr (kSplit) {
+          lds_wait<pending>(f.lo[it], f.hi[it]);
+          v = join_tr(f.lo[it], f.hi[it]);
+        } else {
+          lds_wait<pending>(f.full[it]);
+          v = f.full[it];
+        }
         if constexpr (side == 0) {
           if (ragged_last) {
             // k rows past K were clamped when the slice was requested: clear their slots on the
@@ -255,50 +249,26 @@ __global__ __launch_bounds__(kGThreads) void gemm_bf16_kernel(TunedGemmArgs a) {
       acc[1][0] = mfma32(nf[1], mf[0], acc[1][0]);
       acc[0][1] = mfma32(nf[0], mf[1], acc[0][1]);
       acc[1][1] = mfma32(nf[1], mf[1], acc[1][1]);
-      if constexpr (t2 < 3) {
-        asm volatile("" : "+v"(acc[0][0]), "+v"(acc[1][0]), "+v"(acc[0][1]), "+v"(acc[1][1]));
-        if (kt_load >= 0) {
-          dma_one(kt_load, load_stage, 2 * t2);
-          dma_one(kt_load, load_stage, 2 * t2 + 1);
-        }
-      }
     });
   };
 
-  // prologue: request the first kGStages slices; slice 0 must have landed everywhere before
-  // its operands are read
-  static_for<0, kGStages>([&](auto S_) {
-    constexpr int s = decltype(S_)::value;
-    if (s < KT) dma(kbase + s, s);
-  });
-  asm volatile("" ::: "memory");
-  if (KT >= kGStages) __builtin_amdgcn_s_waitcnt(0x0F70 | (kGLoads * (kGStages - 1)));   // vmcnt(12)
-  else __builtin_amdgcn_s_waitcnt(0x0F70);
-  __builtin_amdgcn_s_barrier();
-  asm volatile("" ::: "memory");
-  issue(fr[0], 0);
-
-  // iteration kt (slice kbase + kt); STAGE = kt % kGStages, its operands are in `cur`
-  auto iteration = [&](int64_t kt, auto STAGE_, Frags& cur, Frags& nxt) {
-    constexpr int stage = decltype(STAGE_)::value, next_stage = (stage + 1) % kGStages;
-    settle(cur);
-    // slice kt+1 has landed for every wave and every wave holds slice kt in registers
+  dma(kbase, 0);
+  auto iteration = [&](int64_t kt, auto STAGE_) {
+    constexpr int stage = decltype(STAGE_)::value;
     asm volatile("" ::: "memory");
-    if (kt + kGStages - 1 < KT) __builtin_amdgcn_s_waitcnt(0x0F70 | (kGLoads * (kGStages - 2)));  // vmcnt(6)
-    else __builtin_amdgcn_s_waitcnt(0x0F70);                                                        // vmcnt(0)
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's part of slice kt
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
-    if (kt + 1 < KT) issue(nxt, next_stage * kGStageBytes);
-    compute(cur, kbase + kt, kt + kGStages < KT ? kbase + kt + kGStages : -1, stage);
+    if (kt + 1 < KT) dma(kbase + kt + 1, stage ^ 1);
+    Half f;
+    issue_half(f, stage * kGStageBytes, std::integral_constant<int, 0>{});
+    compute_half(f, kbase + kt, std::integral_constant<int, 0>{});
+    issue_half(f, stage * kGStageBytes, std::integral_constant<int, 1>{});
+    compute_half(f, kbase + kt, std::integral_constant<int, 1>{});
   };
-  // six iterations per trip: stage (mod 3) and register set (mod 2) are compile-time
-  for (int64_t kt = 0; kt < KT; kt += 6) {
-    iteration(kt, std::integral_constant<int, 0>{}, fr[0], fr[1]);
-    if (kt + 1 < KT) iteration(kt + 1, std::integral_constant<int, 1>{}, fr[1], fr[0]);
-    if (kt + 2 < KT) iteration(kt + 2, std::integral_constant<int, 2>{}, fr[0], fr[1]);
-    if (kt + 3 < KT) iteration(kt + 3, std::integral_constant<int, 0>{}, fr[1], fr[0]);
-    if (kt + 4 < KT) iteration(kt + 4, std::integral_constant<int, 1>{}, fr[0], fr[1]);
-    if (kt + 5 < KT) iteration(kt + 5, std::integral_constant<int, 2>{}, fr[1], fr[0]);
+  for (int64_t kt = 0; kt < KT; kt += 2) {
+    iteration(kt, std::integral_constant<int, 0>{});
+    if (kt + 1 < KT) iteration(kt + 1, std::integral_constant<int, 1>{});
   }
 
   // ---- store: lane = row m, registers = four consecutive n per group ----------------------
