@@ -151,6 +151,28 @@ def module_bench(args, w):
     torch.cuda.synchronize()
     ms_per_step = (time.perf_counter() - t0) * 1e3 / K
     t["module_fwd"], t["module_bwd"] = timed(mod_fwd), timed(mod_bwd)
+    # A dense SwiGLU FFN of the same d_model and d_ff (the layer the module replaces; same
+    # 3 + 6 units of contraction work, no projections, no recompute): the unfused path with
+    # one head, one sub-network and unit weights, which runs on the same product kernel and
+    # keeps G, U' and A in device memory.
+    dff = w.d_ff
+    sw = [(torch.randn(1, 1, dff, w.d_model, device="cuda") * 0.02).to(torch.bfloat16) for _ in range(3)]
+    ones = torch.ones(w.n_tokens, 1, 1, device="cuda", dtype=torch.float32)
+    sdesc = mhffn.make_desc(g["X"], sw[0], mhffn.ROUTE_WEIGHTS, w.eps)
+    s_ws_f = mhffn.workspace_bytes(sdesc, mhffn.OP_UNFUSED_FORWARD)
+    s_ws_b = mhffn.workspace_bytes(sdesc, mhffn.OP_UNFUSED_BACKWARD)
+    sws = torch.empty(max(s_ws_b, 256), dtype=torch.uint8, device="cuda")
+    sout = {"Y": torch.empty_like(g["X"]), "dX": torch.empty_like(g["X"]), "d_route": torch.empty_like(ones),
+            "dW_gate": torch.empty_like(sw[0]), "dW_up": torch.empty_like(sw[0]), "dW_down": torch.empty_like(sw[0])}
+
+    def swiglu_fwd():
+        mhffn.reference_unfused(g["X"], *sw, ones, w.eps, mhffn.ROUTE_WEIGHTS, workspace=sws, out=sout)
+
+    def swiglu_all():
+        mhffn.reference_unfused(g["X"], *sw, ones, w.eps, mhffn.ROUTE_WEIGHTS, dY=g["dY"], workspace=sws, out=sout)
+
+    t["swiglu_fwd"], t["swiglu_fwd_bwd"] = timed(swiglu_fwd), timed(swiglu_all)
+    act_bytes = g["X"].numel() * 2
     unit = w.unit_flops()
     proj = 2.0 * w.n_tokens * w.d_model * w.d_model          # one projection-sized product
     flops = 11.0 * unit + 6.0 * proj
@@ -166,6 +188,13 @@ def module_bench(args, w):
                    "step": "module forward + module backward"},
         "frac_of_bf16_peak": round(value / PEAK_BF16_TFLOPS, 4),
         "phase_ms": {k: round(v, 4) for k, v in t.items()},
+        "dense_swiglu_same_size": {
+            "forward_ms": round(t["swiglu_fwd"], 4), "forward_backward_ms": round(t["swiglu_fwd_bwd"], 4),
+            "module_forward_speedup": round(t["swiglu_fwd"] / t["module_fwd"], 3),
+            "module_step_speedup": round(t["swiglu_fwd_bwd"] / (t["module_fwd"] + t["module_bwd"]), 3),
+            "saved_activation_bytes": {"module (Q, S)": 2 * act_bytes, "swiglu (G, U', A)": 3 * w.n_tokens * dff * 2},
+            "forward_workspace_bytes": {"module": mhffn.workspace_bytes(desc, mhffn.OP_MODULE_FORWARD), "swiglu": s_ws_f},
+        },
         "projections": {"count": 6, "ms": round(gemm_ms, 4),
                         "tflops": round(6.0 * proj / (gemm_ms * 1e-3) / 1e12, 1) if gemm_ms > 0 else None,
                         "frac_of_bf16_peak": round(6.0 * proj / (gemm_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4)

@@ -57,6 +57,7 @@ struct TunedGemmArgs {
   int splits;
   int64_t slices_per_split;
   float* P;
+  int accumulate;   // add to what C holds (one more rounding to bf16)
 };
 
 template <int B, int E, typename F>
@@ -287,10 +288,20 @@ __global__ __launch_bounds__(kGThreads) void gemm_bf16_kernel(TunedGemmArgs a) {
                            acc[jn][im][4 * vq + 3]};
           *reinterpret_cast<f32x4*>(a.P + ((size_t)split * a.M + m) * a.N + n) = v;
         } else {
+          float o[4] = {acc[jn][im][4 * vq], acc[jn][im][4 * vq + 1], acc[jn][im][4 * vq + 2],
+                        acc[jn][im][4 * vq + 3]};
+          u32x2* dst = reinterpret_cast<u32x2*>(a.C + m * a.ldc + n);
+          if (a.accumulate) {
+            const u32x2 old = *dst;
+            o[0] += __builtin_bit_cast(float, old[0] << 16);
+            o[1] += __builtin_bit_cast(float, old[0] & 0xFFFF0000u);
+            o[2] += __builtin_bit_cast(float, old[1] << 16);
+            o[3] += __builtin_bit_cast(float, old[1] & 0xFFFF0000u);
+          }
           u32x2 pk;
-          pk[0] = pack_bf16(acc[jn][im][4 * vq], acc[jn][im][4 * vq + 1]);
-          pk[1] = pack_bf16(acc[jn][im][4 * vq + 2], acc[jn][im][4 * vq + 3]);
-          *reinterpret_cast<u32x2*>(a.C + m * a.ldc + n) = pk;
+          pk[0] = pack_bf16(o[0], o[1]);
+          pk[1] = pack_bf16(o[2], o[3]);
+          *dst = pk;
         }
       }
     }
@@ -305,10 +316,18 @@ __global__ void gemm_bf16_reduce_kernel(TunedGemmArgs a) {
   for (int s = 0; s < a.splits; ++s)
     sum += *reinterpret_cast<const f32x4*>(a.P + (size_t)s * a.M * a.N + idx);
   const int64_t m = idx / a.N, n = idx % a.N;
+  u32x2* dst = reinterpret_cast<u32x2*>(a.C + m * a.ldc + n);
+  if (a.accumulate) {
+    const u32x2 old = *dst;
+    sum[0] += __builtin_bit_cast(float, old[0] << 16);
+    sum[1] += __builtin_bit_cast(float, old[0] & 0xFFFF0000u);
+    sum[2] += __builtin_bit_cast(float, old[1] << 16);
+    sum[3] += __builtin_bit_cast(float, old[1] & 0xFFFF0000u);
+  }
   u32x2 pk;
   pk[0] = pack_bf16(sum[0], sum[1]);
   pk[1] = pack_bf16(sum[2], sum[3]);
-  *reinterpret_cast<u32x2*>(a.C + m * a.ldc + n) = pk;
+  *dst = pk;
 }
 
 // Split k only when the output tiles alone leave most of the chip idle (the weight-gradient
@@ -366,8 +385,10 @@ size_t gemm_bf16_workspace_bytes(int64_t M, int64_t N, int64_t K) {
 }
 
 int launch_gemm_bf16(bool a_tr, bool b_tr, const void* A, int64_t lda, const void* B, int64_t ldb,
-                     void* C, int64_t ldc, int64_t M, int64_t N, int64_t K, void* ws, void* stream) {
+                     void* C, int64_t ldc, int64_t M, int64_t N, int64_t K, void* ws, void* stream,
+                     bool accumulate) {
   TunedGemmArgs a;
+  a.accumulate = accumulate ? 1 : 0;
   a.A = static_cast<const uint16_t*>(A);
   a.B = static_cast<const uint16_t*>(B);
   a.C = static_cast<uint16_t*>(C);

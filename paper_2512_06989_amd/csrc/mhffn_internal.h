@@ -76,7 +76,8 @@ bool gemm_bf16_supported(bool a_tr, bool b_tr, const void* A, int64_t lda, const
 // workgroups because the output tiles alone cannot fill the chip; 0 otherwise.
 size_t gemm_bf16_workspace_bytes(int64_t M, int64_t N, int64_t K);
 int launch_gemm_bf16(bool a_tr, bool b_tr, const void* A, int64_t lda, const void* B, int64_t ldb,
-                     void* C, int64_t ldc, int64_t M, int64_t N, int64_t K, void* ws, void* stream);
+                     void* C, int64_t ldc, int64_t M, int64_t N, int64_t K, void* ws, void* stream,
+                     bool accumulate = false);
 
 // ---- whole module: projections around the fused path -------------------------
 // Problem::ldx / ldy are the row strides of the module's input X (dX) and output O (dO);

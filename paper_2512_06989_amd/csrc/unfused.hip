@@ -219,9 +219,46 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g) {
     }
 }
 
+// bf16 products whose operands lie in one of the three forms of the tuned projection kernel
+// go there, one launch per batch entry (a pair of products: the second accumulates).
+// `gws`: scratch for its split-k partial tiles (0 bytes needed => may be NULL).
+inline bool tuned_form(const GemmArgs& g, bool* a_tr, bool* b_tr, int64_t* lda, int64_t* ldb) {
+  if (g.a_ks == 1 && g.b_ks == 1) { *a_tr = false; *b_tr = false; *lda = g.a_ms; *ldb = g.b_ns; return true; }
+  if (g.a_ks == 1 && g.b_ns == 1) { *a_tr = false; *b_tr = true; *lda = g.a_ms; *ldb = g.b_ks; return true; }
+  if (g.a_ms == 1 && g.b_ns == 1) { *a_tr = true; *b_tr = true; *lda = g.a_ks; *ldb = g.b_ks; return true; }
+  return false;
+}
+
 template <typename T>
-int run_gemm(const GemmArgs& g, int batch, hipStream_t st) {
+int run_gemm(const GemmArgs& g, int batch, hipStream_t st, void* gws = nullptr, size_t gws_bytes = 0) {
   if (g.M <= 0 || g.N <= 0 || batch <= 0) return 0;
+  if constexpr (sizeof(T) == 2) {
+    bool a_tr, b_tr;
+    int64_t lda, ldb;
+    if (!g.accumulate && g.K > 0 && tuned_form(g, &a_tr, &b_tr, &lda, &ldb) &&
+        gemm_bf16_workspace_bytes(g.M, g.N, g.K) <= gws_bytes) {
+      bool ok = true;
+      for (int b = 0; b < batch && ok; ++b)
+        for (int pair = 0; pair < (g.A2 ? 2 : 1) && ok; ++pair) {
+          const T* A = static_cast<const T*>(pair ? g.A2 : g.A) + (int64_t)b * g.a_bs;
+          const T* B = static_cast<const T*>(pair ? g.B2 : g.B) + (int64_t)b * g.b_bs;
+          ok = gemm_bf16_supported(a_tr, b_tr, A, lda, B, ldb, static_cast<T*>(g.C) + (int64_t)b * g.c_bs,
+                                   g.c_ms, g.M, g.N, g.K);
+        }
+      if (ok) {
+        for (int b = 0; b < batch; ++b)
+          for (int pair = 0; pair < (g.A2 ? 2 : 1); ++pair) {
+            const T* A = static_cast<const T*>(pair ? g.A2 : g.A) + (int64_t)b * g.a_bs;
+            const T* B = static_cast<const T*>(pair ? g.B2 : g.B) + (int64_t)b * g.b_bs;
+            const int rc = launch_gemm_bf16(a_tr, b_tr, A, lda, B, ldb,
+                                            static_cast<T*>(g.C) + (int64_t)b * g.c_bs, g.c_ms, g.M, g.N,
+                                            g.K, gws, st, pair == 1);
+            if (rc) return rc;
+          }
+        return 0;
+      }
+    }
+  }
   dim3 grid((unsigned)((g.N + kGN - 1) / kGN), (unsigned)((g.M + kGM - 1) / kGM), (unsigned)batch);
   hipLaunchKernelGGL(gemm_kernel<T>, grid, dim3(256), 0, st, g);
   return (int)hipGetLastError();
@@ -434,7 +471,7 @@ __global__ void zero_words_kernel(uint32_t* p, size_t n) {
 size_t al256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct Layout {
-  size_t R, Zinv, G, U, A, dA, DR, DPt, total;
+  size_t R, Zinv, G, U, A, dA, DR, DPt, gemm, gemm_bytes, total;
 };
 Layout make_layout(const Problem& p, size_t es, bool backward) {
   Layout L{};
@@ -450,6 +487,22 @@ Layout make_layout(const Problem& p, size_t es, bool backward) {
     L.dA = o; o += al256(big);
     L.DR = o; o += al256(nhe * 4);
     L.DPt = o; o += al256(nhe * es);
+  }
+  // split-k partial tiles of the tuned bf16 product (largest need over the call sites)
+  L.gemm = o;
+  L.gemm_bytes = 0;
+  if (es == 2) {
+    const int64_t dff = (int64_t)p.E * p.de;
+    size_t need = gemm_bf16_workspace_bytes(p.N, dff, p.dh);
+    const size_t w2 = gemm_bf16_workspace_bytes(p.N, p.dh, dff);
+    need = need > w2 ? need : w2;
+    if (backward) {
+      const size_t w3 = gemm_bf16_workspace_bytes(dff, p.dh, p.N), w4 = gemm_bf16_workspace_bytes(p.dh, p.E, p.N);
+      need = need > w3 ? need : w3;
+      need = need > w4 ? need : w4;
+    }
+    L.gemm_bytes = al256(need);
+    o += L.gemm_bytes;
   }
   L.total = o;
   return L;
@@ -475,6 +528,7 @@ int run_unfused(const Problem& p, const void* X, const void* Wg, const void* Wu,
     return (int)hipGetLastError();
   }
   const Layout L = make_layout(p, sizeof(T), backward);
+  void* gws = static_cast<unsigned char*>(ws) + L.gemm;
   unsigned char* w = static_cast<unsigned char*>(ws);
   UArgs a{};
   a.X = X; a.route = route; a.dY = dY; a.dX = dX;
@@ -501,7 +555,7 @@ int run_unfused(const Problem& p, const void* X, const void* Wg, const void* Wu,
       gate_attr = true;
     }
     hipLaunchKernelGGL(gating_kernel<T>, dim3((unsigned)((p.N + kGateTok - 1) / kGateTok), p.H),
-                       dim3(256), gating_lds_bytes(p.dh, p.E), st, a);
+                       dim3(256), p.route_mode == 0 ? gating_lds_bytes(p.dh, p.E) : 0, st, a);
   }
   // 16-byte vectors in the elementwise kernels when a run of them stays inside a sub-network
   const int vec = (p.de % (16 / (int)sizeof(T)) == 0) ? 16 / (int)sizeof(T) : 1;
@@ -513,7 +567,7 @@ int run_unfused(const Problem& p, const void* X, const void* Wg, const void* Wu,
     g.a_ms = p.ldx; g.a_ks = 1; g.a_bs = p.dh;
     g.b_ns = p.dh; g.b_ks = 1; g.b_bs = dff * p.dh;
     g.c_ms = dff; g.c_bs = hs;
-    if ((rc = run_gemm<T>(g, p.H, st))) return rc;
+    if ((rc = run_gemm<T>(g, p.H, st, gws, L.gemm_bytes))) return rc;
   }
   // (iii) activation and weighting
   {
@@ -528,7 +582,7 @@ int run_unfused(const Problem& p, const void* X, const void* Wg, const void* Wu,
     g.a_ms = dff; g.a_ks = 1; g.a_bs = hs;
     g.b_ns = 1; g.b_ks = p.dh; g.b_bs = dff * p.dh;
     g.c_ms = p.ldy; g.c_bs = p.dh;
-    if ((rc = run_gemm<T>(g, p.H, st))) return rc;
+    if ((rc = run_gemm<T>(g, p.H, st, gws, L.gemm_bytes))) return rc;
   }
   if (!backward) return (int)hipGetLastError();
 
@@ -541,7 +595,7 @@ int run_unfused(const Problem& p, const void* X, const void* Wg, const void* Wu,
     g.a_ms = p.ldy; g.a_ks = 1; g.a_bs = p.dh;
     g.b_ns = p.dh; g.b_ks = 1; g.b_bs = dff * p.dh;
     g.c_ms = dff; g.c_bs = hs;
-    if ((rc = run_gemm<T>(g, p.H, st))) return rc;
+    if ((rc = run_gemm<T>(g, p.H, st, gws, L.gemm_bytes))) return rc;
   }
   // dG, dU' in place of G, U'; dr
   {
@@ -559,7 +613,7 @@ int run_unfused(const Problem& p, const void* X, const void* Wg, const void* Wu,
     g.a_ms = dff; g.a_ks = 1; g.a_bs = hs;
     g.b_ns = 1; g.b_ks = p.dh; g.b_bs = dff * p.dh;
     g.c_ms = p.ldx; g.c_bs = p.dh;
-    if ((rc = run_gemm<T>(g, p.H, st))) return rc;
+    if ((rc = run_gemm<T>(g, p.H, st, gws, L.gemm_bytes))) return rc;
   }
   // dK_h = dG^T X_h, dU_h = dU'^T X_h, dV_h = A^T dY_h   (contraction over tokens)
   for (int which = 0; which < 3; ++which) {
@@ -573,7 +627,7 @@ int run_unfused(const Problem& p, const void* X, const void* Wg, const void* Wu,
     g.a_ms = 1; g.a_ks = dff; g.a_bs = hs;
     g.b_ns = 1; g.b_ks = which == 2 ? p.ldy : p.ldx; g.b_bs = p.dh;
     g.c_ms = p.dh; g.c_bs = dff * p.dh;
-    if ((rc = run_gemm<T>(g, p.H, st))) return rc;
+    if ((rc = run_gemm<T>(g, p.H, st, gws, L.gemm_bytes))) return rc;
   }
   // routing derivative
   hipLaunchKernelGGL(route_bwd_kernel<T>, dim3((unsigned)(p.N * p.H)), dim3(128),
@@ -585,7 +639,7 @@ int run_unfused(const Problem& p, const void* X, const void* Wg, const void* Wu,
     g.a_ms = 1; g.a_ks = p.ldx; g.a_bs = p.dh;
     g.b_ns = 1; g.b_ks = p.E; g.b_bs = (int64_t)p.N * p.E;
     g.c_ms = p.E; g.c_bs = (int64_t)p.dh * p.E;
-    if ((rc = run_gemm<T>(g, p.H, st))) return rc;
+    if ((rc = run_gemm<T>(g, p.H, st, gws, L.gemm_bytes))) return rc;
   }
   return (int)hipGetLastError();
 }
@@ -614,7 +668,8 @@ int launch_unfused(const Problem& p, int dtype, const void* X, const void* Wg, c
                    void* dWg, void* dWu, void* dWd, void* d_route, void* ws, void* stream) {
   hipStream_t st = static_cast<hipStream_t>(stream);
   if ((int64_t)p.N * p.H * p.E > 0x7fffffffLL) return -1;  // one wave per (token, head, sub-network)
-  if (gating_lds_bytes(p.dh, p.E) > kLdsBytesPerWorkgroup) return -1;  // W_r[h] must fit in LDS
+  // W_r[h] must fit in LDS (not needed when the weights R are given)
+  if (p.route_mode == 0 && gating_lds_bytes(p.dh, p.E) > kLdsBytesPerWorkgroup) return -1;
   if (dtype == 1)
     return run_unfused<uint16_t>(p, X, Wg, Wu, Wd, route, Y, dY, dX, dWg, dWu, dWd, d_route, ws, st);
   return run_unfused<float>(p, X, Wg, Wu, Wd, route, Y, dY, dX, dWg, dWu, dWd, d_route, ws, st);
