@@ -300,18 +300,30 @@ __global__ __launch_bounds__(64 * NW) void bwd_tok_kernel(BwdArgs a) {
       }
     }
     __builtin_amdgcn_s_setprio(0);
+    // K^T / U^T operands, item c = (t2, jb, which): transposing reads issued four items ahead
+    // of their use with counted waits, like the row operands above
+    {
+      const unsigned sto = lds_addr_of(st);
+      constexpr int NI = 2 * JB * 2, W2 = 4;
+      s16x4 lo[NI], hi[NI];
+      const int li = lane & 15;
+      const int trow = 4 * g + (li >> 2), tcol = 16 * ((lane >> 4) & 1) + 4 * (li & 3);
+      auto issue2 = [&](auto C_) {
+        constexpr int c = decltype(C_)::value, which = c & 1, jb = (c >> 1) % JB, t2 = c / (2 * JB);
+        constexpr int OFF = which * kTileBytes + t2 * 16 * 2 * DH;   // 16 rows further: same swizzle
+        lo[c] = lds_read_tr16_untracked<OFF>(sto + tile_off8_dh<DH>(trow, 32 * jb + tcol));
+        hi[c] = lds_read_tr16_untracked<OFF>(sto + tile_off8_dh<DH>(trow + 8, 32 * jb + tcol));
+      };
+      static_for<0, W2>(issue2);
+      static_for<0, NI>([&](auto C_) {
+        constexpr int c = decltype(C_)::value, which = c & 1, jb = (c >> 1) % JB, t2 = c / (2 * JB);
+        if constexpr (c + W2 < NI) issue2(std::integral_constant<int, c + W2>{});
+        lds_wait<2 * ((NI - 1 - c) < W2 ? (NI - 1 - c) : W2)>(lo[c], hi[c]);
+        const bf16x8 xt = join_tr(lo[c], hi[c]);
 #pragma unroll
-    for (int t2 = 0; t2 < 2; ++t2) {
-#pragma unroll
-      for (int jb = 0; jb < JB; ++jb) {
-        const bf16x8 kt = tile_read_tr_dh<DH>(st, 16 * t2 + 4 * g, 32 * jb, lane);
-        const bf16x8 ut = tile_read_tr_dh<DH>(st + kTileBytes, 16 * t2 + 4 * g, 32 * jb, lane);
-#pragma unroll
-        for (int tb = 0; tb < TB; ++tb) {
-          dXa[tb][jb] = mfma32(kt, dmf[tb][t2], dXa[tb][jb]);
-          dXa[tb][jb] = mfma32(ut, dnf[tb][t2], dXa[tb][jb]);
-        }
-      }
+        for (int tb = 0; tb < TB; ++tb)
+          dXa[tb][jb] = mfma32(xt, which ? dnf[tb][t2] : dmf[tb][t2], dXa[tb][jb]);
+      });
     }
     if ((t + 1) % tiles_per_sub == 0) {
 #pragma unroll
