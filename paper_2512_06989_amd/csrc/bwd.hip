@@ -61,6 +61,12 @@ struct BwdArgs {
   float* Rws;   // [H][E][N]
   float* DPws;  // [H][E][N]  dp (params mode) or dr (weights mode)
   float* WRws;  // [H][S][128][E] partial dW_r
+  // weight-major kernel with the tokens shared out over `wsplit` workgroups per neuron group
+  // (only when the neuron groups alone fill less than a round of the chip well): fp32
+  // partial gradients [wsplit][3][H*E*d_e][128], summed in fixed order afterwards
+  float* WPws;
+  int wsplit;
+  int64_t blocks_per_seg;
   int64_t N, ldx, ldy, n_tiles, n_items;
   int H, E, de, dh, route_mode, n_split;
   float eps;
@@ -478,8 +484,10 @@ __global__ __launch_bounds__(kW16Threads) void bwd_wgt16_kernel(BwdArgs a) {
   auto rho = [](int m) { return (m & 9) | ((m & 2) << 1) | ((m & 4) >> 1); };
   const int nblk = a.E * a.de / 16;              // 16-neuron blocks per head
   const int wg_per_head = (nblk + kW16Waves - 1) / kW16Waves;
-  const int64_t item = xcd_work_item(blockIdx.x, a.n_items);
-  if (item >= a.n_items) return;
+  const int64_t item_s = xcd_work_item(blockIdx.x, a.n_items);
+  if (item_s >= a.n_items) return;
+  const int seg = (int)(item_s % a.wsplit);          // this workgroup's share of the tokens
+  const int64_t item = item_s / a.wsplit;
   const int h = (int)(item / wg_per_head);
   const int blk = (int)(item % wg_per_head) * kW16Waves + wave;
   const bool active = blk < nblk;
@@ -513,11 +521,13 @@ __global__ __launch_bounds__(kW16Threads) void bwd_wgt16_kernel(BwdArgs a) {
   // (three loads per wave and block; the r load is a full wave wide, its upper half
   // repeats the lower one into the unused half of the wave's slot)
   // Blocks are requested in order, each once: the per-lane source pointers just advance.
-  const int64_t nb = (N + 31) / 32;
+  const int64_t nb = (N + 31) / 32;                       // all blocks of 32 tokens
+  const int64_t b0 = seg * a.blocks_per_seg;              // this workgroup's blocks: b0 .. b1-1
+  const int64_t b1 = b0 + a.blocks_per_seg < nb ? b0 + a.blocks_per_seg : nb;
   const int rrow = (lane & 16) + rho(lane & 15);   // r is kept in MFMA row order
-  const uint16_t* xsrc = a.X + drow * a.ldx + dcol;
-  const uint16_t* ysrc = a.dY + drow * a.ldy + dcol;
-  const float* rsrc = Rw + rrow;
+  const uint16_t* xsrc = a.X + (b0 * 32 + drow) * a.ldx + dcol;
+  const uint16_t* ysrc = a.dY + (b0 * 32 + drow) * a.ldy + dcol;
+  const float* rsrc = Rw + b0 * 32 + rrow;
   auto dma = [&](int64_t blkidx, int stage) {
     const uint16_t* xs = xsrc;
     const uint16_t* ys = ysrc;
@@ -541,9 +551,9 @@ __global__ __launch_bounds__(kW16Threads) void bwd_wgt16_kernel(BwdArgs a) {
     ysrc += 32 * a.ldy;
     rsrc += 32;
   };
-  dma(0, 0);
-  if (nb > 1) dma(1, 1);
-  if (nb > 2) dma(2, 2);
+  dma(b0, 0);
+  if (b0 + 1 < b1) dma(b0 + 1, 1);
+  if (b0 + 2 < b1) dma(b0 + 2, 2);
   __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0)
   __syncthreads();
 
@@ -578,7 +588,7 @@ __global__ __launch_bounds__(kW16Threads) void bwd_wgt16_kernel(BwdArgs a) {
     constexpr int S = decltype(S_)::value;
     constexpr int SN1 = (S + 1) % kW16Stages;               // next block's stage
     constexpr int SO = S * kTileBytes, SN = SN1 * kTileBytes;   // tile offsets inside a ring
-    const bool more2 = (b + 2 < nb), more3 = (b + 3 < nb);
+    const bool more2 = (b + 2 < b1), more3 = (b + 3 < b1);
     if (b == nb - 1) {   // rows past N were read from row N-1: give them r = 0
 #pragma unroll
       for (int tb = 0; tb < 2; ++tb)
@@ -693,17 +703,27 @@ __global__ __launch_bounds__(kW16Threads) void bwd_wgt16_kernel(BwdArgs a) {
   using C1 = std::integral_constant<int, 1>;
   using C2 = std::integral_constant<int, 2>;
   using C3 = std::integral_constant<int, 3>;
-  for (int64_t b = 0; b < nb; b += 4) {
+  for (int64_t b = b0; b < b1; b += 4) {
     step(b, C0{});
-    if (b + 1 < nb) step(b + 1, C1{});
-    if (b + 2 < nb) step(b + 2, C2{});
-    if (b + 3 < nb) step(b + 3, C3{});
+    if (b + 1 < b1) step(b + 1, C1{});
+    if (b + 2 < b1) step(b + 2, C2{});
+    if (b + 3 < b1) step(b + 3, C3{});
   }
   // drain the reads issued for a block that does not exist
   asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(opc[0]), "+v"(opc[1]), "+v"(opc[2]), "+v"(opc[3]),
                                         "+v"(rvc[0]), "+v"(rvc[1]));
 
-  if (active) {
+  if (active && a.wsplit > 1) {
+    // fp32 partial gradients of this token segment: [seg][K | U | V][row][128]
+    const size_t rows = (size_t)a.H * nblk * 16;
+    float* dst = a.WPws + (((size_t)seg * 3) * rows + row0 + cn) * kDh + 4 * gq;
+#pragma unroll
+    for (int jb = 0; jb < 8; ++jb) {
+      *reinterpret_cast<f32x4*>(dst + 16 * jb) = dK[jb];
+      *reinterpret_cast<f32x4*>(dst + rows * kDh + 16 * jb) = dU[jb];
+      *reinterpret_cast<f32x4*>(dst + 2 * rows * kDh + 16 * jb) = dV[jb];
+    }
+  } else if (active) {
     // accumulators are [j][c]: lane = neuron column cn, register v = row 16jb + 4gq + v
     const size_t off = (row0 + cn) * kDh + 4 * gq;
 #pragma unroll
@@ -723,6 +743,45 @@ __global__ __launch_bounds__(kW16Threads) void bwd_wgt16_kernel(BwdArgs a) {
       }
     }
   }
+}
+
+// dW[i] = bf16(sum_seg partial[seg][which][i]) for which = K, U, V; fixed order
+__global__ void bwd_wgt_reduce_kernel(BwdArgs a, size_t count) {
+  const size_t idx = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
+  if (idx >= count) return;
+  uint16_t* outs[3] = {a.dWg, a.dWu, a.dWd};
+#pragma unroll
+  for (int which = 0; which < 3; ++which) {
+    if (!outs[which]) continue;
+    f32x4 sum = {0.f, 0.f, 0.f, 0.f};
+    for (int sgm = 0; sgm < a.wsplit; ++sgm)
+      sum += *reinterpret_cast<const f32x4*>(a.WPws + ((size_t)sgm * 3 + which) * count + idx);
+    u32x2 pk = {pack_bf16(sum[0], sum[1]), pack_bf16(sum[2], sum[3])};
+    *reinterpret_cast<u32x2*>(outs[which] + idx) = pk;
+  }
+}
+
+// Tokens are shared out only when that shortens the kernel by a fifth or more: its time goes in
+// rounds of 256 workgroups (one per CU), so S segments cost ceil(groups * S / 256) / S rounds.
+struct WgtSplit { int segs; int64_t blocks_per_seg; };
+WgtSplit plan_wgt_split(const Problem& p) {
+  const int64_t nb = (p.N + 31) / 32;
+  const int64_t groups = (int64_t)p.H * (((int64_t)p.E * p.de / 16 + kW16Waves - 1) / kW16Waves);
+  auto rounds = [&](int64_t S) { return (double)((groups * S + 255) / 256) / (double)S; };
+  int best = 1;
+  for (int S = 2; S <= 8; ++S)
+    if (nb / S >= 16 && rounds(S) < 0.9 * rounds(best)) best = S;   // more segments only for a clear gain
+  if (rounds(best) > 0.8 * rounds(1)) best = 1;
+  WgtSplit w;
+  w.blocks_per_seg = (nb + best - 1) / best;
+  w.segs = (int)((nb + w.blocks_per_seg - 1) / w.blocks_per_seg);
+  if (w.segs < 1) { w.segs = 1; w.blocks_per_seg = nb > 0 ? nb : 1; }
+  return w;
+}
+size_t wgt_split_bytes(const Problem& p) {
+  if (p.dh != kDh || p.N == 0) return 0;
+  const WgtSplit w = plan_wgt_split(p);
+  return w.segs > 1 ? (size_t)w.segs * 3 * p.H * p.E * p.de * kDh * sizeof(float) : 0;
 }
 
 // ---------------------------------------------------------------------------
@@ -1104,7 +1163,10 @@ int launch_tok(const Problem& p, BwdArgs a, hipStream_t stream) {
 int launch_wgt16(const Problem& p, BwdArgs a, hipStream_t stream) {
   const int nblk = p.E * p.de / 16;
   const int wg_per_head = (nblk + kW16Waves - 1) / kW16Waves;
-  a.n_items = (int64_t)wg_per_head * p.H;
+  const WgtSplit wsp = plan_wgt_split(p);
+  a.wsplit = wsp.segs;
+  a.blocks_per_seg = wsp.blocks_per_seg;
+  a.n_items = (int64_t)wg_per_head * p.H * wsp.segs;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = allow_full_lds(&bwd_wgt16_kernel);
@@ -1113,6 +1175,11 @@ int launch_wgt16(const Problem& p, BwdArgs a, hipStream_t stream) {
   }
   hipLaunchKernelGGL(bwd_wgt16_kernel, dim3((unsigned)xcd_grid_size(a.n_items)),
                      dim3(kW16Threads), kW16LdsBytes, stream, a);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess || wsp.segs == 1) return (int)e;
+  const size_t count = (size_t)p.H * p.E * p.de * kDh;
+  hipLaunchKernelGGL(bwd_wgt_reduce_kernel, dim3((unsigned)((count / 4 + 255) / 256)), dim3(256), 0,
+                     stream, a, count);
   return (int)hipGetLastError();
 }
 
@@ -1169,7 +1236,7 @@ size_t bwd_workspace_bytes(const Problem& p, int dtype) {
   if (p.N == 0) return 0;   // an empty batch only zero-fills the weight gradients
   const size_t nhe = align256((size_t)p.N * p.H * p.E * sizeof(float));
   const size_t wr = align256((size_t)p.H * kRouteParts * p.dh * p.E * sizeof(float));
-  return 2 * nhe + wr;
+  return 2 * nhe + wr + wgt_split_bytes(p);
 }
 
 int launch_bwd(const Problem& p, int dtype, const void* X, const void* Wg, const void* Wu,
@@ -1219,6 +1286,10 @@ int launch_bwd(const Problem& p, int dtype, const void* X, const void* Wg, const
   a.Rws = reinterpret_cast<float*>(static_cast<unsigned char*>(ws));
   a.DPws = reinterpret_cast<float*>(static_cast<unsigned char*>(ws) + nhe);
   a.WRws = reinterpret_cast<float*>(static_cast<unsigned char*>(ws) + 2 * nhe);
+  a.WPws = reinterpret_cast<float*>(static_cast<unsigned char*>(ws) + 2 * nhe +
+                                    align256((size_t)p.H * kRouteParts * p.dh * p.E * sizeof(float)));
+  a.wsplit = 1;
+  a.blocks_per_seg = (p.N + 31) / 32;
   a.N = p.N; a.ldx = p.ldx; a.ldy = p.ldy;
   a.H = p.H; a.E = p.E; a.de = p.de; a.dh = p.dh; a.route_mode = p.route_mode; a.eps = p.eps;
   a.n_split = kRouteParts;
