@@ -764,10 +764,14 @@ __global__ void bwd_wgt_reduce_kernel(BwdArgs a, size_t count) {
 // Tokens are shared out only when that shortens the kernel by a fifth or more: its time goes in
 // rounds of 256 workgroups (one per CU), so S segments cost ceil(groups * S / 256) / S rounds.
 struct WgtSplit { int segs; int64_t blocks_per_seg; };
+// waves per workgroup and workgroups the chip holds at once, per head width
+constexpr int wgt_waves(int dh) { return dh == kDh ? kW16Waves : 4; }
+constexpr int wgt_slots(int dh) { return dh == 64 ? 512 : 256; }
 WgtSplit plan_wgt_split(const Problem& p) {
   const int64_t nb = (p.N + 31) / 32;
-  const int64_t groups = (int64_t)p.H * (((int64_t)p.E * p.de / 16 + kW16Waves - 1) / kW16Waves);
-  auto rounds = [&](int64_t S) { return (double)((groups * S + 255) / 256) / (double)S; };
+  const int waves = wgt_waves(p.dh), slots = wgt_slots(p.dh);
+  const int64_t groups = (int64_t)p.H * (((int64_t)p.E * p.de / 16 + waves - 1) / waves);
+  auto rounds = [&](int64_t S) { return (double)((groups * S + slots - 1) / slots) / (double)S; };
   int best = 1;
   for (int S = 2; S <= 8; ++S)
     if (nb / S >= 16 && rounds(S) < 0.9 * rounds(best)) best = S;   // more segments only for a clear gain
@@ -779,9 +783,9 @@ WgtSplit plan_wgt_split(const Problem& p) {
   return w;
 }
 size_t wgt_split_bytes(const Problem& p) {
-  if (p.dh != kDh || p.N == 0) return 0;
+  if (p.N == 0) return 0;
   const WgtSplit w = plan_wgt_split(p);
-  return w.segs > 1 ? (size_t)w.segs * 3 * p.H * p.E * p.de * kDh * sizeof(float) : 0;
+  return w.segs > 1 ? (size_t)w.segs * 3 * p.H * p.E * p.de * p.dh * sizeof(float) : 0;
 }
 
 // ---------------------------------------------------------------------------
@@ -822,8 +826,10 @@ __global__ __launch_bounds__(64 * NW, DH == 64 ? 2 : 1) void bwd_wgt_dh_kernel(B
   auto rho = [](int m) { return DH >= 128 ? ((m & 9) | ((m & 2) << 1) | ((m & 4) >> 1)) : m; };
   const int nblk = a.E * a.de / 16;              // 16-neuron blocks per head
   const int wg_per_head = (nblk + NW - 1) / NW;
-  const int64_t item = xcd_work_item(blockIdx.x, a.n_items);
-  if (item >= a.n_items) return;
+  const int64_t item_s = xcd_work_item(blockIdx.x, a.n_items);
+  if (item_s >= a.n_items) return;
+  const int seg = (int)(item_s % a.wsplit);          // this workgroup's share of the tokens
+  const int64_t item = item_s / a.wsplit;
   const int h = (int)(item / wg_per_head);
   const int blk = (int)(item % wg_per_head) * NW + wave;
   const bool active = blk < nblk;
@@ -849,6 +855,8 @@ __global__ __launch_bounds__(64 * NW, DH == 64 ? 2 : 1) void bwd_wgt_dh_kernel(B
 
   // ---- staging: rows past N are zero (and get r = 0), so they add nothing ----------
   const int64_t nb = (N + 31) / 32;
+  const int64_t b0 = seg * a.blocks_per_seg;              // this workgroup's blocks: b0 .. b1-1
+  const int64_t b1 = b0 + a.blocks_per_seg < nb ? b0 + a.blocks_per_seg : nb;
   // Two register sets: while block b is consumed from LDS, block b+1 sits in one set (stored
   // at the end of the step) and the loads of block b+2 are in flight into the other.  At
   // d_h = 256 there are no registers for a second set: one set, requested one block ahead.
@@ -893,21 +901,21 @@ __global__ __launch_bounds__(64 * NW, DH == 64 ? 2 : 1) void bwd_wgt_dh_kernel(B
   };
   using S0 = std::integral_constant<int, 0>;
   using SB = std::integral_constant<int, SETS - 1>;   // the second set, if there is one
-  gload(0, S0{});
-  if (SETS == 2 && nb > 1) gload(1, SB{});
-  lstore(0, S0{});
+  gload(b0, S0{});
+  if (SETS == 2 && b0 + 1 < b1) gload(b0 + 1, SB{});
+  lstore((int)(b0 & 1), S0{});
   float rv[2][4];
   __syncthreads();
 
   // block b: its tiles are in LDS buffer b & 1 and its r in register set SL, which is then
   // free and receives block b+2; SS holds block b+1
   auto step = [&](int64_t b, auto SL, auto SS) {
-    const bool more = (b + 1 < nb);
+    const bool more = (b + 1 < b1);
 #pragma unroll
     for (int tb = 0; tb < 2; ++tb)
 #pragma unroll
       for (int v = 0; v < 4; ++v) rv[tb][v] = rnext[decltype(SL)::value][tb][v];
-    if (b + SETS < nb) gload(b + SETS, SL);
+    if (b + SETS < b1) gload(b + SETS, SL);
     const unsigned char* qt = smem + (b & 1) * 2 * kTileBytes;   // dY tile: + kTileBytes
 
     // All LDS operands of the step form one stream, issued untracked kDhWindow items ahead
@@ -993,15 +1001,25 @@ __global__ __launch_bounds__(64 * NW, DH == 64 ? 2 : 1) void bwd_wgt_dh_kernel(B
     __syncthreads();
   };
   if constexpr (SETS == 1) {
-    for (int64_t b = 0; b < nb; ++b) step(b, S0{}, S0{});
+    for (int64_t b = b0; b < b1; ++b) step(b, S0{}, S0{});
   } else {
-    for (int64_t b = 0; b < nb; b += 2) {
+    for (int64_t b = b0; b < b1; b += 2) {
       step(b, S0{}, SB{});
-      if (b + 1 < nb) step(b + 1, SB{}, S0{});
+      if (b + 1 < b1) step(b + 1, SB{}, S0{});
     }
   }
 
-  if (active) {
+  if (active && a.wsplit > 1) {
+    // fp32 partial gradients of this token segment: [seg][K | U | V][row][d_h]
+    const size_t rows = (size_t)a.H * nblk * 16;
+    float* dst = a.WPws + (((size_t)seg * 3) * rows + row0 + cn) * DH + 4 * gq;
+#pragma unroll
+    for (int jb = 0; jb < JB; ++jb) {
+      *reinterpret_cast<f32x4*>(dst + 16 * jb) = dK[jb];
+      *reinterpret_cast<f32x4*>(dst + rows * DH + 16 * jb) = dU[jb];
+      *reinterpret_cast<f32x4*>(dst + 2 * rows * DH + 16 * jb) = dV[jb];
+    }
+  } else if (active) {
     // accumulators are [j][c]: lane = neuron column cn, register v = row 16jb + 4gq + v
     const size_t off = (row0 + cn) * DH + 4 * gq;
 #pragma unroll
@@ -1185,9 +1203,13 @@ int launch_wgt16(const Problem& p, BwdArgs a, hipStream_t stream) {
 
 template <int DH, int NW>
 int launch_wgt_dh(const Problem& p, BwdArgs a, hipStream_t stream) {
+  static_assert(NW == wgt_waves(DH), "plan_wgt_split assumes this workgroup size");
   const int nblk = p.E * p.de / 16;
   const int wg_per_head = (nblk + NW - 1) / NW;
-  a.n_items = (int64_t)wg_per_head * p.H;
+  const WgtSplit wsp = plan_wgt_split(p);
+  a.wsplit = wsp.segs;
+  a.blocks_per_seg = wsp.blocks_per_seg;
+  a.n_items = (int64_t)wg_per_head * p.H * wsp.segs;
   constexpr size_t lds = 2 * 2 * 32 * DH * 2;   // two buffers of a q and a dY tile
   static bool attr_set = false;
   if (!attr_set) {
@@ -1197,6 +1219,11 @@ int launch_wgt_dh(const Problem& p, BwdArgs a, hipStream_t stream) {
   }
   hipLaunchKernelGGL((bwd_wgt_dh_kernel<DH, NW>), dim3((unsigned)xcd_grid_size(a.n_items)),
                      dim3(64 * NW), lds, stream, a);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess || wsp.segs == 1) return (int)e;
+  const size_t count = (size_t)p.H * p.E * p.de * DH;
+  hipLaunchKernelGGL(bwd_wgt_reduce_kernel, dim3((unsigned)((count / 4 + 255) / 256)), dim3(256), 0,
+                     stream, a, count);
   return (int)hipGetLastError();
 }
 
