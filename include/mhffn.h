@@ -112,7 +112,11 @@ typedef struct {
  * prefill) the blocks of eq:flash-ffn-loop are shared out over several
  * workgroups per token tile and their fp32 partial outputs, n_split * N *
  * d_model * 4 bytes (a few output-sized buffers, never d_ff-sized ones), pass
- * through the workspace.  For the unfused ops it is the three
+ * through the workspace.  For MHFFN_OP_BACKWARD it is the gating weights R and
+ * their gradient as [H][E][N] fp32, the partial sums of dW_r, and, for shapes
+ * whose weights alone cannot fill the chip, fp32 partial weight gradients of a
+ * few token segments (all summed in a fixed order: results are bit-identical
+ * from run to run).  For the unfused ops it is the three
  * materialised [N][H][d_ff] activations plus the [N][H][E] weights, i.e. the
  * O((L*H + d_model)*d_ff) footprint of the naive multi-head FFN. */
 size_t mhffn_workspace_bytes(const mhffn_desc* desc, int op);
