@@ -21,8 +21,11 @@
  *    caller.  `desc` is a HOST pointer.  `hip_stream` is a hipStream_t passed
  *    as void* (NULL = the default stream).
  *  - The library never allocates or frees device memory, never synchronises
- *    and keeps no state between calls: all work is enqueued on `hip_stream`
- *    and the call returns immediately.  Scratch comes from the caller through
+ *    and keeps no data between calls (all it remembers is on which devices it
+ *    has already raised a kernel's LDS limit): all work is enqueued on
+ *    `hip_stream`, which must belong to the calling thread's current device,
+ *    and the call returns immediately.  Calls may come from several threads
+ *    and for several devices.  Scratch comes from the caller through
  *    `workspace` (at least mhffn_workspace_bytes() bytes, 256-byte aligned;
  *    may be NULL when that size is 0).
  *  - Outputs are overwritten, never accumulated into.

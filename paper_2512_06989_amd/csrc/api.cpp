@@ -1,6 +1,6 @@
 // C ABI of the fused Multi-Head FFN library: argument validation on the host,
 // then dispatch to the gfx950 kernels.  Nothing here allocates, synchronises or
-// keeps state; see include/mhffn.h for the contract.
+// keeps data between calls; see include/mhffn.h for the contract.
 #include "../../include/mhffn.h"
 
 #include "mhffn_internal.h"

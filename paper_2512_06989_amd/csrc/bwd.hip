@@ -1153,9 +1153,8 @@ __global__ void fill_zero_kernel(uint32_t* p, size_t n_words) {
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 template <typename K>
-hipError_t allow_full_lds(K kernel) {
-  return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
-                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBytesPerWorkgroup);
+hipError_t allow_full_lds(K kernel, std::atomic<uint64_t>& done) {
+  return allow_lds_bytes(reinterpret_cast<const void*>(kernel), (int)kLdsBytesPerWorkgroup, done);
 }
 
 constexpr int tok_block_tokens(int dh) { return dh == 128 ? 256 : 128; }
@@ -1167,12 +1166,8 @@ int launch_tok(const Problem& p, BwdArgs a, hipStream_t stream) {
   a.n_tiles = (p.N + BM - 1) / BM;
   a.n_items = a.n_tiles * p.H;
   const size_t lds = (size_t)kTokStages * tok_stage_bytes(DH) + (size_t)p.E * BM * sizeof(float);
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = allow_full_lds(&bwd_tok_kernel<DH, TB, NW>);
-    if (e != hipSuccess) return (int)e;
-    attr_set = true;
-  }
+  static std::atomic<uint64_t> lds_allowed{0};
+  if (hipError_t e = allow_full_lds(&bwd_tok_kernel<DH, TB, NW>, lds_allowed); e != hipSuccess) return (int)e;
   hipLaunchKernelGGL((bwd_tok_kernel<DH, TB, NW>), dim3((unsigned)xcd_grid_size(a.n_items)),
                      dim3(64 * NW), lds, stream, a);
   return (int)hipGetLastError();
@@ -1185,12 +1180,8 @@ int launch_wgt16(const Problem& p, BwdArgs a, hipStream_t stream) {
   a.wsplit = wsp.segs;
   a.blocks_per_seg = wsp.blocks_per_seg;
   a.n_items = (int64_t)wg_per_head * p.H * wsp.segs;
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = allow_full_lds(&bwd_wgt16_kernel);
-    if (e != hipSuccess) return (int)e;
-    attr_set = true;
-  }
+  static std::atomic<uint64_t> lds_allowed{0};
+  if (hipError_t e = allow_full_lds(&bwd_wgt16_kernel, lds_allowed); e != hipSuccess) return (int)e;
   hipLaunchKernelGGL(bwd_wgt16_kernel, dim3((unsigned)xcd_grid_size(a.n_items)),
                      dim3(kW16Threads), kW16LdsBytes, stream, a);
   hipError_t e = hipGetLastError();
@@ -1211,12 +1202,8 @@ int launch_wgt_dh(const Problem& p, BwdArgs a, hipStream_t stream) {
   a.blocks_per_seg = wsp.blocks_per_seg;
   a.n_items = (int64_t)wg_per_head * p.H * wsp.segs;
   constexpr size_t lds = 2 * 2 * 32 * DH * 2;   // two buffers of a q and a dY tile
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = allow_full_lds(&bwd_wgt_dh_kernel<DH, NW>);
-    if (e != hipSuccess) return (int)e;
-    attr_set = true;
-  }
+  static std::atomic<uint64_t> lds_allowed{0};
+  if (hipError_t e = allow_full_lds(&bwd_wgt_dh_kernel<DH, NW>, lds_allowed); e != hipSuccess) return (int)e;
   hipLaunchKernelGGL((bwd_wgt_dh_kernel<DH, NW>), dim3((unsigned)xcd_grid_size(a.n_items)),
                      dim3(64 * NW), lds, stream, a);
   hipError_t e = hipGetLastError();

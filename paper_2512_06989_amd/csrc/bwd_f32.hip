@@ -431,18 +431,13 @@ int launch_bwd_f32(const Problem& p, const void* X, const void* Wg, const void* 
   a.H = p.H; a.dh = p.dh; a.E = p.E; a.de = p.de; a.route_mode = p.route_mode; a.eps = p.eps;
   a.chunks_per_sub = (p.de + kBC - 1) / kBC;
 
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&bwd_f32_tok_kernel),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       (int)kLdsBytesPerWorkgroup);
-    if (e == hipSuccess)
-      e = hipFuncSetAttribute(reinterpret_cast<const void*>(&bwd_f32_wgt_kernel),
-                              hipFuncAttributeMaxDynamicSharedMemorySize,
-                              (int)kLdsBytesPerWorkgroup);
-    if (e != hipSuccess) return (int)e;
-    attr_set = true;
-  }
+  static std::atomic<uint64_t> tok_allowed{0}, wgt_allowed{0};
+  if (hipError_t e0 = allow_lds_bytes(reinterpret_cast<const void*>(&bwd_f32_tok_kernel),
+                                      (int)kLdsBytesPerWorkgroup, tok_allowed); e0 != hipSuccess)
+    return (int)e0;
+  if (hipError_t e0 = allow_lds_bytes(reinterpret_cast<const void*>(&bwd_f32_wgt_kernel),
+                                      (int)kLdsBytesPerWorkgroup, wgt_allowed); e0 != hipSuccess)
+    return (int)e0;
   // token-major kernel (always: it also produces R for the weight-major kernel)
   a.n_tiles = (p.N + kTM - 1) / kTM;
   a.n_items = a.n_tiles * p.H;

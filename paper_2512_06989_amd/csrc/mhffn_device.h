@@ -14,6 +14,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 namespace mhffn {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -196,6 +198,21 @@ __device__ __forceinline__ int64_t xcd_work_item(int64_t bid, int64_t n_items) {
 }
 __host__ __device__ __forceinline__ int64_t xcd_grid_size(int64_t n_items) {
   return 8 * ((n_items + 7) / 8);
+}
+
+// Host side.  A kernel's dynamic-LDS limit is an attribute of the kernel on one device:
+// raise it the first time the kernel is launched on each device.  `done` is the launcher's
+// own bit mask of devices (one static per kernel instantiation); concurrent first launches
+// from several threads at worst set the attribute twice.
+inline hipError_t allow_lds_bytes(const void* kernel, int bytes, std::atomic<uint64_t>& done) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  const uint64_t bit = (uint64_t)1 << (dev & 63);
+  if (dev < 64 && (done.load(std::memory_order_acquire) & bit)) return hipSuccess;
+  e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  if (e == hipSuccess && dev < 64) done.fetch_or(bit, std::memory_order_release);
+  return e;
 }
 
 }  // namespace mhffn

@@ -546,14 +546,10 @@ int run_unfused(const Problem& p, const void* X, const void* Wg, const void* Wu,
 
   // (i) gating weights
   {
-    static bool gate_attr = false;
-    if (!gate_attr) {
-      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gating_kernel<T>),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize,
-                                         (int)kLdsBytesPerWorkgroup);
-      if (e != hipSuccess) return (int)e;
-      gate_attr = true;
-    }
+    static std::atomic<uint64_t> lds_allowed{0};
+    if (hipError_t e0 = allow_lds_bytes(reinterpret_cast<const void*>(&gating_kernel<T>),
+                                        (int)kLdsBytesPerWorkgroup, lds_allowed); e0 != hipSuccess)
+      return (int)e0;
     hipLaunchKernelGGL(gating_kernel<T>, dim3((unsigned)((p.N + kGateTok - 1) / kGateTok), p.H),
                        dim3(256), p.route_mode == 0 ? gating_lds_bytes(p.dh, p.E) : 0, st, a);
   }
