@@ -98,10 +98,10 @@ typedef struct {
  *   bf16: the fused kernels need d_head in {64, 128, 256}, d_sub % 32 == 0 and
  *         n_sub <= 96 (backward with d_head = 256: n_sub <= 64); other shapes
  *         return MHFFN_ERR_UNSUPPORTED.
- *   fp32: the fused kernels take d_head % 4 == 0, any n_sub, d_sub, as long as their LDS
- *         tiles fit: the forward up to d_head = 256, the backward (which keeps whole
- *         d_head-wide token and weight tiles resident) up to d_head = 232 with few
- *         sub-networks and d_head = 128 with several hundred.
+ *   fp32: the fused kernels take d_head % 4 == 0 up to 256, any n_sub, d_sub, as long as
+ *         their LDS tiles fit.  The backward keeps whole d_head-wide token and weight tiles
+ *         and two n_sub-wide rows per token resident: d_head = 256 with up to about 170
+ *         sub-networks, d_head = 128 with several hundred.
  *   mhffn_reference_unfused takes any shape with d_head % 8 == 0.
  *   Row strides must keep every row 16-byte aligned.
  */

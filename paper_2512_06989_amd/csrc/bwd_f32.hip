@@ -1,13 +1,14 @@
 // Fused, recompute-based backward of the Multi-Head FFN in fp32 (storage and
 // arithmetic), gfx950.  Shape-generic companion of the bf16 MFMA kernels: any E,
-// any d_e, d_h a multiple of 4 up to 256 (as long as the LDS tiles fit).  Same two
+// any d_e, d_h a multiple of 4 up to 256 (as long as the LDS tiles fit; weight chunks
+// of 32 neurons, of 16 where 32 would not fit, i.e. for d_h above 232).  Same two
 // sweeps as the bf16 path (appendix algorithms "Backward (dQ,dR)" and "Backward
 // (dK,dU,dV)", plus the derivative through eq:routing); nothing of the
 // [N][H][d_ff] intermediate is saved or written.  Plain fp32 FMAs on tiles staged
 // in LDS: this path exists for parity at fp32 accuracy, not for throughput.
 //
 //   bwd_f32_tok_kernel   32 tokens x one head: R, dX, dr_e -> dp_e (or dR)
-//   bwd_f32_wgt_kernel   32 neurons of one sub-network, all tokens: dK, dU, dV
+//   bwd_f32_wgt_kernel   32 (16) neurons of one sub-network, all tokens: dK, dU, dV
 //   bwd_f32_route_kernel dW_r[h][j][e] = sum_tok q[tok][j] dp[tok][e]
 // Every sum runs in a fixed order: results are bit-identical run to run.
 #include "mhffn_device.h"
@@ -17,7 +18,7 @@ namespace mhffn {
 namespace {
 
 constexpr int kTM = 32;       // tokens per tile
-constexpr int kBC = 32;       // neurons per chunk
+// neurons per weight chunk: template parameter BC of the kernels, 32 or 16
 constexpr int kThreads = 256;
 
 struct BwdF32Args {
@@ -46,9 +47,10 @@ __device__ __forceinline__ float sigmoid_f32(float x) {
   return t / (1.0f + t);
 }
 
-// sum over the 32 lanes of a half-wave (lanes with equal tid / 32), fixed order
-__device__ __forceinline__ float half_wave_sum(float v) {
-  v += __shfl_xor(v, 16);
+// sum over the BC lanes with equal tid / BC, fixed order
+template <int BC>
+__device__ __forceinline__ float lane_group_sum(float v) {
+  if (BC == 32) v += __shfl_xor(v, 16);
   v += __shfl_xor(v, 8);
   v += __shfl_xor(v, 4);
   v += __shfl_xor(v, 2);
@@ -59,17 +61,20 @@ __device__ __forceinline__ float half_wave_sum(float v) {
 // ---------------------------------------------------------------------------
 // token-major: R (to the workspace), dX, dp or dR
 // ---------------------------------------------------------------------------
+template <int BC>
 __global__ __launch_bounds__(kThreads) void bwd_f32_tok_kernel(BwdF32Args a) {
+  constexpr int kBC = BC;
+  constexpr int TPT = kTM * BC / kThreads;   // tokens per thread in the products: 4 or 2
   extern __shared__ __attribute__((aligned(16))) float smem_f[];
   const int dh = a.dh, E = a.E, de = a.de;
   const int kst = dh + 1;                  // padded row stride of the weight chunks
   float* Qs = smem_f;                      // [32][dh]
   float* Ys = Qs + kTM * dh;               // [32][dh]   dY
-  float* Ks = Ys + kTM * dh;               // [32][dh+1]
-  float* Us = Ks + kBC * kst;              // [32][dh+1]
-  float* Vs = Us + kBC * kst;              // [32][dh+1]
-  float* DMs = Vs + kBC * kst;             // [32 tokens][33]
-  float* DNs = DMs + kTM * (kBC + 1);      // [32 tokens][33]
+  float* Ks = Ys + kTM * dh;               // [BC][dh+1]
+  float* Us = Ks + kBC * kst;              // [BC][dh+1]
+  float* Vs = Us + kBC * kst;              // [BC][dh+1]
+  float* DMs = Vs + kBC * kst;             // [32 tokens][BC+1]
+  float* DNs = DMs + kTM * (kBC + 1);      // [32 tokens][BC+1]
   float* Rs = DNs + kTM * (kBC + 1);       // [32 tokens][E]
   float* DRs = Rs + kTM * E;               // [32 tokens][E]  dr_e, later dp_e
   float* Zinv = DRs + kTM * E;             // [32]  1 / (Z + eps)
@@ -124,7 +129,7 @@ __global__ __launch_bounds__(kThreads) void bwd_f32_tok_kernel(BwdF32Args a) {
   }
 
   // thread roles
-  const int c1 = tid & 31, tg1 = tid >> 5;   // products: neuron c1, tokens 4*tg1 .. +3
+  const int c1 = tid % BC, tg1 = tid / BC;   // products: neuron c1, tokens TPT*tg1 .. +TPT-1
   const int jq = tid & 63, tq = tid >> 6;    // dX: columns jq + 64*i, tokens 8*tq .. +7
   float acc[8][4];
 #pragma unroll
@@ -145,25 +150,27 @@ __global__ __launch_bounds__(kThreads) void bwd_f32_tok_kernel(BwdF32Args a) {
         Vs[c * kst + j] = ok ? a.Wd[base + idx] : 0.f;
       }
       __syncthreads();
-      float m[4] = {0.f, 0.f, 0.f, 0.f}, n[4] = {0.f, 0.f, 0.f, 0.f}, da[4] = {0.f, 0.f, 0.f, 0.f};
+      float m[TPT], n[TPT], da[TPT];
+#pragma unroll
+      for (int t = 0; t < TPT; ++t) { m[t] = 0.f; n[t] = 0.f; da[t] = 0.f; }
       for (int j = 0; j < dh; ++j) {
         const float kv = Ks[c1 * kst + j], uv = Us[c1 * kst + j], vv = Vs[c1 * kst + j];
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
-          const float qv = Qs[(4 * tg1 + t) * dh + j];
+        for (int t = 0; t < TPT; ++t) {
+          const float qv = Qs[(TPT * tg1 + t) * dh + j];
           m[t] = fmaf(qv, kv, m[t]);
           n[t] = fmaf(qv, uv, n[t]);
-          da[t] = fmaf(Ys[(4 * tg1 + t) * dh + j], vv, da[t]);
+          da[t] = fmaf(Ys[(TPT * tg1 + t) * dh + j], vv, da[t]);
         }
       }
 #pragma unroll
-      for (int t = 0; t < 4; ++t) {
-        const int tok = 4 * tg1 + t;
+      for (int t = 0; t < TPT; ++t) {
+        const int tok = TPT * tg1 + t;
         const float sg = sigmoid_f32(m[t]);
         const float silu = m[t] * sg;
         const float rw = Rs[tok * E + e];
-        // dr_e += sum_c dA SiLU(M) N : the 32 neurons of the chunk sit in one half-wave
-        const float part = half_wave_sum(da[t] * silu * n[t]);
+        // dr_e += sum_c dA SiLU(M) N : the BC neurons of the chunk sit in adjacent lanes
+        const float part = lane_group_sum<BC>(da[t] * silu * n[t]);
         if (c1 == 0) DRs[tok * E + e] += part;
         const float rda = rw * da[t];
         DNs[tok * (kBC + 1) + c1] = rda * silu;
@@ -248,16 +255,21 @@ __global__ __launch_bounds__(kThreads) void bwd_f32_tok_kernel(BwdF32Args a) {
 // ---------------------------------------------------------------------------
 // weight-major: dK, dU, dV of one chunk of 32 neurons, summed over all tokens
 // ---------------------------------------------------------------------------
+template <int BC>
 __global__ __launch_bounds__(kThreads) void bwd_f32_wgt_kernel(BwdF32Args a) {
+  constexpr int kBC = BC;
+  constexpr int TPT = kTM * BC / kThreads;   // tokens per thread in the products
+  constexpr int TPN = kThreads / BC;         // threads per neuron in the gradients: 8 or 16
+  constexpr int NI = 256 / TPN;              // columns per thread at d_h = 256
   extern __shared__ __attribute__((aligned(16))) float smem_f[];
   const int dh = a.dh, E = a.E, de = a.de;
   const int kst = dh + 1;
   float* Qs = smem_f;                      // [32][dh]
   float* Ys = Qs + kTM * dh;               // [32][dh]
-  float* Ks = Ys + kTM * dh;               // [32][dh+1]
+  float* Ks = Ys + kTM * dh;               // [BC][dh+1]
   float* Us = Ks + kBC * kst;
   float* Vs = Us + kBC * kst;
-  float* DMs = Vs + kBC * kst;             // [32 tokens][33]
+  float* DMs = Vs + kBC * kst;             // [32 tokens][BC+1]
   float* DNs = DMs + kTM * (kBC + 1);
   float* AGs = DNs + kTM * (kBC + 1);      // r SiLU(m) n
   float* Rt = AGs + kTM * (kBC + 1);       // [32] r of this sub-network
@@ -281,12 +293,12 @@ __global__ __launch_bounds__(kThreads) void bwd_f32_wgt_kernel(BwdF32Args a) {
     Vs[c * kst + j] = ok ? a.Wd[base + idx] : 0.f;
   }
 
-  const int c1 = tid & 31, tg1 = tid >> 5;   // products: neuron c1, tokens 4*tg1 .. +3
-  const int c2 = tid >> 3, j0 = tid & 7;     // gradients: neuron c2, columns j0 + 8*i
-  float gk[32], gu[32], gv[32];
+  const int c1 = tid % BC, tg1 = tid / BC;   // products: neuron c1, tokens TPT*tg1 .. +TPT-1
+  const int c2 = tid / TPN, j0 = tid % TPN;  // gradients: neuron c2, columns j0 + TPN*i
+  float gk[NI], gu[NI], gv[NI];
 #pragma unroll
-  for (int i = 0; i < 32; ++i) { gk[i] = 0.f; gu[i] = 0.f; gv[i] = 0.f; }
-  const int ni = (dh + 7) / 8;
+  for (int i = 0; i < NI; ++i) { gk[i] = 0.f; gu[i] = 0.f; gv[i] = 0.f; }
+  const int ni = (dh + TPN - 1) / TPN;
   const float* Rrow = a.Rws + ((size_t)h * E + e) * N;
 
   for (int64_t tok0 = 0; tok0 < N; tok0 += kTM) {
@@ -299,20 +311,22 @@ __global__ __launch_bounds__(kThreads) void bwd_f32_wgt_kernel(BwdF32Args a) {
     }
     if (tid < kTM) Rt[tid] = (tok0 + tid < N) ? Rrow[tok0 + tid] : 0.f;
     __syncthreads();
-    float m[4] = {0.f, 0.f, 0.f, 0.f}, n[4] = {0.f, 0.f, 0.f, 0.f}, da[4] = {0.f, 0.f, 0.f, 0.f};
+    float m[TPT], n[TPT], da[TPT];
+#pragma unroll
+    for (int t = 0; t < TPT; ++t) { m[t] = 0.f; n[t] = 0.f; da[t] = 0.f; }
     for (int j = 0; j < dh; ++j) {
       const float kv = Ks[c1 * kst + j], uv = Us[c1 * kst + j], vv = Vs[c1 * kst + j];
 #pragma unroll
-      for (int t = 0; t < 4; ++t) {
-        const float qv = Qs[(4 * tg1 + t) * dh + j];
+      for (int t = 0; t < TPT; ++t) {
+        const float qv = Qs[(TPT * tg1 + t) * dh + j];
         m[t] = fmaf(qv, kv, m[t]);
         n[t] = fmaf(qv, uv, n[t]);
-        da[t] = fmaf(Ys[(4 * tg1 + t) * dh + j], vv, da[t]);
+        da[t] = fmaf(Ys[(TPT * tg1 + t) * dh + j], vv, da[t]);
       }
     }
 #pragma unroll
-    for (int t = 0; t < 4; ++t) {
-      const int tok = 4 * tg1 + t;
+    for (int t = 0; t < TPT; ++t) {
+      const int tok = TPT * tg1 + t;
       const float sg = sigmoid_f32(m[t]);
       const float silu = m[t] * sg;
       const float rw = Rt[tok];
@@ -326,9 +340,9 @@ __global__ __launch_bounds__(kThreads) void bwd_f32_wgt_kernel(BwdF32Args a) {
     for (int t = 0; t < kTM; ++t) {
       const float dm = DMs[t * (kBC + 1) + c2], dn = DNs[t * (kBC + 1) + c2], ag = AGs[t * (kBC + 1) + c2];
 #pragma unroll
-      for (int i = 0; i < 32; ++i) {
+      for (int i = 0; i < NI; ++i) {
         if (i < ni) {
-          const int j = j0 + 8 * i;
+          const int j = j0 + TPN * i;
           const float qv = (j < dh) ? Qs[t * dh + j] : 0.f;
           const float yv = (j < dh) ? Ys[t * dh + j] : 0.f;
           gk[i] = fmaf(dm, qv, gk[i]);
@@ -340,8 +354,8 @@ __global__ __launch_bounds__(kThreads) void bwd_f32_wgt_kernel(BwdF32Args a) {
   }
   if (c2 < rows) {
 #pragma unroll
-    for (int i = 0; i < 32; ++i) {
-      const int j = j0 + 8 * i;
+    for (int i = 0; i < NI; ++i) {
+      const int j = j0 + TPN * i;
       if (i < ni && j < dh) {
         const size_t o = base + (size_t)c2 * dh + j;
         if (a.dWg) a.dWg[o] = gk[i];
@@ -374,22 +388,48 @@ __global__ void fill_zero_f32_kernel(float* p, size_t n) {
 
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
-size_t tok_lds_bytes(const Problem& p) {
+size_t tok_lds_bytes(const Problem& p, int bc) {
   const size_t dh = p.dh;
-  return sizeof(float) * (2 * kTM * dh + 3 * kBC * (dh + 1) + 2 * kTM * (kBC + 1) +
+  return sizeof(float) * (2 * kTM * dh + 3 * bc * (dh + 1) + 2 * kTM * (bc + 1) +
                           2 * (size_t)kTM * p.E + kTM);
 }
-size_t wgt_lds_bytes(const Problem& p) {
+size_t wgt_lds_bytes(const Problem& p, int bc) {
   const size_t dh = p.dh;
-  return sizeof(float) * (2 * kTM * dh + 3 * kBC * (dh + 1) + 3 * kTM * (kBC + 1) + kTM);
+  return sizeof(float) * (2 * kTM * dh + 3 * bc * (dh + 1) + 3 * kTM * (bc + 1) + kTM);
+}
+size_t lds_bytes_for(const Problem& p, int bc) {
+  const size_t t = tok_lds_bytes(p, bc), w = wgt_lds_bytes(p, bc);
+  return t > w ? t : w;
+}
+// neurons per weight chunk: 32 where the tiles fit in LDS, else 16
+int chunk_neurons(const Problem& p) { return lds_bytes_for(p, 32) <= kLdsBytesPerWorkgroup ? 32 : 16; }
+
+template <int BC>
+int launch_kernels(const Problem& p, BwdF32Args a, bool weights, hipStream_t stream) {
+  static std::atomic<uint64_t> tok_allowed{0}, wgt_allowed{0};
+  if (hipError_t e0 = allow_lds_bytes(reinterpret_cast<const void*>(&bwd_f32_tok_kernel<BC>),
+                                      (int)kLdsBytesPerWorkgroup, tok_allowed); e0 != hipSuccess)
+    return (int)e0;
+  if (hipError_t e0 = allow_lds_bytes(reinterpret_cast<const void*>(&bwd_f32_wgt_kernel<BC>),
+                                      (int)kLdsBytesPerWorkgroup, wgt_allowed); e0 != hipSuccess)
+    return (int)e0;
+  a.chunks_per_sub = (p.de + BC - 1) / BC;
+  // token-major kernel (always: it also produces R for the weight-major kernel)
+  a.n_tiles = (p.N + kTM - 1) / kTM;
+  a.n_items = a.n_tiles * p.H;
+  hipLaunchKernelGGL(bwd_f32_tok_kernel<BC>, dim3((unsigned)xcd_grid_size(a.n_items)), dim3(kThreads),
+                     tok_lds_bytes(p, BC), stream, a);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess || !weights) return (int)e;
+  a.n_items = (int64_t)p.H * p.E * a.chunks_per_sub;
+  hipLaunchKernelGGL(bwd_f32_wgt_kernel<BC>, dim3((unsigned)xcd_grid_size(a.n_items)), dim3(kThreads),
+                     wgt_lds_bytes(p, BC), stream, a);
+  return (int)hipGetLastError();
 }
 
 }  // namespace
 
-size_t bwd_f32_lds_bytes(const Problem& p) {
-  const size_t t = tok_lds_bytes(p), w = wgt_lds_bytes(p);
-  return t > w ? t : w;
-}
+size_t bwd_f32_lds_bytes(const Problem& p) { return lds_bytes_for(p, chunk_neurons(p)); }
 
 size_t bwd_f32_workspace_bytes(const Problem& p) {
   if (p.N == 0) return 0;
@@ -429,29 +469,13 @@ int launch_bwd_f32(const Problem& p, const void* X, const void* Wg, const void* 
   a.DPws = reinterpret_cast<float*>(static_cast<unsigned char*>(ws) + nhe);
   a.N = p.N; a.ldx = p.ldx; a.ldy = p.ldy;
   a.H = p.H; a.dh = p.dh; a.E = p.E; a.de = p.de; a.route_mode = p.route_mode; a.eps = p.eps;
-  a.chunks_per_sub = (p.de + kBC - 1) / kBC;
+  a.chunks_per_sub = 0; a.n_tiles = 0; a.n_items = 0;
 
-  static std::atomic<uint64_t> tok_allowed{0}, wgt_allowed{0};
-  if (hipError_t e0 = allow_lds_bytes(reinterpret_cast<const void*>(&bwd_f32_tok_kernel),
-                                      (int)kLdsBytesPerWorkgroup, tok_allowed); e0 != hipSuccess)
-    return (int)e0;
-  if (hipError_t e0 = allow_lds_bytes(reinterpret_cast<const void*>(&bwd_f32_wgt_kernel),
-                                      (int)kLdsBytesPerWorkgroup, wgt_allowed); e0 != hipSuccess)
-    return (int)e0;
-  // token-major kernel (always: it also produces R for the weight-major kernel)
-  a.n_tiles = (p.N + kTM - 1) / kTM;
-  a.n_items = a.n_tiles * p.H;
-  hipLaunchKernelGGL(bwd_f32_tok_kernel, dim3((unsigned)xcd_grid_size(a.n_items)), dim3(kThreads),
-                     tok_lds_bytes(p), stream, a);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return (int)e;
-  if (dWg || dWu || dWd) {
-    a.n_items = (int64_t)p.H * p.E * a.chunks_per_sub;
-    hipLaunchKernelGGL(bwd_f32_wgt_kernel, dim3((unsigned)xcd_grid_size(a.n_items)), dim3(kThreads),
-                       wgt_lds_bytes(p), stream, a);
-    e = hipGetLastError();
-    if (e != hipSuccess) return (int)e;
-  }
+  const bool weights = dWg || dWu || dWd;
+  const int rc = chunk_neurons(p) == 32 ? launch_kernels<32>(p, a, weights, stream)
+                                        : launch_kernels<16>(p, a, weights, stream);
+  if (rc != 0) return rc;
+  hipError_t e = hipSuccess;
   if (d_route && p.route_mode == 0) {
     const int64_t total = (int64_t)p.H * p.dh * p.E;
     hipLaunchKernelGGL(bwd_f32_route_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0,

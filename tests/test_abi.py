@@ -130,7 +130,7 @@ def test_backward_rejects_bad_arguments():
     # fp32 backward: supported shapes pass validation up to the workspace check, others do not
     assert lib.mhffn_backward(ctypes.byref(desc(dtype=mhffn.F32)), *args, None, 0, None) == 5
     assert lib.mhffn_backward(ctypes.byref(desc(dtype=mhffn.F32, d_head=512)), *args, FAKE, 1 << 30, None) == 3
-    assert lib.mhffn_backward(ctypes.byref(desc(dtype=mhffn.F32, d_head=256, n_sub=96)), *args, FAKE, 1 << 30, None) == 3
+    assert lib.mhffn_backward(ctypes.byref(desc(dtype=mhffn.F32, d_head=256, n_sub=200)), *args, FAKE, 1 << 30, None) == 3
     bad = list(args)
     bad[5] = None                                                               # dY missing
     assert lib.mhffn_backward(ctypes.byref(d), *bad, FAKE, 1 << 30, None) == 1

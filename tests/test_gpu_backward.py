@@ -79,12 +79,12 @@ def test_f32_ragged_and_generic_shapes(N):
     check_all(got, ref, TOL["f32"])
 
 
-@pytest.mark.parametrize("dh,E,de", [(64, 6, 192), (256, 3, 704)])
+@pytest.mark.parametrize("dh,E,de", [(64, 6, 192), (256, 3, 704), (248, 5, 40), (232, 2, 96)])
 def test_f32_other_head_widths(dh, E, de):
     """The paper's head-width variants (d_h = 64, 256 with d_e = 8/3 d_h rounded up to a
-    multiple of 64) through the shape-generic fp32 kernels.  The forward takes both; the
-    fp32 backward keeps whole d_h-wide tiles in LDS and takes d_h up to 128, beyond which it
-    has to refuse rather than compute."""
+    multiple of 64) and two odd widths through the shape-generic fp32 kernels.  The fp32
+    backward keeps whole d_h-wide tiles in LDS: weight chunks of 32 neurons up to d_h = 232,
+    of 16 beyond (d_h = 248, 256 here), with a ragged last chunk (d_e = 40)."""
     import torch
     w = inputs.Workload("f32_head_width", 150, 2, dh, E, de, "f32", w_std=0.05, route_scale=2.0,
                         backward=True)
@@ -94,14 +94,18 @@ def test_f32_other_head_widths(dh, E, de):
     torch.cuda.synchronize()
     ref_y = orc.forward(d["X"], d["W_gate"], d["W_up"], d["W_down"], d["W_r"], w.eps)
     assert relerr(to_host(Y), ref_y) <= TOL["f32"]
-    if dh > 128:
-        with pytest.raises(mhffn.MhffnError) as err:
-            run_backward(w, seed=dh)
-        assert err.value.status == 3   # MHFFN_ERR_UNSUPPORTED
-        return
     _, got = run_backward(w, seed=dh)
     ref = orc.backward(d["X"], d["W_gate"], d["W_up"], d["W_down"], d["W_r"], d["dY"], w.eps)
     check_all(got, ref, TOL["f32"])
+
+
+def test_f32_backward_refuses_what_does_not_fit_in_lds():
+    """d_h = 256 with 200 sub-networks: the token tile, a 16-neuron weight chunk and the
+    per-token gating rows exceed 160 KB of LDS; the call has to refuse rather than compute."""
+    w = inputs.Workload("f32_too_wide", 40, 1, 256, 200, 16, "f32", backward=True)
+    with pytest.raises(mhffn.MhffnError) as err:
+        run_backward(w, seed=1)
+    assert err.value.status == 3   # MHFFN_ERR_UNSUPPORTED
 
 
 def test_f32_weights_mode_returns_dr():
