@@ -76,10 +76,26 @@ struct BwdArgs {
 // token-major kernel: dX, R, dp
 // ---------------------------------------------------------------------------
 constexpr int tok_stage_bytes(int dh) { return 3 * 32 * dh * 2; }  // K, U, V tiles of 32 rows
-constexpr int kTokStages = 2;
+// Weight tiles reach LDS either through registers (two stages: loaded at the top of a step,
+// stored at its end) or, DMA = true (d_h = 128, 512 threads: one 16-byte chunk of each tile
+// per thread), by direct global -> LDS loads into three stages, requested two steps ahead:
+// no staging registers, no LDS stores, and the step ends on a counted wait and a bare barrier.
+constexpr int tok_stages(bool dma) { return dma ? 3 : 2; }
 
-template <int DH, int TB, int NW>
+// PHASED (with DMA): the two waves of a SIMD run half a step apart.  A step is two halves,
+// the gate/up/dA products (MFMA only) and the activation arithmetic plus the dX products
+// (VALU, then MFMA), each closed by a barrier; waves NW/2 .. NW-1 pass one barrier more before
+// the loop and the others one more after it, so that a SIMD always has one wave in each half
+// and the arithmetic of one hides behind the products of the other.  Same code for both, no
+// extra registers.  A tile is then read during three consecutive half-steps; its stage is
+// requested again at the start of the fourth (the late waves are then at the top of a step,
+// the early ones in its middle), and every wave waits for its own requests at the end of the
+// half-step in which it made them, two half-steps before the first use.
+template <int DH, int TB, int NW, bool DMA = false, bool PHASED = false>
 __global__ __launch_bounds__(64 * NW) void bwd_tok_kernel(BwdArgs a) {
+  static_assert(!DMA || (DH == 128 && TB == 1 && NW == 8), "direct staging: 32 rows x 16 chunks = 512 lanes");
+  static_assert(DMA || !PHASED, "the half-step schedule relies on direct staging");
+  constexpr int kTokStages = tok_stages(DMA);
   constexpr int BM = 32 * TB * NW;
   constexpr int THREADS = 64 * NW;
   constexpr int KS = DH / 16;              // contraction steps over the head width
@@ -92,7 +108,7 @@ __global__ __launch_bounds__(64 * NW) void bwd_tok_kernel(BwdArgs a) {
   constexpr bool kAllLoad = (CHUNKS % THREADS == 0);   // else the upper threads carry none
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   unsigned char* stage_base = smem;
-  float* DRs = reinterpret_cast<float*>(smem + kTokStages * kTokStageBytes);  // [E][BM]
+  float* DRs = reinterpret_cast<float*>(smem + kTokStages * kTokStageBytes);  // [E][BM]: r_e, then dr_e
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r = lane & 31, g = lane >> 5;
@@ -105,6 +121,29 @@ __global__ __launch_bounds__(64 * NW) void bwd_tok_kernel(BwdArgs a) {
   const int64_t N = a.N;
   float* Rh = a.Rws + (size_t)h * E * N;
   float* DPh = a.DPws + (size_t)h * E * N;
+
+  const int tiles_per_sub = a.de / 32;
+  const int T = E * tiles_per_sub;
+  const size_t head_off = (size_t)h * E * a.de * DH;
+  const uint16_t* Kh = a.Wg + head_off;
+  const uint16_t* Uh = a.Wu + head_off;
+  const uint16_t* Vh = a.Wd + head_off;
+  // direct staging: wave w moves rows 4w .. 4w+3 of a tile; lane l lands at chunk position
+  // l % 16 of row 4w + l / 16 and fetches the global chunk that the swizzle maps there
+  const int drow = 4 * wave + (lane >> 4);
+  const int dma_goff = drow * DH + (((lane & 15) ^ swz(drow)) << 3);   // elements
+  const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+  auto dma = [&](int t, int stage) {
+    const size_t off = (size_t)t * (32 * DH) + dma_goff;
+    unsigned char* dst = stage_base + stage * kTokStageBytes + wave_u * 1024;
+    global_to_lds_16B(Kh + off, dst);
+    global_to_lds_16B(Uh + off, dst + kTileBytes);
+    global_to_lds_16B(Vh + off, dst + 2 * kTileBytes);
+  };
+  // the gating prologue stages W_r^T (up to 24 KB) in one stage: the last one, so that the
+  // first two tiles can be on their way meanwhile (the epilogue, with all stages retired,
+  // starts from the first)
+  unsigned char* scratch = stage_base + (DMA ? 2 * kTokStageBytes : 0);
 
   bf16x8 q[TB][KS], dy[TB][KS];
   int64_t tok[TB];
@@ -125,6 +164,10 @@ __global__ __launch_bounds__(64 * NW) void bwd_tok_kernel(BwdArgs a) {
       dy[tb][ks] = vy;
     }
   }
+  if constexpr (DMA) {
+    dma(0, 0);
+    if (T > 1) dma(1, 1);
+  }
 
   // ---- gating weights -> workspace R[h][e][tok] ----------------------------
   float inv[TB];  // 1 / (Z + eps)
@@ -136,11 +179,11 @@ __global__ __launch_bounds__(64 * NW) void bwd_tok_kernel(BwdArgs a) {
     const uint16_t* Wr = reinterpret_cast<const uint16_t*>(a.route) + (size_t)h * DH * E;
     for (int idx = tid; idx < DH * E; idx += THREADS) {
       const int j = idx / E, e = idx - j * E;
-      *reinterpret_cast<uint16_t*>(stage_base + tile_off_dh<DH>(e, j >> 3) + (j & 7) * 2) = Wr[idx];
+      *reinterpret_cast<uint16_t*>(scratch + tile_off_dh<DH>(e, j >> 3) + (j & 7) * 2) = Wr[idx];
     }
     for (int idx = tid; idx < (32 * EB - E) * DH; idx += THREADS) {
       const int e = E + idx / DH, j = idx % DH;
-      *reinterpret_cast<uint16_t*>(stage_base + tile_off_dh<DH>(e, j >> 3) + (j & 7) * 2) = 0;
+      *reinterpret_cast<uint16_t*>(scratch + tile_off_dh<DH>(e, j >> 3) + (j & 7) * 2) = 0;
     }
     __syncthreads();
     float zsum[TB];
@@ -153,7 +196,7 @@ __global__ __launch_bounds__(64 * NW) void bwd_tok_kernel(BwdArgs a) {
           f32x16 acc = {0};
 #pragma unroll
           for (int ks = 0; ks < KS; ++ks) {
-            const bf16x8 af = *reinterpret_cast<const bf16x8*>(stage_base + tile_off_dh<DH>(32 * eb + r, 2 * ks + g));
+            const bf16x8 af = *reinterpret_cast<const bf16x8*>(scratch + tile_off_dh<DH>(32 * eb + r, 2 * ks + g));
             acc = mfma32(af, q[tb][ks], acc);
           }
 #pragma unroll
@@ -162,8 +205,10 @@ __global__ __launch_bounds__(64 * NW) void bwd_tok_kernel(BwdArgs a) {
             const float s = (e < E) ? sigmoid_fast(acc[v]) : 0.f;
             if (pass == 0) {
               zsum[tb] += s;
-            } else if (e < E && valid[tb]) {
-              Rh[(size_t)e * N + tok[tb]] = s * inv[tb];
+            } else if (e < E) {
+              const float rv = s * inv[tb];
+              if (valid[tb]) Rh[(size_t)e * N + tok[tb]] = rv;
+              DRs[e * BM + wtok + 32 * tb + r] = rv;   // until sub-network e has been swept
             }
           }
         }
@@ -181,21 +226,16 @@ __global__ __launch_bounds__(64 * NW) void bwd_tok_kernel(BwdArgs a) {
     for (int idx = tid; idx < BM * E; idx += THREADS) {
       const int tl = idx / E, e = idx - tl * E;
       const int64_t t = tile_tok0 + tl;
-      if (t < N) Rh[(size_t)e * N + t] = R[((size_t)t * a.H + h) * E + e];
+      const float rv = (t < N) ? R[((size_t)t * a.H + h) * E + e] : 0.f;
+      if (t < N) Rh[(size_t)e * N + t] = rv;
+      DRs[e * BM + tl] = rv;
     }
   }
-  __threadfence();   // R written above is read back (by this workgroup) below
-  __syncthreads();
+  __threadfence();   // R written above is read back (by this workgroup) in the epilogue
+  __syncthreads();   // (waits for every load in flight: direct staging has tiles 0 and 1 in place)
 
   // ---- main loop -------------------------------------------------------------
-  const int tiles_per_sub = a.de / 32;
-  const int T = E * tiles_per_sub;
-  const size_t head_off = (size_t)h * E * a.de * DH;
-  const uint16_t* Kh = a.Wg + head_off;
-  const uint16_t* Uh = a.Wu + head_off;
-  const uint16_t* Vh = a.Wd + head_off;
-
-  u32x4 kreg[CH], ureg[CH], vreg[CH];
+  u32x4 kreg[DMA ? 1 : CH], ureg[DMA ? 1 : CH], vreg[DMA ? 1 : CH];
   auto gload = [&](int t) {
 #pragma unroll
     for (int i = 0; i < CH; ++i) {
@@ -226,33 +266,54 @@ __global__ __launch_bounds__(64 * NW) void bwd_tok_kernel(BwdArgs a) {
 #pragma unroll
     for (int jb = 0; jb < JB; ++jb) dXa[tb][jb] = f32x16{0};
 
-  float rw[TB], rw_next[TB], drp[TB];
+  float rw[TB], drp[TB];
 #pragma unroll
   for (int tb = 0; tb < TB; ++tb) {
-    rw_next[tb] = valid[tb] ? Rh[tok[tb]] : 0.f;
     rw[tb] = 0.f;
     drp[tb] = 0.f;
   }
-  gload(0);
-  lstore(0);
-  __syncthreads();
+  if constexpr (!DMA) {
+    gload(0);
+    lstore(0);
+    __syncthreads();
+  }
+  int stage = 0;   // t % kTokStages
+  const bool late = PHASED && wave_u >= NW / 2;   // the second wave of each SIMD
+  auto bare_barrier = [&]() {
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+  };
+  // wait for the tiles requested before the newest request (all, if none was made), and for
+  // this wave's LDS traffic
+  auto wait_tiles = [&](bool requested) {
+    asm volatile("" ::: "memory");
+    if (requested) __builtin_amdgcn_s_waitcnt(0x0073);  // vmcnt(3) lgkmcnt(0)
+    else __builtin_amdgcn_s_waitcnt(0x0070);            // vmcnt(0) lgkmcnt(0)
+  };
+  if (late) bare_barrier();
   for (int t = 0; t < T; ++t) {
     const bool more = (t + 1 < T);
-    if (more) gload(t + 1);
+    const bool ahead = DMA && (t + 2 < T);
     const int e = t / tiles_per_sub;
+    // The gating weight of sub-network e waits in LDS, in the slot that takes dr_e once the
+    // sub-network has been swept (a load from the workspace here would have to stay in flight
+    // across the loop's back edge, where the compiler waits for every load, tile requests
+    // included).
     if (t % tiles_per_sub == 0) {
 #pragma unroll
-      for (int tb = 0; tb < TB; ++tb) {
-        rw[tb] = rw_next[tb];
-        rw_next[tb] = (e + 1 < E && valid[tb]) ? Rh[(size_t)(e + 1) * N + tok[tb]] : 0.f;
-      }
+      for (int tb = 0; tb < TB; ++tb) rw[tb] = DRs[e * BM + wtok + 32 * tb + r];
     }
-    const unsigned char* st = stage_base + (t & 1) * kTokStageBytes;
+    if constexpr (DMA) {
+      // the stage that step t-1 retired (for the late waves; the early ones wait half a step)
+      if (ahead && (!PHASED || late)) dma(t + 2, stage == 0 ? 2 : stage - 1);
+    } else {
+      if (more) gload(t + 1);
+    }
+    const unsigned char* st = stage_base + stage * kTokStageBytes;
 
     __builtin_amdgcn_s_setprio(1);
-    f32x16 accM[TB], accN[TB], accA[TB];
-#pragma unroll
-    for (int tb = 0; tb < TB; ++tb) { accM[tb] = f32x16{0}; accN[tb] = f32x16{0}; accA[tb] = f32x16{0}; }
+    f32x16 accM[TB], accN[TB], accA[TB];   // started by their first product (C operand 0)
     // K/U/V row operands, item c = 3 ks + {0: K, 1: U, 2: V}: each is read six items (two
     // contraction steps) ahead of its use, with counted waits.  Left to the compiler, each
     // step's three reads are issued and waited for back to back, and every step pays the
@@ -272,11 +333,17 @@ __global__ __launch_bounds__(64 * NW) void bwd_tok_kernel(BwdArgs a) {
         lds_wait<(NOP - 1 - c) < 6 ? (NOP - 1 - c) : 6>(op[c]);
 #pragma unroll
         for (int tb = 0; tb < TB; ++tb) {
-          if constexpr (which == 0) accM[tb] = mfma32(op[c], q[tb][ks], accM[tb]);
-          if constexpr (which == 1) accN[tb] = mfma32(op[c], q[tb][ks], accN[tb]);
-          if constexpr (which == 2) accA[tb] = mfma32(op[c], dy[tb][ks], accA[tb]);
+          if constexpr (which == 0) accM[tb] = mfma32(op[c], q[tb][ks], ks == 0 ? f32x16{0} : accM[tb]);
+          if constexpr (which == 1) accN[tb] = mfma32(op[c], q[tb][ks], ks == 0 ? f32x16{0} : accN[tb]);
+          if constexpr (which == 2) accA[tb] = mfma32(op[c], dy[tb][ks], ks == 0 ? f32x16{0} : accA[tb]);
         }
       });
+    }
+    if constexpr (PHASED) {
+      if (late) wait_tiles(ahead);
+      else __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0): this half's operand reads
+      bare_barrier();
+      if (ahead && !late) dma(t + 2, stage == 0 ? 2 : stage - 1);
     }
     bf16x8 dmf[TB][2], dnf[TB][2];
 #pragma unroll
@@ -339,9 +406,24 @@ __global__ __launch_bounds__(64 * NW) void bwd_tok_kernel(BwdArgs a) {
         drp[tb] = 0.f;
       }
     }
-    if (more) lstore((t + 1) & 1);
-    __syncthreads();
+    stage = (stage + 1 == kTokStages) ? 0 : stage + 1;
+    if constexpr (DMA) {
+      // Publish tile t+1 (requested one step ago; the three loads issued in this step may stay
+      // in flight) and retire this step's stage.  A bare barrier: __syncthreads() would wait
+      // for every load in flight.
+      if (PHASED && late) {
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0)
+      } else {
+        wait_tiles(ahead);
+      }
+      bare_barrier();
+    } else {
+      if (more) lstore(stage);
+      __syncthreads();
+    }
   }
+  if (PHASED && !late) bare_barrier();
 
   // ---- derivative through the gating weights ------------------------------------
   if (a.route_mode == 0) {
@@ -1159,16 +1241,27 @@ hipError_t allow_full_lds(K kernel, std::atomic<uint64_t>& done) {
 
 constexpr int tok_block_tokens(int dh) { return dh == 128 ? 256 : 128; }
 
-template <int DH, int TB, int NW>
+// LDS of the token-major kernel: the weight stages and dr_e of every token of the block
+size_t tok_lds_bytes(const Problem& p, bool dma) {
+  return (size_t)tok_stages(dma) * tok_stage_bytes(p.dh) +
+         (size_t)p.E * tok_block_tokens(p.dh) * sizeof(float);
+}
+// direct staging (three stages) where it fits: d_h = 128 with up to 88 sub-networks
+bool tok_direct_staging(const Problem& p) {
+  return p.dh == 128 && tok_lds_bytes(p, true) <= kLdsBytesPerWorkgroup;
+}
+
+template <int DH, int TB, int NW, bool DMA = false, bool PHASED = false>
 int launch_tok(const Problem& p, BwdArgs a, hipStream_t stream) {
   constexpr int BM = 32 * TB * NW;
   static_assert(BM == tok_block_tokens(DH), "bwd_bf16_lds_bytes assumes this block size");
   a.n_tiles = (p.N + BM - 1) / BM;
   a.n_items = a.n_tiles * p.H;
-  const size_t lds = (size_t)kTokStages * tok_stage_bytes(DH) + (size_t)p.E * BM * sizeof(float);
+  const size_t lds = tok_lds_bytes(p, DMA);
   static std::atomic<uint64_t> lds_allowed{0};
-  if (hipError_t e = allow_full_lds(&bwd_tok_kernel<DH, TB, NW>, lds_allowed); e != hipSuccess) return (int)e;
-  hipLaunchKernelGGL((bwd_tok_kernel<DH, TB, NW>), dim3((unsigned)xcd_grid_size(a.n_items)),
+  if (hipError_t e = allow_full_lds(&bwd_tok_kernel<DH, TB, NW, DMA, PHASED>, lds_allowed); e != hipSuccess)
+    return (int)e;
+  hipLaunchKernelGGL((bwd_tok_kernel<DH, TB, NW, DMA, PHASED>), dim3((unsigned)xcd_grid_size(a.n_items)),
                      dim3(64 * NW), lds, stream, a);
   return (int)hipGetLastError();
 }
@@ -1240,10 +1333,7 @@ int launch_fill_zero(void* p, size_t bytes, void* stream) {
 // d_h = 256: the routing-gradient kernel keeps 8 accumulator tiles per 32 sub-networks
 int bwd_bf16_max_sub(const Problem& p) { return p.dh == 256 ? 64 : kRouteMaxSub; }
 
-size_t bwd_bf16_lds_bytes(const Problem& p) {
-  return (size_t)kTokStages * tok_stage_bytes(p.dh) +
-         (size_t)p.E * tok_block_tokens(p.dh) * sizeof(float);
-}
+size_t bwd_bf16_lds_bytes(const Problem& p) { return tok_lds_bytes(p, tok_direct_staging(p)); }
 
 size_t bwd_workspace_bytes(const Problem& p, int dtype) {
   if (dtype != 1) return bwd_f32_workspace_bytes(p);
@@ -1314,6 +1404,7 @@ int launch_bwd(const Problem& p, int dtype, const void* X, const void* Wg, const
   // their steps (measured 4 % and 11 % faster than one workgroup of 8 waves)
   if (p.dh == 64) rc = launch_tok<64, 1, 4>(p, a, stream);
   else if (p.dh == 256) rc = launch_tok<256, 1, 4>(p, a, stream);   // needs one wave per SIMD: see the kernel
+  else if (tok_direct_staging(p)) rc = launch_tok<kDh, 1, 8, true, true>(p, a, stream);
   else rc = launch_tok<kDh, 1, 8>(p, a, stream);
   if (rc) return rc;
   if (mark(1) != hipSuccess) return (int)hipErrorInvalidHandle;
