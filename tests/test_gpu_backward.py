@@ -45,7 +45,11 @@ def check_all(got, ref, tol, single_subnetwork=False):
                                        (700, 1, 7, 160),
                                        # many sub-networks (three 32-wide blocks of gating logits),
                                        # token counts that leave the last 32-token block ragged
-                                       (300, 1, 80, 32), (97, 2, 96, 32)])
+                                       (300, 1, 80, 32), (97, 2, 96, 32),
+                                       # two and three tiles per head (the staging ring's start and
+                                       # tail), and both sides of the largest E that the directly
+                                       # staged token-major kernel holds in LDS
+                                       (40, 1, 2, 32), (40, 2, 1, 96), (70, 1, 88, 32), (70, 1, 89, 32)])
 def test_bf16_small_shapes_params_mode(N, H, E, de):
     w = small_workload("bwd_small", N, H, E, de, "bf16", backward=True)
     d, got = run_backward(w, seed=N + E)
