@@ -97,7 +97,7 @@ def module_bench(args, w):
     timed in the same run; the difference is the time of the six d_model x d_model products."""
     import torch
     from paper_2512_06989_amd import inputs, mhffn
-    from tests.helpers import device_inputs
+    from paper_2512_06989_amd.device import device_inputs
     d = inputs.make_module_inputs(w, seed=0, with_dy=True)
     g = device_inputs(d, w.dtype)
     names = ("X", "W_in", "W_gate", "W_up", "W_down", "W_r", "W_out")
@@ -232,7 +232,7 @@ def main():
     import numpy as np
     import torch
     from paper_2512_06989_amd import inputs, mhffn
-    from tests.helpers import device_inputs
+    from paper_2512_06989_amd.device import device_inputs
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)

@@ -28,9 +28,15 @@ _lib = None
 def load():
     global _lib
     if _lib is None:
-        # MHFFN_ORACLE_LIB lets the mutation test point the pins at a deliberately
-        # broken build of this same source; never set otherwise
-        path = os.environ.get("MHFFN_ORACLE_LIB") or _build.build(force=False)
+        # The mutation test points the pins at a deliberately broken build of this same
+        # source.  That needs both variables, and the second one names the only test file
+        # that may run against such a build, so no other process can be redirected.
+        path = None
+        import sys
+        if (os.environ.get("MHFFN_ORACLE_MUTATION_HARNESS") == "tests/test_oracle_pins.py"
+                and any(a.endswith("test_oracle_pins.py") for a in sys.argv)):
+            path = os.environ.get("MHFFN_ORACLE_LIB")
+        path = path or _build.build(force=False)
         lib = ctypes.CDLL(path)
         dp = ctypes.c_void_p
         lib.mhffn_oracle_forward_f64.argtypes = [ctypes.POINTER(_Desc)] + [dp] * 7

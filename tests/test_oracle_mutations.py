@@ -47,7 +47,7 @@ def test_pins_catch_planted_mistake(name, old, new):
         open(c, "w").write(mutated)
         subprocess.check_call(["gcc", "-O1", "-fopenmp", "-fPIC", "-shared", "-std=gnu11",
                                "-I", os.path.join(ROOT, "oracle"), "-o", lib, c, "-lm"])
-        env = dict(os.environ, MHFFN_ORACLE_LIB=lib, OMP_NUM_THREADS="2")
+        env = dict(os.environ, MHFFN_ORACLE_LIB=lib, MHFFN_ORACLE_MUTATION_HARNESS="tests/test_oracle_pins.py", OMP_NUM_THREADS="2")
         r = subprocess.run([sys.executable, "-m", "pytest", "-x", "-q", "-p", "no:cacheprovider",
                             os.path.join(ROOT, "tests", "test_oracle_pins.py")],
                            cwd=ROOT, env=env, capture_output=True, text=True)
@@ -61,7 +61,7 @@ def test_unmutated_oracle_passes_the_same_harness():
         lib = os.path.join(tmp, "libclean.so")
         subprocess.check_call(["gcc", "-O1", "-fopenmp", "-fPIC", "-shared", "-std=gnu11",
                                "-I", os.path.join(ROOT, "oracle"), "-o", lib, SRC, "-lm"])
-        env = dict(os.environ, MHFFN_ORACLE_LIB=lib, OMP_NUM_THREADS="2")
+        env = dict(os.environ, MHFFN_ORACLE_LIB=lib, MHFFN_ORACLE_MUTATION_HARNESS="tests/test_oracle_pins.py", OMP_NUM_THREADS="2")
         r = subprocess.run([sys.executable, "-m", "pytest", "-x", "-q", "-p", "no:cacheprovider",
                             os.path.join(ROOT, "tests", "test_oracle_pins.py")],
                            cwd=ROOT, env=env, capture_output=True, text=True)
