@@ -312,7 +312,7 @@ def main():
     # up to 64 sub-networks the forward runs the pipelined kernel
     # (d_h = 128; the other head widths run the plainer kernels)
     fwd_pipelined = w.d_head == 128 and w.n_sub <= 64
-    kernel_names = {"fwd": "fwd_bf16_pipe_kernel" if fwd_pipelined else "fwd_bf16_kernel",
+    kernel_names = {"fwd": "fwd_bf16_flow_kernel" if fwd_pipelined else "fwd_bf16_kernel",
                     "bwd_tok": "bwd_tok_kernel",
                     "bwd_wgt": "bwd_wgt16_kernel" if w.d_head == 128 else "bwd_wgt_dh_kernel",
                     "bwd_route": "bwd_route_*"}

@@ -193,7 +193,10 @@ int mhffn_module_forward(const mhffn_desc* desc, const void* X, const void* W_in
  *     mhffn_backward(Q, dS);  dW_in = X^T dQ;  dX = dQ W_in^T.
  * Any gradient pointer may be NULL => not computed.  dS and dQ pass through the
  * workspace (MHFFN_OP_MODULE_BACKWARD: two [n_tokens][d_model] buffers plus the
- * fused backward's own scratch).  Shape support is that of mhffn_backward. */
+ * fused backward's own scratch): it begins with dS, then dQ, each dense
+ * [n_tokens][d_model] in desc.dtype and rounded up to a multiple of 256 bytes; both
+ * hold their values when the call has finished (dQ only if dX or dW_in was asked
+ * for).  Shape support is that of mhffn_backward. */
 int mhffn_module_backward(const mhffn_desc* desc, const void* X, const void* W_in,
                           const void* W_gate, const void* W_up, const void* W_down,
                           const void* W_r, const void* W_out, const void* Q, const void* S,

@@ -342,23 +342,33 @@ __global__ __launch_bounds__(64 * NW) void fwd_bf16_kernel(FwdArgs a) {
 }
 
 // ---------------------------------------------------------------------------
-// Pipelined variant for the unsplit path (256 tokens per workgroup, 8 waves).
-//
-// Same arithmetic and tiling as fwd_bf16_kernel; what differs is how a wave's
-// instruction stream is laid out, because that, not the MFMA rate, bounds the
-// kernel:
-//   * weight tiles go global -> LDS directly (one 1 KB image of four swizzled
-//     rows per wave-wide load): staging costs no registers, no LDS-store
-//     instructions and no wait inside the step.  Four stages are in rotation and
-//     a tile is requested three steps before its down projection, two steps
-//     before its gate/up products;
-//   * the gate/up products of tile i+1 are issued interleaved with the
-//     activation arithmetic of tile i (two accumulator sets in alternation), so
-//     a wave keeps both the MFMA pipe and the VALU busy on its own;
-//   * the loop is unrolled over stage x accumulator set (4 bodies), which makes
-//     every LDS operand address an immediate offset from a loop-invariant
-//     per-lane register.
-// One barrier per tile: it publishes tile i+2 and retires the stage of tile i.
+// Pipelined kernel for up to 64 sub-networks at d_h = 128 (256 tokens per workgroup, 8 waves
+// of 32 tokens, two waves per SIMD).  Same arithmetic and tiling as fwd_bf16_kernel; what
+// differs is how a wave's instruction stream is laid out, because that, not the MFMA rate,
+// bounds the kernel:
+//   * weight tiles go global -> LDS directly (one 1 KB image of four swizzled rows per
+//     wave-wide load) into three rings of four stages (K | U | V): staging costs no
+//     registers, no LDS-store instructions and no wait inside the step;
+//   * the issue port that MFMA and VALU instructions share is the scarce resource: a
+//     32x32x16 product holds it for about 20 of its 32 cycles, a plain VALU instruction for
+//     about 3, a transcendental one for about 8, and one wave issues at most one
+//     instruction every 5 cycles.  Four to five VALU instructions behind every product are
+//     therefore almost free, while a run of products with nothing between them, or a run of
+//     arithmetic with few products, leaves one of the two pipes idle.  So a step works on
+//     three tiles at once:
+//         gate/up products of tile i+1 | activation of tile i | down projection of tile i-1
+//     in 12 slots of two products and eight to nine VALU instructions each (slot pattern:
+//     gate+up, gate+up, down+down).  The activation of an element pair runs in three stages
+//     (A: 2^(-m log2 e) and m*n;  B: rcp((1+t)/r);  C: product and rounding) that sit one to
+//     two slots apart, the last ones of a tile in the first slots of the next step;
+//   * LDS operands are read two slots ahead into three rotating register sets, untracked,
+//     with counted waits, and the stream of reads runs across the step boundary: a K/U tile
+//     is published by the barrier two steps before its products (requested four steps
+//     ahead), a V tile one step before its down projection (requested two steps ahead);
+//   * the loop is unrolled over stage x accumulator set (4 bodies), which makes every LDS
+//     operand address an immediate offset from a loop-invariant per-lane register.
+// One barrier per step: it publishes the tiles requested one step ago and retires the K/U
+// stage of tile i+1 and the V stage of tile i-1.
 // ---------------------------------------------------------------------------
 constexpr int kPipeStages = 4;
 constexpr int kPipeTile = kBI * kDh * 2;            // 8 KB, rows of 256 B, chunks swizzled
@@ -368,8 +378,12 @@ constexpr int kPipeBM = 32 * kPipeWaves;
 constexpr int kPipeMaxSub = (kLdsBytesPerWorkgroup - 3 * kPipeRing) / (kPipeBM * 4);
 constexpr int kPipeMaxSubStatic = 64;   // = kPipeMaxSub, as a literal for array bounds
 static_assert(kPipeMaxSub == kPipeMaxSubStatic, "gating code is written for up to two blocks of 32");
+template <int N, typename T0, typename T1, typename T2, typename T3>
+__device__ __forceinline__ void lds_wait4(T0& a, T1& b, T2& c, T3& d) {
+  asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(a), "+v"(b), "+v"(c), "+v"(d) : "n"(N));
+}
 
-__global__ __launch_bounds__(64 * kPipeWaves) void fwd_bf16_pipe_kernel(FwdArgs a) {
+__global__ __launch_bounds__(64 * kPipeWaves) void fwd_bf16_flow_kernel(FwdArgs a) {
   constexpr int BM = kPipeBM;
   constexpr int THREADS = 64 * kPipeWaves;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -379,42 +393,31 @@ __global__ __launch_bounds__(64 * kPipeWaves) void fwd_bf16_pipe_kernel(FwdArgs 
   const int r = lane & 31, g = lane >> 5;
   const int64_t item = xcd_work_item(blockIdx.x, a.n_items);
   if (item >= a.n_items) return;  // whole workgroup leaves together
-  // item = (head * n_tiles + token tile) * n_split + split, as in fwd_bf16_kernel
   const int split = (int)(item % a.n_split);
   const int64_t ht = item / a.n_split;
   const int h = (int)(ht / a.n_tiles);
   const int64_t tile_tok0 = (ht % a.n_tiles) * BM;
   const int wtok = wave * 32;
   const int E = a.E;
-  // a wave whose 32 tokens all lie past N only helps with staging and barriers
   const bool active = tile_tok0 + wtok < a.N;
 
   const int tiles_per_sub = a.de / kBI;
-  const int t_begin = split * a.tiles_per_split;   // this workgroup's share of the tiles
+  const int t_begin = split * a.tiles_per_split;
   const int T = min(E * tiles_per_sub, t_begin + a.tiles_per_split) - t_begin;
   const size_t head_off = ((size_t)h * E * a.de + (size_t)t_begin * kBI) * kDh;
   const uint16_t* Kh = a.Wg + head_off;
   const uint16_t* Uh = a.Wu + head_off;
   const uint16_t* Vh = a.Wd + head_off;
 
-  // ---- direct global -> LDS staging: wave w moves rows 4w..4w+3 of each tile ----
-  // lane l lands at LDS chunk position l%16 of row 4w + l/16, so it fetches the
-  // global chunk that the swizzle maps there.
+  // direct global -> LDS staging: wave w moves rows 4w..4w+3 of each tile (lane l lands at LDS chunk position l%16 of row 4w + l/16, so it fetches the global chunk that the swizzle maps there)
   const int drow = 4 * wave + (lane >> 4);
-  const int dma_goff = drow * kDh + (((lane & 15) ^ swz(drow)) << 3);  // elements
+  const unsigned dma_goff = (unsigned)(drow * kDh + (((lane & 15) ^ swz(drow)) << 3));  // elements
   const int wave_u = __builtin_amdgcn_readfirstlane(wave);
-  auto dma = [&](int t, int stage) {
-    const size_t off = (size_t)t * (kBI * kDh) + dma_goff;
-    unsigned char* dst = smem + stage * kPipeTile + wave_u * 1024;
-    global_to_lds_16B(Kh + off, dst);
-    global_to_lds_16B(Uh + off, dst + kPipeRing);
-    global_to_lds_16B(Vh + off, dst + 2 * kPipeRing);
+  auto dma1 = [&](const uint16_t* base, int t, int ring, int stage) {
+    global_to_lds_16B(base + (size_t)t * (kBI * kDh) + dma_goff,
+                      smem + ring * kPipeRing + stage * kPipeTile + wave_u * 1024);
   };
-  // Order of the first requests: the token rows and W_r first, the weight tiles after them.
-  // Loads return in order, so the gating arithmetic below waits only for the two small ones
-  // and runs while the first tiles are still on their way (with few tokens the kernel is
-  // little more than this prologue: the first tiles take about 5 us to arrive).
-  // ---- q fragments (B operands), resident for the whole kernel -------------
+
   bf16x8 q[8];
   {
     const int64_t tok = tile_tok0 + wtok + r;
@@ -427,6 +430,15 @@ __global__ __launch_bounds__(64 * kPipeWaves) void fwd_bf16_pipe_kernel(FwdArgs 
       q[ks] = v;
     }
   }
+  // first requests: K/U tiles 0..2 and V tiles 0, 1 (stage 3 of every ring is the scratch of
+  // the gating phase; K/U tile 3 follows it)
+  auto first_requests = [&]() {
+#pragma unroll
+    for (int t = 0; t < 3; ++t)
+      if (t < T) { dma1(Kh, t, 0, t); dma1(Uh, t, 1, t); }
+    dma1(Vh, 0, 2, 0);
+    if (T > 1) dma1(Vh, 1, 2, 1);
+  };
 
   // ---- gating weights 1/R[e][token] into LDS; scratch: stage 3 of all rings ----
   // (a [96][128] bf16 image needs 24 KB: rows 0-31 in the K ring, 32-63 U, 64-95 V)
@@ -434,9 +446,6 @@ __global__ __launch_bounds__(64 * kPipeWaves) void fwd_bf16_pipe_kernel(FwdArgs 
     const int EB = (E + 31) >> 5;
     auto wr_off = [&](int e, int chunk) { return (e >> 5) * kPipeRing + 3 * kPipeTile + tile_off(e & 31, chunk); };
     const uint16_t* Wr = reinterpret_cast<const uint16_t*>(a.route) + (size_t)h * kDh * E;
-    // W_r[h] is [128][E] in memory and wanted as [E][128]: 16-byte loads (8 consecutive
-    // elements of the flat array, E need not divide 8; 16 E chunks, at most two per thread
-    // for E <= 64), then the tile requests, then 2-byte transposing stores
     constexpr int kWrIter = (kDh * kPipeMaxSubStatic / 8 + THREADS - 1) / THREADS;
     u32x4 wv[kWrIter];
 #pragma unroll
@@ -445,9 +454,7 @@ __global__ __launch_bounds__(64 * kPipeWaves) void fwd_bf16_pipe_kernel(FwdArgs 
       wv[it] = u32x4{0, 0, 0, 0};
       if (c < kDh * E / 8) wv[it] = *reinterpret_cast<const u32x4*>(Wr + 8 * c);
     }
-    dma(0, 0);
-    if (T > 1) dma(1, 1);
-    if (T > 2) dma(2, 2);
+    first_requests();
 #pragma unroll
     for (int it = 0; it < kWrIter; ++it) {
       const int c = tid + it * THREADS;
@@ -466,12 +473,9 @@ __global__ __launch_bounds__(64 * kPipeWaves) void fwd_bf16_pipe_kernel(FwdArgs 
       *reinterpret_cast<uint16_t*>(smem + wr_off(e, j >> 3) + (j & 7) * 2) = 0;
     }
     __syncthreads();
-    // One sweep: the logits of all sub-networks (up to two blocks of 32: this kernel takes
-    // E <= 64) on two independent accumulators, their sigmoids kept in registers, then the
-    // normalisation.
     if (active) {
       f32x16 acc[2] = {f32x16{0}, f32x16{0}};
-      bf16x8 af[2][8];   // all operand reads first: sixteen LDS latencies overlap instead of adding up
+      bf16x8 af[2][8];
 #pragma unroll
       for (int eb = 0; eb < 2; ++eb)
 #pragma unroll
@@ -502,9 +506,7 @@ __global__ __launch_bounds__(64 * kPipeWaves) void fwd_bf16_pipe_kernel(FwdArgs 
         }
     }
   } else {
-    dma(0, 0);
-    if (T > 1) dma(1, 1);
-    if (T > 2) dma(2, 2);
+    first_requests();
     const float* R = reinterpret_cast<const float*>(a.route);
     for (int idx = tid; idx < BM * E; idx += THREADS) {
       const int tl = idx / E, e = idx - tl * E;
@@ -512,185 +514,221 @@ __global__ __launch_bounds__(64 * kPipeWaves) void fwd_bf16_pipe_kernel(FwdArgs 
       Rs[e * BM + tl] = inv_weight((tok < a.N) ? R[((size_t)tok * a.H + h) * E + e] : 0.f);
     }
   }
-  __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0): tiles 0..2 have landed
+  __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0): the first tiles have landed
   __syncthreads();
+  if (T > 3) { dma1(Kh, 3, 0, 3); dma1(Uh, 3, 1, 3); }   // the scratch stage is free now
 
-  // ---- loop-invariant operand addresses inside a tile ------------------------
-  int kaddr[8];      // K/U operand of contraction step ks: row r, chunk 2ks+g
+  // ---- loop-invariant operand addresses (LDS byte addresses) -------------------
+  const unsigned lds0 = lds_addr_of(smem);
+  unsigned kaddr[8];      // K/U operand of contraction step ks: row r, chunk 2ks+g
 #pragma unroll
-  for (int ks = 0; ks < 8; ++ks) kaddr[ks] = tile_off(r, 2 * ks + g);
-  unsigned vaddr[4][2];  // V operand, transposing read: rows 4g + li/4 (+8), 64-byte window jb
+  for (int ks = 0; ks < 8; ++ks) kaddr[ks] = lds0 + tile_off(r, 2 * ks + g);
+  unsigned vaddr[4][2];   // V operand, transposing read: rows 4g + li/4 (+8), 64-byte window jb
   {
     const int li = lane & 15;
     const int row = 4 * g + (li >> 2);
     const int colb = 16 * ((lane >> 4) & 1) + 4 * (li & 3);
-    const unsigned vbase = lds_addr_of(smem + 2 * kPipeRing);
+    const unsigned vbase = lds0 + 2 * kPipeRing;
 #pragma unroll
     for (int jb = 0; jb < 4; ++jb) {
       vaddr[jb][0] = vbase + tile_off8(row, 32 * jb + colb);
       vaddr[jb][1] = vbase + tile_off8(row + 8, 32 * jb + colb);
     }
   }
+  const unsigned rs_lane = lds_addr_of(Rs) + (unsigned)(wtok + r) * 4;
 
   f32x16 O[4];
 #pragma unroll
   for (int jb = 0; jb < 4; ++jb) O[jb] = f32x16{0};
   f32x16 accM[2], accN[2];
-
-  // gate/up products of tile 0
+  u32x4 pk[2][2] = {{u32x4{0, 0, 0, 0}, u32x4{0, 0, 0, 0}}, {u32x4{0, 0, 0, 0}, u32x4{0, 0, 0, 0}}};
+  float tt[8][2], ss[8][2], mn[8][2];
 #pragma unroll
-  for (int ks = 0; ks < (active ? 8 : 0); ++ks) {
-    const bf16x8 ak = *reinterpret_cast<const bf16x8*>(smem + kaddr[ks]);
-    const bf16x8 au = *reinterpret_cast<const bf16x8*>(smem + kPipeRing + kaddr[ks]);
-    if (ks == 0) { accM[0] = mfma32(ak, q[0], f32x16{0}); accN[0] = mfma32(au, q[0], f32x16{0}); }
-    else { accM[0] = mfma32(ak, q[ks], accM[0]); accN[0] = mfma32(au, q[ks], accN[0]); }
+  for (int p = 0; p < 8; ++p) { tt[p][0] = tt[p][1] = 0.f; ss[p][0] = ss[p][1] = 0.f; mn[p][0] = mn[p][1] = 0.f; }
+  float rwv[2] = {1.f, 1.f};
+  bf16x8 gK[2], gU[2];    // operands of the gate/up slots in flight
+  s16x4 dV[4];            // operands of the down slot in flight
+
+  // gate/up products of tile 0 (K/U stage 0), then the operands of the first two slots of
+  // step 0 (gate/up steps 0, 1 of tile 1) and 1/r of tile 0
+  if (active) {
+    bf16x8 ak[8], au[8];
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+      ak[ks] = *reinterpret_cast<const bf16x8*>(smem + tile_off(r, 2 * ks + g));
+      au[ks] = *reinterpret_cast<const bf16x8*>(smem + kPipeRing + tile_off(r, 2 * ks + g));
+    }
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+      if (ks == 0) { accM[0] = mfma32(ak[0], q[0], f32x16{0}); accN[0] = mfma32(au[0], q[0], f32x16{0}); }
+      else { accM[0] = mfma32(ak[ks], q[ks], accM[0]); accN[0] = mfma32(au[ks], q[ks], accN[0]); }
+    }
   }
+  // all waves are through with stage 0 of K/U before step 0 requests tile 4 into it
+  __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0), vmcnt untouched
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
 
-  // 1/r of the current sub-network for this lane's token
-  const float* rs_ptr = Rs + (t_begin / tiles_per_sub) * BM + wtok + r;
-  int sub_cnt = t_begin % tiles_per_sub;
+  // scalar bookkeeping of the sub-network of the *next* tile (for its 1/r)
+  int sub_cnt = __builtin_amdgcn_readfirstlane(t_begin % tiles_per_sub);
+  unsigned rs_off = (unsigned)__builtin_amdgcn_readfirstlane(t_begin / tiles_per_sub) * (BM * 4);
+  if (active) {
+    gK[0] = lds_read_b128_untracked<1 * kPipeTile>(kaddr[0]);
+    gU[0] = lds_read_b128_untracked<1 * kPipeTile + kPipeRing>(kaddr[0]);
+    asm volatile("ds_read_b32 %0, %1" : "=v"(rwv[0]) : "v"(rs_lane + rs_off));
+    gK[1] = lds_read_b128_untracked<1 * kPipeTile>(kaddr[1]);
+    gU[1] = lds_read_b128_untracked<1 * kPipeTile + kPipeRing>(kaddr[1]);
+  }
+  const unsigned rs_off_max = (unsigned)(E - 1) * (BM * 4);
+  if (++sub_cnt == tiles_per_sub) { sub_cnt = 0; rs_off = min(rs_off + BM * 4, rs_off_max); }
 
-  // step i: tile i sits in stage S with its gate/up accumulators in set P
-  auto step = [&](int i, auto S_, auto P_) {
-    constexpr int S = decltype(S_)::value, P = decltype(P_)::value, Q = 1 - P;
-    const bool more = (i + 3 < T);
-    if (more) dma(i + 3, (S + 3) % 4);
+  using I0 = std::integral_constant<int, 0>;
+  using I1 = std::integral_constant<int, 1>;
+  using I2 = std::integral_constant<int, 2>;
+  using I3 = std::integral_constant<int, 3>;
+
+  // step i: tile i has its gate/up accumulators in set P and K/U stage S = i % 4.
+  // MODE 0: ordinary step, 1: first step (no tile i-1), 2: the step after the last tile
+  // (only the last stages of tile T-1 and its down projection).
+  auto step = [&](int i, auto S_, auto P_, auto MODE_) {
+    constexpr int S = decltype(S_)::value, P = decltype(P_)::value, Qs = 1 - P;
+    constexpr int MODE = decltype(MODE_)::value;
+    const bool more_ku = (i + 4 < T), more_v = (i + 2 < T);
+    if (more_ku) { dma1(Kh, i + 4, 0, S); dma1(Uh, i + 4, 1, S); }
+    if (more_v) dma1(Vh, i + 2, 2, (S + 2) % 4);
     if (active) {
-    // the wave that is further behind in its step gets the issue slots: both waves of a
-    // SIMD then reach the barrier closer together (measured: 2 % faster)
-    __builtin_amdgcn_s_setprio(1);
-    const float rw = *rs_ptr;
-    if (++sub_cnt == tiles_per_sub) { sub_cnt = 0; rs_ptr += BM; }
-
-    // Gate/up products of tile i+1 (stage S+1) interleaved with the activation of tile i,
-    // slot by slot.  Slot s issues the LDS reads of contraction step s+2, the two MFMAs of
-    // step s, and one stage each of three element pairs of the activation, so that
-    // dependent VALU instructions sit a slot apart:
-    //   A(pair s): t = 2^(-m log2 e)   B(pair s-1): s = rcp((1+t)/r)   C(pair s-2): m n s, rounding.
-    // The empty asm statements carry the values from slot to slot and thereby pin the order
-    // (the compiler would otherwise issue all MFMAs first and the arithmetic after them).
-    // After the last tile the products read a stale stage and are never used.
-    const unsigned char* kn = smem + ((S + 1) % 4) * kPipeTile;
-    u32x4 pk[2];
-    bf16x8 ka[3], ua[3];
-    float tt[2][2], ss[2][2];
-    s16x4 vlo[4], vhi[4], wlo[4], whi[4];
-#pragma unroll
-    for (int ks = 0; ks < 2; ++ks) {
-      ka[ks] = *reinterpret_cast<const bf16x8*>(kn + kaddr[ks]);
-      ua[ks] = *reinterpret_cast<const bf16x8*>(kn + kPipeRing + kaddr[ks]);
-    }
-    MHFFN_SB();
-#pragma unroll
-    for (int sl = 0; sl < 10; ++sl) {
-      if (sl + 2 < 8) {
-        ka[(sl + 2) % 3] = *reinterpret_cast<const bf16x8*>(kn + kaddr[sl + 2]);
-        ua[(sl + 2) % 3] = *reinterpret_cast<const bf16x8*>(kn + kPipeRing + kaddr[sl + 2]);
-      } else if (sl == 6) {
-        // operands of the first half of the down projection
-        vlo[0] = lds_read_tr16_untracked<S * kPipeTile>(vaddr[0][0]);
-        vhi[0] = lds_read_tr16_untracked<S * kPipeTile>(vaddr[0][1]);
-        vlo[1] = lds_read_tr16_untracked<S * kPipeTile>(vaddr[1][0]);
-        vhi[1] = lds_read_tr16_untracked<S * kPipeTile>(vaddr[1][1]);
-      } else if (sl == 7) {
-        vlo[2] = lds_read_tr16_untracked<S * kPipeTile>(vaddr[2][0]);
-        vhi[2] = lds_read_tr16_untracked<S * kPipeTile>(vaddr[2][1]);
-        vlo[3] = lds_read_tr16_untracked<S * kPipeTile>(vaddr[3][0]);
-        vhi[3] = lds_read_tr16_untracked<S * kPipeTile>(vaddr[3][1]);
-      }
-      const int c = sl & 1, p1 = (sl + 1) & 1;   // slots of pair sl (and sl-2), of pair sl-1
-      if (sl < 8) {
-        if (sl == 0) {
-          accM[Q] = mfma32(ka[0], q[0], f32x16{0});
-          accN[Q] = mfma32(ua[0], q[0], f32x16{0});
+      // activation stages of pair p (registers 2p, 2p+1 of the accumulators), see above
+      auto stA1 = [&](auto p_) {
+        constexpr int p = decltype(p_)::value;
+        tt[p][0] = __builtin_amdgcn_exp2f(-MHFFN_LOG2E * accM[P][2 * p]);
+        tt[p][1] = __builtin_amdgcn_exp2f(-MHFFN_LOG2E * accM[P][2 * p + 1]);
+      };
+      auto stA2 = [&](auto p_) {
+        constexpr int p = decltype(p_)::value;
+        mn[p][0] = accM[P][2 * p] * accN[P][2 * p];
+        mn[p][1] = accM[P][2 * p + 1] * accN[P][2 * p + 1];
+      };
+      auto stB = [&](auto p_, float rw) {
+        constexpr int p = decltype(p_)::value;
+        ss[p][0] = __builtin_amdgcn_rcpf(__builtin_fmaf(tt[p][0], rw, rw));
+        ss[p][1] = __builtin_amdgcn_rcpf(__builtin_fmaf(tt[p][1], rw, rw));
+      };
+      auto stC = [&](auto p_, auto set_) {
+        constexpr int p = decltype(p_)::value, set = decltype(set_)::value;
+        pk[set][p >> 2][p & 3] = pack_bf16(mn[p][0] * ss[p][0], mn[p][1] * ss[p][1]);
+      };
+      auto slot = [&](auto s_) {
+        constexpr int s = decltype(s_)::value;
+        constexpr int k = s / 3, ph = s % 3;
+        // ---- operands of slot s+2 ----
+        // (the step after the last tile requests nothing for a step that never comes: a
+        // register whose read is never waited for could be handed out again too early)
+        constexpr int ts = (s + 2) % 12, so = (s + 2) / 12;
+        if constexpr (MODE == 2 && so == 1) {
+        } else if constexpr (ts % 3 != 2) {
+          constexpr int ks = 2 * (ts / 3) + ts % 3;
+          constexpr int off = ((S + 1 + so) % 4) * kPipeTile;
+          gK[ts % 3] = lds_read_b128_untracked<off>(kaddr[ks]);
+          gU[ts % 3] = lds_read_b128_untracked<off + kPipeRing>(kaddr[ks]);
         } else {
-          accM[Q] = mfma32(ka[sl % 3], q[sl], accM[Q]);
-          accN[Q] = mfma32(ua[sl % 3], q[sl], accN[Q]);
+          constexpr int d0 = 2 * (ts / 3), t2 = d0 / 4, jb0 = d0 % 4;
+          constexpr int off = ((S + 3 + so) % 4) * kPipeTile + t2 * 4096;
+          dV[0] = lds_read_tr16_untracked<off>(vaddr[jb0][0]);
+          dV[1] = lds_read_tr16_untracked<off>(vaddr[jb0][1]);
+          dV[2] = lds_read_tr16_untracked<off>(vaddr[jb0 + 1][0]);
+          dV[3] = lds_read_tr16_untracked<off>(vaddr[jb0 + 1][1]);
         }
-        // the arithmetic below may not start before the two MFMAs above are issued
-        asm volatile("" : "+v"(accM[Q]), "+v"(accN[Q]), "+v"(accM[P]));
-      }
-      uint32_t pkw = 0;
-      if (sl >= 2) {   // C(pair sl-2)
-        const int e = sl - 2;
-        pkw = pack_bf16((accM[P][2 * e] * accN[P][2 * e]) * ss[c][0],
-                        (accM[P][2 * e + 1] * accN[P][2 * e + 1]) * ss[c][1]);
-      }
-      if (sl >= 1 && sl <= 8) {   // B(pair sl-1)
-        ss[p1][0] = __builtin_amdgcn_rcpf(__builtin_fmaf(tt[p1][0], rw, rw));
-        ss[p1][1] = __builtin_amdgcn_rcpf(__builtin_fmaf(tt[p1][1], rw, rw));
-      }
-      if (sl < 8) {               // A(pair sl)
-        tt[c][0] = __builtin_amdgcn_exp2f(-MHFFN_LOG2E * accM[P][2 * sl]);
-        tt[c][1] = __builtin_amdgcn_exp2f(-MHFFN_LOG2E * accM[P][2 * sl + 1]);
-      }
-      // ... and the next slot's MFMAs not before this slot's arithmetic
-      if (sl == 0)
-        asm volatile("" : "+v"(accM[Q]), "+v"(accN[Q]), "+v"(tt[c][0]), "+v"(tt[c][1]) :: "memory");
-      else if (sl == 1)
-        asm volatile("" : "+v"(accM[Q]), "+v"(accN[Q]), "+v"(tt[c][0]), "+v"(tt[c][1]),
-                          "+v"(ss[p1][0]), "+v"(ss[p1][1]) :: "memory");
-      else if (sl < 8)
-        asm volatile("" : "+v"(accM[Q]), "+v"(accN[Q]), "+v"(tt[c][0]), "+v"(tt[c][1]),
-                          "+v"(ss[p1][0]), "+v"(ss[p1][1]), "+v"(pkw) :: "memory");
-      else if (sl == 8)
-        asm volatile("" : "+v"(ss[p1][0]), "+v"(ss[p1][1]), "+v"(pkw) :: "memory");
-      else
-        asm volatile("" : "+v"(pkw) :: "memory");
-      if (sl >= 2) pk[(sl - 2) >> 2][(sl - 2) & 3] = pkw;
-      MHFFN_SB();
+        if constexpr (s == 10 && MODE != 2)   // 1/r of tile i+1 (set Qs)
+          asm volatile("ds_read_b32 %0, %1" : "=v"(rwv[Qs]) : "v"(rs_lane + rs_off));
+        // ---- wait for this slot's operands: all but the reads issued in slots s-1 and s ----
+        constexpr int n_issued[12] = {4, 2, 2, 4, 2, 2, 4, 2, 2, 4, MODE == 2 ? 0 : 3, MODE == 2 ? 0 : 2};
+        constexpr int n_before = (s == 0) ? 2 : n_issued[(s + 11) % 12];   // slot 11 of the step before
+        constexpr int nwait = n_before + n_issued[s];
+        if constexpr (ph != 2) {
+          constexpr int ks = 2 * k + ph;
+          lds_wait<nwait>(gK[ph], gU[ph]);
+          if constexpr (s == 0) asm volatile("" : "+v"(rwv[P]));   // read in slot 10 of the last step
+          if constexpr (MODE != 2) {
+            if constexpr (ks == 0) accM[Qs] = mfma32(gK[ph], q[0], f32x16{0});
+            else accM[Qs] = mfma32(gK[ph], q[ks], accM[Qs]);
+          }
+          MHFFN_SB();
+          if constexpr (ph == 0) { if constexpr (MODE != 2) stA1(std::integral_constant<int, 2 * k>{}); }
+          else {
+            if constexpr (k == 0) stB(std::integral_constant<int, 7>{}, rwv[Qs]);
+            else if constexpr (MODE != 2) stB(std::integral_constant<int, (2 * k + 7) % 8>{}, rwv[P]);
+          }
+          MHFFN_SB();
+          if constexpr (MODE != 2) {
+            if constexpr (ks == 0) accN[Qs] = mfma32(gU[ph], q[0], f32x16{0});
+            else accN[Qs] = mfma32(gU[ph], q[ks], accN[Qs]);
+          }
+          MHFFN_SB();
+          if constexpr (ph == 0) {
+            if constexpr (k == 0) stC(std::integral_constant<int, 6>{}, std::integral_constant<int, Qs>{});
+            else if constexpr (MODE != 2) stC(std::integral_constant<int, 2 * k - 2>{}, std::integral_constant<int, P>{});
+            if constexpr (MODE != 2) stA2(std::integral_constant<int, 2 * k>{});
+          } else {
+            if constexpr (MODE != 2) stA1(std::integral_constant<int, 2 * k + 1>{});
+          }
+          MHFFN_SB();
+        } else {
+          constexpr int d0 = 2 * k, t2 = d0 / 4, jb0 = d0 % 4;
+          lds_wait4<nwait>(dV[0], dV[1], dV[2], dV[3]);
+          const bf16x8 b = __builtin_bit_cast(bf16x8, pk[Qs][t2]);
+          if constexpr (MODE != 1) O[jb0] = mfma32(join_tr(dV[0], dV[1]), b, O[jb0]);
+          MHFFN_SB();
+          if constexpr (MODE != 2) stB(std::integral_constant<int, 2 * k>{}, rwv[P]);
+          MHFFN_SB();
+          if constexpr (MODE != 1) O[jb0 + 1] = mfma32(join_tr(dV[2], dV[3]), b, O[jb0 + 1]);
+          MHFFN_SB();
+          if constexpr (k == 0) stC(std::integral_constant<int, 7>{}, std::integral_constant<int, Qs>{});
+          else if constexpr (MODE != 2) stC(std::integral_constant<int, 2 * k - 1>{}, std::integral_constant<int, P>{});
+          if constexpr (MODE != 2) stA2(std::integral_constant<int, 2 * k + 1>{});
+          MHFFN_SB();
+        }
+      };
+      slot(std::integral_constant<int, 0>{});
+      slot(std::integral_constant<int, 1>{});
+      slot(std::integral_constant<int, 2>{});
+      slot(std::integral_constant<int, 3>{});
+      slot(std::integral_constant<int, 4>{});
+      slot(std::integral_constant<int, 5>{});
+      slot(std::integral_constant<int, 6>{});
+      slot(std::integral_constant<int, 7>{});
+      slot(std::integral_constant<int, 8>{});
+      slot(std::integral_constant<int, 9>{});
+      slot(std::integral_constant<int, 10>{});
+      slot(std::integral_constant<int, 11>{});
     }
-
-    __builtin_amdgcn_s_setprio(0);
-    // down projection of tile i.  Only the 16 untracked reads can be outstanding here
-    // (every tracked read of this step has been consumed above, the next ones follow the
-    // barrier), so lgkmcnt(8) means: the first eight have returned.
-#pragma unroll
-    for (int jb = 0; jb < 4; ++jb) {
-      wlo[jb] = lds_read_tr16_untracked<S * kPipeTile + 4096>(vaddr[jb][0]);
-      whi[jb] = lds_read_tr16_untracked<S * kPipeTile + 4096>(vaddr[jb][1]);
-    }
-    asm volatile("s_waitcnt lgkmcnt(8)"
-                 : "+v"(vlo[0]), "+v"(vhi[0]), "+v"(vlo[1]), "+v"(vhi[1]), "+v"(vlo[2]), "+v"(vhi[2]),
-                   "+v"(vlo[3]), "+v"(vhi[3]));
-    const bf16x8 b0 = __builtin_bit_cast(bf16x8, pk[0]), b1 = __builtin_bit_cast(bf16x8, pk[1]);
-    typedef short s16x8 __attribute__((ext_vector_type(8)));
-#pragma unroll
-    for (int jb = 0; jb < 4; ++jb) {
-      const s16x8 both = __builtin_shufflevector(vlo[jb], vhi[jb], 0, 1, 2, 3, 4, 5, 6, 7);
-      O[jb] = mfma32(__builtin_bit_cast(bf16x8, both), b0, O[jb]);
-    }
-    asm volatile("s_waitcnt lgkmcnt(0)"
-                 : "+v"(wlo[0]), "+v"(whi[0]), "+v"(wlo[1]), "+v"(whi[1]), "+v"(wlo[2]), "+v"(whi[2]),
-                   "+v"(wlo[3]), "+v"(whi[3]));
-#pragma unroll
-    for (int jb = 0; jb < 4; ++jb) {
-      const s16x8 both = __builtin_shufflevector(wlo[jb], whi[jb], 0, 1, 2, 3, 4, 5, 6, 7);
-      O[jb] = mfma32(__builtin_bit_cast(bf16x8, both), b1, O[jb]);
-    }
-    }  // active
-    // Publish tile i+2 (requested one step ago; the three loads issued at the top of this
-    // step may stay in flight) and retire stage S.  A bare barrier: __syncthreads() would
-    // wait for every load in flight.
+    if (++sub_cnt == tiles_per_sub) { sub_cnt = 0; rs_off = min(rs_off + BM * 4, rs_off_max); }
+    // Publish what was requested one step ago (K/U tile i+3, V tile i+1; this step's own
+    // requests may stay in flight) and retire K/U stage S+1 and V stage S+3.  The LDS reads
+    // in flight belong to the next step's first slots and to stages that stay.
     asm volatile("" ::: "memory");
-    if (more) __builtin_amdgcn_s_waitcnt(0x0073);  // vmcnt(3) lgkmcnt(0)
-    else __builtin_amdgcn_s_waitcnt(0x0070);       // vmcnt(0) lgkmcnt(0)
+    if (more_ku) __builtin_amdgcn_s_waitcnt(0x0f73);       // vmcnt(3), lgkmcnt untouched
+    else if (more_v) __builtin_amdgcn_s_waitcnt(0x0f71);   // vmcnt(1)
+    else __builtin_amdgcn_s_waitcnt(0x0f70);               // vmcnt(0)
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
   };
-  using C0 = std::integral_constant<int, 0>;
-  using C1 = std::integral_constant<int, 1>;
-  using C2 = std::integral_constant<int, 2>;
-  using C3 = std::integral_constant<int, 3>;
-  for (int i = 0; i < T; i += 4) {
-    step(i, C0{}, C0{});
-    if (i + 1 < T) step(i + 1, C1{}, C1{});
-    if (i + 2 < T) step(i + 2, C2{}, C0{});
-    if (i + 3 < T) step(i + 3, C3{}, C1{});
+  step(0, I0{}, I0{}, I1{});
+  for (int i = 1; i < T; i += 4) {
+    step(i, I1{}, I1{}, I0{});
+    if (i + 1 < T) step(i + 1, I2{}, I0{}, I0{});
+    if (i + 2 < T) step(i + 2, I3{}, I1{}, I0{});
+    if (i + 3 < T) step(i + 3, I0{}, I0{}, I0{});
   }
+  // the step after the last tile: the remaining stages of tile T-1 and its down projection
+  switch (T & 3) {
+    case 0: step(T, I0{}, I0{}, I2{}); break;
+    case 1: step(T, I1{}, I1{}, I2{}); break;
+    case 2: step(T, I2{}, I0{}, I2{}); break;
+    default: step(T, I3{}, I1{}, I2{}); break;
+  }
+  __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0): the reads issued for a step that never comes
 
   const int64_t tok = tile_tok0 + wtok + r;
-  // ---- split runs leave an fp32 partial; fwd_bf16_reduce_kernel sums them ---
   if (a.n_split > 1) {
     if (tok < a.N) {
       float* dst = a.P + (((size_t)split * a.N + tok) * a.H + h) * kDh + 4 * g;
@@ -704,17 +742,16 @@ __global__ __launch_bounds__(64 * kPipeWaves) void fwd_bf16_pipe_kernel(FwdArgs 
     }
     return;
   }
-  // ---- store Y (concat_H: head h owns columns h*d_h ..) --------------------
   if (tok < a.N) {
     uint16_t* dst = a.Y + tok * a.ldy + h * kDh + 4 * g;
 #pragma unroll
     for (int jb = 0; jb < 4; ++jb) {
 #pragma unroll
       for (int vq = 0; vq < 4; ++vq) {
-        u32x2 pk;
-        pk[0] = pack_bf16(O[jb][4 * vq], O[jb][4 * vq + 1]);
-        pk[1] = pack_bf16(O[jb][4 * vq + 2], O[jb][4 * vq + 3]);
-        *reinterpret_cast<u32x2*>(dst + 32 * jb + 8 * vq) = pk;
+        u32x2 pkw;
+        pkw[0] = pack_bf16(O[jb][4 * vq], O[jb][4 * vq + 1]);
+        pkw[1] = pack_bf16(O[jb][4 * vq + 2], O[jb][4 * vq + 3]);
+        *reinterpret_cast<u32x2*>(dst + 32 * jb + 8 * vq) = pkw;
       }
     }
   }
@@ -790,10 +827,10 @@ int launch_pipe(const Problem& p, FwdArgs a, const SplitPlan& sp, hipStream_t st
   a.n_items = a.n_tiles * p.H * sp.n_split;
   const size_t lds = (size_t)3 * kPipeRing + (size_t)p.E * kPipeBM * sizeof(float);
   static std::atomic<uint64_t> lds_allowed{0};
-  if (hipError_t e0 = allow_lds_bytes(reinterpret_cast<const void*>(&fwd_bf16_pipe_kernel),
+  if (hipError_t e0 = allow_lds_bytes(reinterpret_cast<const void*>(&fwd_bf16_flow_kernel),
                                       (int)kLdsBytesPerWorkgroup, lds_allowed); e0 != hipSuccess)
     return (int)e0;
-  hipLaunchKernelGGL(fwd_bf16_pipe_kernel, dim3((unsigned)xcd_grid_size(a.n_items)),
+  hipLaunchKernelGGL(fwd_bf16_flow_kernel, dim3((unsigned)xcd_grid_size(a.n_items)),
                      dim3(64 * kPipeWaves), lds, stream, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || sp.n_split == 1) return (int)e;

@@ -88,15 +88,66 @@ def _dtype_code(t):
     raise TypeError("unsupported dtype %s" % t.dtype)
 
 
+def _require(cond, msg):
+    if not cond:
+        raise ValueError(msg)
+
+
+def _rows(name, t, like, n_tokens=None):
+    """Check a row tensor ([N, d_model], unit column stride, dtype and device of `like`);
+    returns its row stride in elements (d_model for fewer than two rows)."""
+    _require(t.dim() == 2 and t.shape[1] == like.shape[1], "%s must be [N, %d], got %s"
+             % (name, like.shape[1], tuple(t.shape)))
+    _require(t.shape[0] == (like.shape[0] if n_tokens is None else n_tokens),
+             "%s has %d rows, expected %d" % (name, t.shape[0], like.shape[0]))
+    _require(t.dtype == like.dtype, "%s has dtype %s, expected %s" % (name, t.dtype, like.dtype))
+    _require(t.device == like.device, "%s is on %s, expected %s" % (name, t.device, like.device))
+    if t.shape[0] < 2:
+        _require(t.shape[0] == 0 or t.stride(1) == 1, "%s rows must be contiguous" % name)
+        return t.shape[1]
+    _require(t.stride(1) == 1, "%s rows must be contiguous" % name)
+    _require(t.stride(0) >= t.shape[1], "%s rows overlap (row stride %d)" % (name, t.stride(0)))
+    return t.stride(0)
+
+
+def _dense(name, t, shape, dtype, device):
+    """Check a dense tensor the kernels index without strides (weights, gating, their gradients)."""
+    _require(tuple(t.shape) == tuple(shape), "%s must have shape %s, got %s"
+             % (name, tuple(shape), tuple(t.shape)))
+    _require(t.dtype == dtype, "%s has dtype %s, expected %s" % (name, t.dtype, dtype))
+    _require(t.device == device, "%s is on %s, expected %s" % (name, t.device, device))
+    _require(t.is_contiguous(), "%s must be contiguous" % name)
+
+
+def _check_params(X, W_gate, W_up, W_down, route, route_mode):
+    _require(W_gate.dim() == 4, "W_gate must be [H, E, d_e, d_h]")
+    H, E, d_e, d_h = W_gate.shape
+    _require(X.dim() == 2 and X.shape[1] == H * d_h,
+             "X must be [N, H*d_h] = [N, %d], got %s" % (H * d_h, tuple(X.shape)))
+    for name, w in (("W_gate", W_gate), ("W_up", W_up), ("W_down", W_down)):
+        _dense(name, w, (H, E, d_e, d_h), X.dtype, X.device)
+    if int(route_mode) == ROUTE_PARAMS:
+        _dense("route (W_r)", route, (H, d_h, E), X.dtype, X.device)
+    else:
+        _dense("route (R)", route, (X.shape[0], H, E), torch.float32, X.device)
+
+
 def make_desc(X, W_gate, route_mode, eps, Y=None):
+    """Descriptor for X (row stride ld_x) and, where given, the Y-side row tensor (Y, dY, O
+    or dO: row stride ld_y; dense otherwise)."""
     H, E, d_e, d_h = W_gate.shape
     if X.dim() != 2 or X.shape[1] != H * d_h:
         raise ValueError("X must be [N, H*d_h] = [N, %d], got %s" % (H * d_h, tuple(X.shape)))
-    if X.stride(1) != 1:
-        raise ValueError("X rows must be contiguous")
-    ld_y = X.stride(0) if Y is None else Y.stride(0)
-    return Desc(X.shape[0], H, d_h, E, d_e, X.stride(0) if X.shape[0] > 1 else H * d_h,
-                ld_y if X.shape[0] > 1 else H * d_h, _dtype_code(X), int(route_mode), float(eps))
+    ld_x = _rows("X", X, X)
+    ld_y = H * d_h if Y is None else _rows("the output-side row tensor", Y, X)
+    return Desc(X.shape[0], H, d_h, E, d_e, ld_x, ld_y, _dtype_code(X), int(route_mode), float(eps))
+
+
+def _empty_rows_like(X):
+    """Uninitialised [N, d_model] tensor with X's row stride (the kernels index dX with ld_x)."""
+    if X.shape[0] < 2 or X.is_contiguous():
+        return torch.empty_like(X)
+    return torch.empty_strided(tuple(X.shape), tuple(X.stride()), dtype=X.dtype, device=X.device)
 
 
 def _p(t):
@@ -124,7 +175,8 @@ def forward(X, W_gate, W_up, W_down, route, eps=1e-6, route_mode=ROUTE_PARAMS, o
             stream=None, workspace=None):
     """Fused forward.  Returns Y [N, H*d_h] (dtype of X).  Scratch is needed only
     for small token counts (see mhffn_workspace_bytes); allocated here if not given."""
-    Y = torch.empty_like(X) if out is None else out
+    _check_params(X, W_gate, W_up, W_down, route, route_mode)
+    Y = torch.empty(X.shape, dtype=X.dtype, device=X.device) if out is None else out
     d = make_desc(X, W_gate, route_mode, eps, Y)
     workspace, have = _workspace(d, OP_FORWARD, X.device, workspace)
     rc = load().mhffn_forward(ctypes.byref(d), _p(X), _p(W_gate), _p(W_up), _p(W_down),
@@ -134,18 +186,33 @@ def forward(X, W_gate, W_up, W_down, route, eps=1e-6, route_mode=ROUTE_PARAMS, o
     return Y
 
 
+def _grad_outputs(X, W_gate, W_up, W_down, route, want, out, ld_x):
+    """The gradient tensors of a backward call: those the caller passed, checked against what
+    the kernels assume (dX: X's row stride; the rest dense, shaped like their parameter), and
+    fresh ones for the rest of `want`."""
+    out = dict(out or {})
+    like = {"dW_gate": W_gate, "dW_up": W_up, "dW_down": W_down, "d_route": route}
+    for k in want:
+        if k not in out:
+            out[k] = _empty_rows_like(X) if k == "dX" else torch.empty_like(like[k])
+    if out.get("dX") is not None:
+        _require(_rows("dX", out["dX"], X) == ld_x or X.shape[0] < 2,
+                 "dX must have X's row stride (%d), got %d" % (ld_x, out["dX"].stride(0)))
+    for k, ref in like.items():
+        if out.get(k) is not None:
+            _dense(k, out[k], ref.shape, ref.dtype, ref.device)
+    return out
+
+
 def backward(X, W_gate, W_up, W_down, route, dY, eps=1e-6, route_mode=ROUTE_PARAMS,
              want=("dX", "dW_gate", "dW_up", "dW_down", "d_route"), workspace=None, out=None,
              stream=None, phase_events=None):
     """Fused recompute-based backward.  Returns a dict of the requested gradients.
     `phase_events`: optional list of raw hipEvent_t handles (ints) recorded between
     the phases of the backward (see mhffn_backward_phases)."""
+    _check_params(X, W_gate, W_up, W_down, route, route_mode)
     d = make_desc(X, W_gate, route_mode, eps, dY)
-    out = dict(out or {})
-    like = {"dX": X, "dW_gate": W_gate, "dW_up": W_up, "dW_down": W_down, "d_route": route}
-    for k in want:
-        if k not in out:
-            out[k] = torch.empty_like(like[k])
+    out = _grad_outputs(X, W_gate, W_up, W_down, route, want, out, d.ld_x)
     workspace, have = _workspace(d, OP_BACKWARD, X.device, workspace)
     args = (ctypes.byref(d), _p(X), _p(W_gate), _p(W_up), _p(W_down), _p(route), _p(dY),
             _p(out.get("dX")), _p(out.get("dW_gate")), _p(out.get("dW_up")),
@@ -165,16 +232,20 @@ def reference_unfused(X, W_gate, W_up, W_down, route, eps=1e-6, route_mode=ROUTE
                       workspace=None, out=None, stream=None):
     """Unfused GPU baseline (materialises the intermediates in `workspace`).
     Returns Y, or (Y, grads) when dY is given."""
-    d = make_desc(X, W_gate, route_mode, eps)
+    _check_params(X, W_gate, W_up, W_down, route, route_mode)
     out = dict(out or {})
     Y = out.get("Y")
     if Y is None:
-        Y = torch.empty_like(X)
-    like = {"dX": X, "dW_gate": W_gate, "dW_up": W_up, "dW_down": W_down, "d_route": route}
+        # Y and dY share the descriptor's ld_y: a fresh Y takes dY's row stride
+        Y = _empty_rows_like(dY) if dY is not None else torch.empty(X.shape, dtype=X.dtype,
+                                                                    device=X.device)
+    d = make_desc(X, W_gate, route_mode, eps, Y)
     if dY is not None:
-        for k in want:
-            if k not in out:
-                out[k] = torch.empty_like(like[k])
+        _require(_rows("dY", dY, X) == d.ld_y or X.shape[0] < 2,
+                 "Y and dY must have the same row stride (%d and %d)" % (d.ld_y, dY.stride(0)))
+        grads = _grad_outputs(X, W_gate, W_up, W_down, route, want,
+                              {k: v for k, v in out.items() if k != "Y"}, d.ld_x)
+        out.update(grads)
     op = OP_UNFUSED_FORWARD if dY is None else OP_UNFUSED_BACKWARD
     workspace, have = _workspace(d, op, X.device, workspace)
     rc = load().mhffn_reference_unfused(
@@ -195,11 +266,16 @@ def module_forward(X, W_in, W_gate, W_up, W_down, W_r, W_out, eps=1e-6, out=None
                    workspace=None):
     """The whole module: O = fused(X W_in) W_out.  Returns (O, Q, S); Q and S are the two
     d_model-wide activations that module_backward needs."""
+    _check_params(X, W_gate, W_up, W_down, W_r, ROUTE_PARAMS)
     out = dict(out or {})
     N, dm = X.shape
     for k in ("O", "Q", "S"):
         if k not in out:
             out[k] = torch.empty((N, dm), dtype=X.dtype, device=X.device)
+    for k, w in (("W_in", W_in), ("W_out", W_out)):
+        _dense(k, w, (dm, dm), X.dtype, X.device)
+    for k in ("Q", "S"):
+        _dense(k, out[k], (N, dm), X.dtype, X.device)
     d = make_desc(X, W_gate, ROUTE_PARAMS, eps, out["O"])
     workspace, have = _workspace(d, OP_MODULE_FORWARD, X.device, workspace)
     rc = load().mhffn_module_forward(ctypes.byref(d), _p(X), _p(W_in), _p(W_gate), _p(W_up),
@@ -213,13 +289,25 @@ def module_forward(X, W_in, W_gate, W_up, W_down, W_r, W_out, eps=1e-6, out=None
 def module_backward(X, W_in, W_gate, W_up, W_down, W_r, W_out, Q, S, dO, eps=1e-6,
                     want=MODULE_GRADS, out=None, stream=None, workspace=None):
     """Backward of module_forward from the saved Q and S.  Returns a dict of gradients."""
+    _check_params(X, W_gate, W_up, W_down, W_r, ROUTE_PARAMS)
     out = dict(out or {})
-    like = {"dX": X, "dW_in": W_in, "dW_gate": W_gate, "dW_up": W_up, "dW_down": W_down,
+    N, dm = X.shape
+    like = {"dW_in": W_in, "dW_gate": W_gate, "dW_up": W_up, "dW_down": W_down,
             "dW_r": W_r, "dW_out": W_out}
+    for k, w in (("W_in", W_in), ("W_out", W_out)):
+        _dense(k, w, (dm, dm), X.dtype, X.device)
+    for k, t in (("Q", Q), ("S", S)):
+        _dense(k, t, (N, dm), X.dtype, X.device)
+    d = make_desc(X, W_gate, ROUTE_PARAMS, eps, dO)
     for k in want:
         if k not in out:
-            out[k] = torch.empty_like(like[k])
-    d = make_desc(X, W_gate, ROUTE_PARAMS, eps, dO)
+            out[k] = _empty_rows_like(X) if k == "dX" else torch.empty_like(like[k])
+    if out.get("dX") is not None:
+        _require(_rows("dX", out["dX"], X) == d.ld_x or N < 2,
+                 "dX must have X's row stride (%d), got %d" % (d.ld_x, out["dX"].stride(0)))
+    for k, ref in like.items():
+        if out.get(k) is not None:
+            _dense(k, out[k], ref.shape, ref.dtype, ref.device)
     workspace, have = _workspace(d, OP_MODULE_BACKWARD, X.device, workspace)
     rc = load().mhffn_module_backward(
         ctypes.byref(d), _p(X), _p(W_in), _p(W_gate), _p(W_up), _p(W_down), _p(W_r), _p(W_out),

@@ -120,6 +120,33 @@ def test_f32_weights_mode_returns_dr():
     check_all(got, ref, TOL["f32"])
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_strided_rows_dx_takes_the_stride_of_x(dtype):
+    """X and dY are column slices of wider buffers (ld_x, ld_y > d_model, different from each
+    other).  The binding allocates dX with X's row stride, the kernels write only the
+    d_model columns of each row, and a caller-provided strided dX keeps its padding."""
+    import torch
+    w = small_workload("bwd_strided", 130, 2, 3, 64, dtype, backward=True)
+    d = inputs.make_inputs(w, seed=9, with_dy=True)
+    g = device_inputs(d, w.dtype)
+    dm, td = w.d_model, g["X"].dtype
+    Xp = torch.zeros(w.n_tokens, dm + 64, dtype=td, device="cuda")
+    Xp[:, :dm] = g["X"]
+    dYp = torch.zeros(w.n_tokens, dm + 128, dtype=td, device="cuda")
+    dYp[:, :dm] = g["dY"]
+    ref = orc.backward(d["X"], d["W_gate"], d["W_up"], d["W_down"], d["W_r"], d["dY"], w.eps)
+    out = mhffn.backward(Xp[:, :dm], g["W_gate"], g["W_up"], g["W_down"], g["W_r"], dYp[:, :dm], w.eps)
+    torch.cuda.synchronize()
+    assert out["dX"].stride(0) == dm + 64 and out["dX"].shape == (w.n_tokens, dm)
+    check_all({k: to_host(v) for k, v in out.items()}, ref, TOL[dtype])
+    dXp = torch.full((w.n_tokens, dm + 64), 7.0, dtype=td, device="cuda")
+    out = mhffn.backward(Xp[:, :dm], g["W_gate"], g["W_up"], g["W_down"], g["W_r"], dYp[:, :dm], w.eps,
+                         want=("dX",), out={"dX": dXp[:, :dm]})
+    torch.cuda.synchronize()
+    assert torch.all(dXp[:, dm:] == 7.0)
+    assert relerr(to_host(dXp[:, :dm]), ref["dX"]) <= TOL[dtype]
+
+
 def test_partial_gradient_requests():
     w = small_workload("bwd_partial", 300, 2, 3, 64, "bf16", backward=True)
     d, full = run_backward(w, seed=8)

@@ -5,10 +5,12 @@ import pytest
 
 from oracle import mhffn_oracle as orc
 from paper_2512_06989_amd import inputs, mhffn
-from tests.helpers import TOL, device_inputs, relerr, small_workload, to_host
+from tests.helpers import TOL, check_parity, device_inputs, relerr, small_workload, to_host
 
 pytestmark = pytest.mark.gpu
-# Tolerance of the bf16 module: the path's own bound (5e-3) covers inputs that are exact in
+# The module is checked stage by stage at the path's own bound (every stage against the oracle
+# fed with the GPU's own input of that stage) and end to end at a second, looser one.
+# End-to-end tolerance of the bf16 module: the path's own bound (5e-3) covers inputs that are exact in
 # bf16.  Here the path's input Q and its output gradient dS are themselves products rounded
 # to bf16 (relative error 2^-9 / sqrt(3) = 1.1e-3 per element, which passes through both the
 # gate and the up product and through every gradient), and S and dQ are rounded once more
@@ -106,3 +108,78 @@ def test_empty_batch_gives_zero_parameter_gradients(dtype):
     torch.cuda.synchronize()
     for k in like:
         assert torch.count_nonzero(res[k]) == 0, k
+
+
+def _stages(w, seed, heads=None, rows=None, cols=None):
+    """Run the module forward and backward and compare every stage with the oracle evaluated
+    on the GPU's own input of that stage (Q from X; S from the GPU's Q; O from the GPU's S; dS
+    from dO; the fused gradients from the GPU's Q and dS; dW_in and dX from the GPU's dQ), at
+    the path's tolerance.  `heads`: heads on which the fused stages are compared (default all);
+    `rows` / `cols`: token rows and weight-gradient columns on which the projection stages are
+    compared (default all)."""
+    import torch
+    d = inputs.make_module_inputs(w, seed=seed, with_dy=True)
+    g = device_inputs(d, w.dtype)
+    a = [g[k] for k in ARGS]
+    N, dm, dh = w.n_tokens, w.d_model, w.d_head
+    desc = mhffn.make_desc(g["X"], g["W_gate"], mhffn.ROUTE_PARAMS, w.eps)
+    ws = torch.empty(mhffn.workspace_bytes(desc, mhffn.OP_MODULE_BACKWARD), dtype=torch.uint8, device="cuda")
+    O, Q, S = mhffn.module_forward(*a, w.eps)
+    grads = mhffn.module_backward(*a, Q, S, g["dY"], w.eps, workspace=ws)
+    torch.cuda.synchronize()
+    # the workspace starts with dS and dQ, dense [N][d_model], each rounded up to 256 bytes
+    es = 2 if w.dtype == "bf16" else 4
+    act = (N * dm * es + 255) // 256 * 256
+    td = torch.bfloat16 if w.dtype == "bf16" else torch.float32
+    dS = to_host(ws[:N * dm * es].view(td).view(N, dm))
+    dQ = to_host(ws[act:act + N * dm * es].view(td).view(N, dm))
+    O, Q, S = to_host(O), to_host(Q), to_host(S)
+    grads = {k: to_host(v) for k, v in grads.items()}
+    tol = TOL[w.dtype]
+    X, dO = d["X"].astype(np.float64), d["dY"].astype(np.float64)
+    W_in, W_out = d["W_in"].astype(np.float64), d["W_out"].astype(np.float64)
+    rows = np.arange(N) if rows is None else np.asarray(rows)
+    cols = np.arange(dm) if cols is None else np.asarray(cols)
+    figs = {}
+    figs.update(check_parity({"Q": Q[rows]}, {"Q": X[rows] @ W_in}, tol, dh, "Q = X W_in"))
+    figs.update(check_parity({"O": O[rows]}, {"O": S[rows] @ W_out}, tol, dh, "O = S W_out"))
+    figs.update(check_parity({"dS": dS[rows]}, {"dS": dO[rows] @ W_out.T}, tol, dh, "dS = dO W_out^T"))
+    figs.update(check_parity({"dX": grads["dX"][rows]}, {"dX": dQ[rows] @ W_in.T}, tol, dh, "dX = dQ W_in^T"))
+    figs.update(check_parity({"dW_in": grads["dW_in"][:, cols].T}, {"dW_in": (X.T @ dQ[:, cols]).T},
+                             tol, dm, "dW_in = X^T dQ"))
+    figs.update(check_parity({"dW_out": grads["dW_out"][:, cols].T}, {"dW_out": (S.T @ dO[:, cols]).T},
+                             tol, dm, "dW_out = S^T dO"))
+    for h in (range(w.n_heads) if heads is None else heads):
+        c = slice(h * dh, (h + 1) * dh)
+        wh = [d[k][h:h + 1] for k in ("W_gate", "W_up", "W_down", "W_r")]
+        ref_s = orc.forward(Q[:, c], *wh, w.eps)
+        figs.update({"S[%d]" % h: check_parity({"S": S[:, c]}, {"S": ref_s}, tol, dh, "S head %d" % h)["S"]})
+        ref = orc.backward(Q[:, c], *wh, dS[:, c], w.eps)
+        mine = {"dX": dQ[:, c], "dW_gate": grads["dW_gate"][h:h + 1], "dW_up": grads["dW_up"][h:h + 1],
+                "dW_down": grads["dW_down"][h:h + 1], "d_route": grads["dW_r"][h:h + 1]}
+        r = check_parity(mine, ref, tol, dh, "fused backward head %d" % h,
+                         skip=("d_route",) if w.n_sub == 1 else ())
+        figs.update({"%s[%d]" % (k, h): v for k, v in r.items()})
+    return figs
+
+
+@pytest.mark.parametrize("dtype,N,H,dh,E,de", [
+    ("f32", 150, 2, 128, 3, 64), ("bf16", 257, 2, 128, 4, 128), ("bf16", 1000, 3, 128, 5, 64),
+    ("bf16", 300, 2, 64, 6, 192), ("bf16", 300, 1, 256, 3, 96)])
+def test_module_stage_by_stage(dtype, N, H, dh, E, de):
+    w = small_workload("module_stages", N, H, E, de, dtype, dh=dh, backward=True)
+    _stages(w, seed=N + dh)
+
+
+def test_full_size_module_stage_by_stage():
+    """The 1.3B shape, forward and backward: the fused stages on two whole heads (heads are
+    independent and a weight gradient needs every token), the projection stages on sampled
+    token rows and sampled weight-gradient columns (each output element of a product is an
+    independent contraction)."""
+    w = inputs.WORKLOADS["1p3b_fwdbwd"]
+    rng = np.random.default_rng(4)
+    rows = np.unique(np.concatenate([[0, 255, 256, w.n_tokens - 1],
+                                     rng.choice(w.n_tokens, size=380, replace=False)]))
+    cols = np.unique(np.concatenate([[0, w.d_model - 1], rng.choice(w.d_model, size=94, replace=False)]))
+    figs = _stages(w, seed=0, heads=(2, 13), rows=rows, cols=cols)
+    print("  " + ", ".join("%s %.2e/%.2e" % (k, f, r) for k, (f, r) in figs.items()), flush=True)

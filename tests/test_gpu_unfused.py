@@ -52,6 +52,37 @@ def test_unfused_weights_mode(dtype):
     assert all(e <= tol for e in errs.values()), str(errs)
 
 
+def test_unfused_strided_rows():
+    """X and dY as column slices of wider buffers: Y takes dY's row stride, dX takes X's, and
+    the padding columns of caller-provided outputs stay untouched."""
+    import torch
+    w = small_workload("unf_strided", 130, 2, 3, 64, "bf16", backward=True)
+    d = inputs.make_inputs(w, seed=9, with_dy=True)
+    g = device_inputs(d, w.dtype)
+    dm = w.d_model
+    Xp = torch.zeros(w.n_tokens, dm + 64, dtype=torch.bfloat16, device="cuda")
+    Xp[:, :dm] = g["X"]
+    dYp = torch.zeros(w.n_tokens, dm + 128, dtype=torch.bfloat16, device="cuda")
+    dYp[:, :dm] = g["dY"]
+    Yp = torch.full((w.n_tokens, dm + 128), 7.0, dtype=torch.bfloat16, device="cuda")
+    dXp = torch.full((w.n_tokens, dm + 64), 9.0, dtype=torch.bfloat16, device="cuda")
+    Y, grads = mhffn.reference_unfused(Xp[:, :dm], g["W_gate"], g["W_up"], g["W_down"], g["W_r"], w.eps,
+                                       dY=dYp[:, :dm], out={"Y": Yp[:, :dm], "dX": dXp[:, :dm]})
+    torch.cuda.synchronize()
+    assert torch.all(Yp[:, dm:] == 7.0) and torch.all(dXp[:, dm:] == 9.0)
+    tol = 3 * TOL["bf16"]
+    assert relerr(to_host(Y), orc.forward(d["X"], d["W_gate"], d["W_up"], d["W_down"], d["W_r"], w.eps)) <= tol
+    ref = orc.backward(d["X"], d["W_gate"], d["W_up"], d["W_down"], d["W_r"], d["dY"], w.eps)
+    errs = {k: relerr(to_host(grads[k]), ref[k]) for k in GRADS}
+    assert all(e <= tol for e in errs.values()), str(errs)
+    # outputs allocated by the binding: Y with dY's stride, dX with X's
+    Y2, g2 = mhffn.reference_unfused(Xp[:, :dm], g["W_gate"], g["W_up"], g["W_down"], g["W_r"], w.eps,
+                                     dY=dYp[:, :dm], want=("dX",))
+    torch.cuda.synchronize()
+    assert Y2.stride(0) == dm + 128 and g2["dX"].stride(0) == dm + 64
+    assert torch.equal(Y2, Y) and torch.equal(g2["dX"], grads["dX"])
+
+
 @pytest.mark.parametrize("seed", range(6))
 def test_fused_agrees_with_unfused_on_random_shapes(seed):
     import torch
