@@ -21,13 +21,17 @@
  *    caller.  `desc` is a HOST pointer.  `hip_stream` is a hipStream_t passed
  *    as void* (NULL = the default stream).
  *  - The library never allocates or frees device memory, never synchronises
- *    and keeps no data between calls (all it remembers is on which devices it
- *    has already raised a kernel's LDS limit): all work is enqueued on
- *    `hip_stream`, which must belong to the calling thread's current device,
- *    and the call returns immediately.  Calls may come from several threads
- *    and for several devices.  Scratch comes from the caller through
- *    `workspace` (at least mhffn_workspace_bytes() bytes, 256-byte aligned;
- *    may be NULL when that size is 0).
+ *    and keeps no data between calls: all work is enqueued on `hip_stream`,
+ *    which must belong to the calling thread's current device, and the call
+ *    returns immediately.  Calls may come from several threads and for
+ *    several devices.  Scratch comes from the caller through `workspace` (at
+ *    least mhffn_workspace_bytes() bytes, 256-byte aligned; may be NULL when
+ *    that size is 0).
+ *  - The only host-side state is, per kernel and device, the fact that the
+ *    kernel's dynamic-LDS limit has been raised (a function attribute).
+ *    mhffn_init() does this for every kernel on the current device; without
+ *    it the first launch of each kernel on a device does it, and that first
+ *    launch must then happen outside stream capture.
  *  - Outputs are overwritten, never accumulated into.
  *  - Errors are reported by return code only; every argument is validated on
  *    the host before anything is launched, so a non-zero return means nothing
@@ -108,14 +112,16 @@ typedef struct {
 
 /* Bytes of caller-provided scratch needed by `op` (an mhffn_op) for `desc`.
  * Returns 0 for an invalid descriptor as well; validate with the entry point.
- * For MHFFN_OP_FORWARD this is 0 whenever the token tiles alone fill the chip
- * (n_tokens * n_heads >= 384 * 256): the fused forward then touches nothing but
- * its inputs and Y, which is the "intermediate never reaches HBM" property of
- * eq:flash-ffn-loop stated as a number.  For fewer tokens (decode, short
+ * For MHFFN_OP_FORWARD this is 0 whenever the token tiles alone give the chip
+ * enough workgroups (d_head = 128 with up to 64 sub-networks: more than 128
+ * tiles of 256 tokens x heads, i.e. ceil(n_tokens / 256) * n_heads > 128; the
+ * other kernels: at least 384 tiles): the fused forward then touches nothing
+ * but its inputs and Y, which is the "intermediate never reaches HBM" property
+ * of eq:flash-ffn-loop stated as a number.  For fewer tokens (decode, short
  * prefill) the blocks of eq:flash-ffn-loop are shared out over several
  * workgroups per token tile and their fp32 partial outputs, n_split * N *
  * d_model * 4 bytes (a few output-sized buffers, never d_ff-sized ones), pass
- * through the workspace.  For MHFFN_OP_BACKWARD it is the gating weights R and
+ * through the workspace; ask this function rather than relying on the rule.  For MHFFN_OP_BACKWARD it is the gating weights R and
  * their gradient as [H][E][N] fp32, the partial sums of dW_r, and, for shapes
  * whose weights alone cannot fill the chip, fp32 partial weight gradients of a
  * few token segments (all summed in a fixed order: results are bit-identical
@@ -203,6 +209,13 @@ int mhffn_module_backward(const mhffn_desc* desc, const void* X, const void* W_i
                           const void* dO, void* dX, void* dW_in, void* dW_gate, void* dW_up,
                           void* dW_down, void* dW_r, void* dW_out, void* workspace,
                           size_t workspace_bytes, void* hip_stream);
+
+/* Optional set-up for the calling thread's current device: raises the
+ * dynamic-LDS limit of every kernel of the library there, so that no later call
+ * on that device changes a kernel attribute (first calls may then be recorded
+ * into a HIP graph).  Idempotent, thread-safe, enqueues nothing.  Returns
+ * MHFFN_OK, or MHFFN_ERR_LAUNCH if HIP refused an attribute. */
+int mhffn_init(void);
 
 /* Static, human-readable name of a status code. */
 const char* mhffn_status_string(int status);

@@ -3,7 +3,15 @@
 // keeps data between calls; see include/mhffn.h for the contract.
 #include "../../include/mhffn.h"
 
+#include "mhffn_device.h"
 #include "mhffn_internal.h"
+
+namespace mhffn {
+LdsKernelEntry*& lds_kernel_list() {
+  static LdsKernelEntry* head = nullptr;   // constant-initialised: safe during static initialisation
+  return head;
+}
+}  // namespace mhffn
 
 namespace {
 
@@ -78,7 +86,13 @@ const char* mhffn_status_string(int status) {
   }
 }
 
-const char* mhffn_version(void) { return "mhffn-gfx950 0.1"; }
+const char* mhffn_version(void) { return "mhffn-gfx950 0.2"; }
+
+int mhffn_init(void) {
+  for (mhffn::LdsKernelEntry* e = mhffn::lds_kernel_list(); e; e = e->next)
+    if (e->ensure() != hipSuccess) return MHFFN_ERR_LAUNCH;
+  return MHFFN_OK;
+}
 
 size_t mhffn_workspace_bytes(const mhffn_desc* desc, int op) {
   Problem p;

@@ -406,12 +406,9 @@ int chunk_neurons(const Problem& p) { return lds_bytes_for(p, 32) <= kLdsBytesPe
 
 template <int BC>
 int launch_kernels(const Problem& p, BwdF32Args a, bool weights, hipStream_t stream) {
-  static std::atomic<uint64_t> tok_allowed{0}, wgt_allowed{0};
-  if (hipError_t e0 = allow_lds_bytes(reinterpret_cast<const void*>(&bwd_f32_tok_kernel<BC>),
-                                      (int)kLdsBytesPerWorkgroup, tok_allowed); e0 != hipSuccess)
+  if (hipError_t e0 = LdsLimit<&bwd_f32_tok_kernel<BC>, (int)kLdsBytesPerWorkgroup>::ensure(); e0 != hipSuccess)
     return (int)e0;
-  if (hipError_t e0 = allow_lds_bytes(reinterpret_cast<const void*>(&bwd_f32_wgt_kernel<BC>),
-                                      (int)kLdsBytesPerWorkgroup, wgt_allowed); e0 != hipSuccess)
+  if (hipError_t e0 = LdsLimit<&bwd_f32_wgt_kernel<BC>, (int)kLdsBytesPerWorkgroup>::ensure(); e0 != hipSuccess)
     return (int)e0;
   a.chunks_per_sub = (p.de + BC - 1) / BC;
   // token-major kernel (always: it also produces R for the weight-major kernel)

@@ -806,9 +806,7 @@ int launch_variant(const Problem& p, FwdArgs a, const SplitPlan& sp, hipStream_t
   a.tiles_per_split = sp.tiles_per_split;
   a.n_items = a.n_tiles * p.H * sp.n_split;
   const size_t lds = (size_t)kStages * fwd_stage_bytes(DH) + (size_t)p.E * BM * sizeof(float);
-  static std::atomic<uint64_t> lds_allowed{0};
-  if (hipError_t e0 = allow_lds_bytes(reinterpret_cast<const void*>(&fwd_bf16_kernel<DH, TB, NW>),
-                                      (int)kLdsBytesPerWorkgroup, lds_allowed); e0 != hipSuccess)
+  if (hipError_t e0 = LdsLimit<&fwd_bf16_kernel<DH, TB, NW>, (int)kLdsBytesPerWorkgroup>::ensure(); e0 != hipSuccess)
     return (int)e0;
   const dim3 grid((unsigned)xcd_grid_size(a.n_items));
   hipLaunchKernelGGL((fwd_bf16_kernel<DH, TB, NW>), grid, dim3(64 * NW), lds, stream, a);
@@ -826,9 +824,7 @@ int launch_pipe(const Problem& p, FwdArgs a, const SplitPlan& sp, hipStream_t st
   a.tiles_per_split = sp.tiles_per_split;
   a.n_items = a.n_tiles * p.H * sp.n_split;
   const size_t lds = (size_t)3 * kPipeRing + (size_t)p.E * kPipeBM * sizeof(float);
-  static std::atomic<uint64_t> lds_allowed{0};
-  if (hipError_t e0 = allow_lds_bytes(reinterpret_cast<const void*>(&fwd_bf16_flow_kernel),
-                                      (int)kLdsBytesPerWorkgroup, lds_allowed); e0 != hipSuccess)
+  if (hipError_t e0 = LdsLimit<&fwd_bf16_flow_kernel, (int)kLdsBytesPerWorkgroup>::ensure(); e0 != hipSuccess)
     return (int)e0;
   hipLaunchKernelGGL(fwd_bf16_flow_kernel, dim3((unsigned)xcd_grid_size(a.n_items)),
                      dim3(64 * kPipeWaves), lds, stream, a);

@@ -179,9 +179,7 @@ int launch_fwd_f32(const Problem& p, const void* X, const void* Wg, const void* 
   a.n_tiles = (p.N + kTM - 1) / kTM;
   a.n_items = a.n_tiles * p.H;
   const size_t lds = fwd_f32_lds_bytes(p);
-  static std::atomic<uint64_t> lds_allowed{0};
-  if (hipError_t e0 = allow_lds_bytes(reinterpret_cast<const void*>(&fwd_f32_kernel),
-                                      (int)kLdsBytesPerWorkgroup, lds_allowed); e0 != hipSuccess)
+  if (hipError_t e0 = LdsLimit<&fwd_f32_kernel, (int)kLdsBytesPerWorkgroup>::ensure(); e0 != hipSuccess)
     return (int)e0;
   hipLaunchKernelGGL(fwd_f32_kernel, dim3((unsigned)xcd_grid_size(a.n_items)), dim3(kThreads),
                      lds, static_cast<hipStream_t>(stream), a);

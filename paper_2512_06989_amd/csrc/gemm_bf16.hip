@@ -347,9 +347,7 @@ SplitK plan_split_k(int64_t M, int64_t N, int64_t K) {
 
 template <bool A_TR, bool B_TR>
 int launch_form(const TunedGemmArgs& a, hipStream_t stream) {
-  static std::atomic<uint64_t> lds_allowed{0};
-  if (hipError_t e0 = allow_lds_bytes(reinterpret_cast<const void*>(&gemm_bf16_kernel<A_TR, B_TR>),
-                                      kGLdsBytes, lds_allowed); e0 != hipSuccess)
+  if (hipError_t e0 = LdsLimit<&gemm_bf16_kernel<A_TR, B_TR>, kGLdsBytes>::ensure(); e0 != hipSuccess)
     return (int)e0;
   hipLaunchKernelGGL((gemm_bf16_kernel<A_TR, B_TR>), dim3((unsigned)xcd_grid_size(a.n_items)),
                      dim3(kGThreads), kGLdsBytes, stream, a);

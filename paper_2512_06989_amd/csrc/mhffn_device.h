@@ -215,4 +215,28 @@ inline hipError_t allow_lds_bytes(const void* kernel, int bytes, std::atomic<uin
   return e;
 }
 
+// Every kernel that needs more dynamic LDS than the default limit has one entry in a list
+// that is built while the library loads (one static object per kernel instantiation, made by
+// the LdsLimit template below wherever a launcher names the kernel).  A launcher calls
+// LdsLimit<&kernel, bytes>::ensure() before its launch; mhffn_init() walks the whole list, so
+// that after it no launch changes a kernel attribute any more (a caller that records
+// launches into a graph wants that).
+struct LdsKernelEntry {
+  const void* kernel;
+  int bytes;
+  std::atomic<uint64_t> done{0};
+  LdsKernelEntry* next;
+  LdsKernelEntry(const void* k, int b);
+  hipError_t ensure() { return allow_lds_bytes(kernel, bytes, done); }
+};
+LdsKernelEntry*& lds_kernel_list();   // head of the list (api.cpp)
+inline LdsKernelEntry::LdsKernelEntry(const void* k, int b) : kernel(k), bytes(b), next(lds_kernel_list()) {
+  lds_kernel_list() = this;
+}
+template <auto Kernel, int Bytes>
+struct LdsLimit {
+  static inline LdsKernelEntry entry{reinterpret_cast<const void*>(Kernel), Bytes};
+  static hipError_t ensure() { return entry.ensure(); }
+};
+
 }  // namespace mhffn

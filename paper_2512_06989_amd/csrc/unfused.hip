@@ -546,9 +546,7 @@ int run_unfused(const Problem& p, const void* X, const void* Wg, const void* Wu,
 
   // (i) gating weights
   {
-    static std::atomic<uint64_t> lds_allowed{0};
-    if (hipError_t e0 = allow_lds_bytes(reinterpret_cast<const void*>(&gating_kernel<T>),
-                                        (int)kLdsBytesPerWorkgroup, lds_allowed); e0 != hipSuccess)
+    if (hipError_t e0 = LdsLimit<&gating_kernel<T>, (int)kLdsBytesPerWorkgroup>::ensure(); e0 != hipSuccess)
       return (int)e0;
     hipLaunchKernelGGL(gating_kernel<T>, dim3((unsigned)((p.N + kGateTok - 1) / kGateTok), p.H),
                        dim3(256), p.route_mode == 0 ? gating_lds_bytes(p.dh, p.E) : 0, st, a);

@@ -18,7 +18,7 @@ OP_FORWARD, OP_BACKWARD, OP_UNFUSED_FORWARD, OP_UNFUSED_BACKWARD = 0, 1, 2, 3
 OP_MODULE_FORWARD, OP_MODULE_BACKWARD = 4, 5
 EXPORTS = ("mhffn_workspace_bytes", "mhffn_forward", "mhffn_backward", "mhffn_backward_phases",
            "mhffn_reference_unfused", "mhffn_module_forward", "mhffn_module_backward",
-           "mhffn_status_string", "mhffn_version")
+           "mhffn_status_string", "mhffn_version", "mhffn_init")
 
 
 class Desc(ctypes.Structure):
@@ -68,6 +68,8 @@ def load():
     lib.mhffn_status_string.argtypes = [ctypes.c_int]
     lib.mhffn_status_string.restype = ctypes.c_char_p
     lib.mhffn_version.restype = ctypes.c_char_p
+    lib.mhffn_init.argtypes = []
+    lib.mhffn_init.restype = ctypes.c_int
     _lib = lib
     return lib
 
@@ -78,6 +80,13 @@ def status_string(status):
 
 def version():
     return load().mhffn_version().decode()
+
+
+def init():
+    """Raise every kernel's LDS limit on the current device (see mhffn_init)."""
+    rc = load().mhffn_init()
+    if rc != OK:
+        raise MhffnError(rc, "mhffn_init")
 
 
 def _dtype_code(t):

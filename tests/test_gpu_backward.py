@@ -182,3 +182,24 @@ def test_full_size_backward_on_whole_heads(name, heads):
                 "dW_up": got["dW_up"][h:h + 1], "dW_down": got["dW_down"][h:h + 1],
                 "d_route": got["d_route"][h:h + 1]}
         check_all(mine, ref, TOL["bf16"])
+
+
+def test_empty_batch_zero_gradients_and_all_phase_events():
+    """N = 0: the parameter gradients are zero, and every phase event is recorded so that the
+    caller's elapsed-time queries between them succeed."""
+    import torch
+    from bench import HipEvents
+    H, E, de, dh = 2, 3, 64, 128
+    X = torch.empty(0, H * dh, dtype=torch.bfloat16, device="cuda")
+    W = [torch.randn(H, E, de, dh, device="cuda").to(torch.bfloat16) for _ in range(3)]
+    Wr = torch.randn(H, dh, E, device="cuda").to(torch.bfloat16)
+    hip = HipEvents()
+    ev = hip.create(4)
+    out = {k: torch.full_like(t, 3.0) for k, t in zip(("dW_gate", "dW_up", "dW_down", "d_route"), W + [Wr])}
+    out["dX"] = torch.empty_like(X)
+    res = mhffn.backward(X, *W, Wr, X.clone(), out=out, phase_events=ev)
+    torch.cuda.synchronize()
+    for k in ("dW_gate", "dW_up", "dW_down", "d_route"):
+        assert torch.count_nonzero(res[k]) == 0, k
+    for i in range(3):
+        assert hip.elapsed_ms(ev[i], ev[i + 1]) >= 0.0

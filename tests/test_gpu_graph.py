@@ -50,3 +50,36 @@ def test_forward_and_backward_replay_from_a_graph(N):
         for k in names:
             assert torch.equal(G1[k], G0[k]), (rep, k)
         del scratch
+
+
+def test_first_call_may_be_captured_after_init():
+    """mhffn_init raises every kernel's LDS limit, so a shape whose kernels may never have run
+    in this process can be recorded into a graph without an eager call first."""
+    import torch
+    mhffn.init()
+    w = small_workload("graph_init", 300, 3, 5, 192, "bf16", dh=64, backward=True)
+    d = inputs.make_inputs(w, seed=2, with_dy=True)
+    g = device_inputs(d, "bf16")
+    args = [g[k] for k in ("X", "W_gate", "W_up", "W_down", "W_r")]
+    desc = mhffn.make_desc(g["X"], g["W_gate"], mhffn.ROUTE_PARAMS, w.eps)
+    fws = torch.empty(max(mhffn.workspace_bytes(desc, mhffn.OP_FORWARD), 256), dtype=torch.uint8, device="cuda")
+    bws = torch.empty(max(mhffn.workspace_bytes(desc, mhffn.OP_BACKWARD), 256), dtype=torch.uint8, device="cuda")
+    names = ("dX", "dW_gate", "dW_up", "dW_down", "d_route")
+    like = dict(zip(names, args))
+    Y1, G1 = torch.empty_like(g["X"]), {k: torch.empty_like(v) for k, v in like.items()}
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            mhffn.forward(*args, w.eps, out=Y1, workspace=fws)
+            mhffn.backward(*args, g["dY"], w.eps, workspace=bws, out=G1)
+    torch.cuda.current_stream().wait_stream(side)
+    graph.replay()
+    torch.cuda.synchronize()
+    Y0 = mhffn.forward(*args, w.eps, workspace=fws)
+    G0 = mhffn.backward(*args, g["dY"], w.eps, workspace=bws)
+    torch.cuda.synchronize()
+    assert torch.equal(Y1, Y0)
+    for k in names:
+        assert torch.equal(G1[k], G0[k]), k
