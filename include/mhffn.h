@@ -62,7 +62,9 @@ typedef enum {
   MHFFN_ERR_UNSUPPORTED = 3, /* valid problem, but no kernel for it (see below)  */
   MHFFN_ERR_ALIGN = 4,       /* a pointer or stride breaks the alignment rule    */
   MHFFN_ERR_WORKSPACE = 5,   /* workspace NULL or smaller than required          */
-  MHFFN_ERR_LAUNCH = 6       /* HIP reported an error when launching             */
+  MHFFN_ERR_LAUNCH = 6,      /* HIP reported an error when launching             */
+  MHFFN_ERR_STATIC_SCRATCH = 7 /* mhffn_forward_static: the problem needs more scratch
+                                  than MHFFN_STATIC_SCRATCH_BYTES                  */
 } mhffn_status;
 
 typedef enum {
@@ -136,6 +138,27 @@ int mhffn_forward(const mhffn_desc* desc, const void* X, const void* W_gate,
                   const void* W_up, const void* W_down, const void* route,
                   void* Y, void* workspace, size_t workspace_bytes,
                   void* hip_stream);
+
+/* mhffn_forward for callers that cannot allocate device memory or hand over a
+ * workspace: code under HIP graph capture, tight serving loops (decode steps),
+ * harnesses that forbid hipMalloc.  Same arguments, kernels and results as
+ * mhffn_forward, but the scratch that small token counts need (the fp32
+ * partial outputs, see mhffn_workspace_bytes) lies in a device buffer of
+ * MHFFN_STATIC_SCRATCH_BYTES that is part of the library's code object: every
+ * GPU the library runs on holds one copy until the process ends, and the call
+ * allocates nothing (its address on the current device is looked up at the first
+ * use there, or by mhffn_init).  A problem whose mhffn_workspace_bytes exceeds
+ * that size returns MHFFN_ERR_STATIC_SCRATCH and launches nothing (d_head = 128
+ * with up to 64 sub-networks never needs more than 32 MiB, whatever the token
+ * count; the kernels of the other shapes can need up to 64 MiB at a few hundred
+ * to a few thousand tokens and are then refused).  All calls on one GPU share the buffer: it keeps the last call's
+ * partial sums (each call overwrites what it reads, nothing has to start at
+ * zero), and two calls that overlap in time on one GPU (different streams) race
+ * on it -- serialise them, or use mhffn_forward with workspaces of their own. */
+#define MHFFN_STATIC_SCRATCH_BYTES (40u << 20)
+int mhffn_forward_static(const mhffn_desc* desc, const void* X, const void* W_gate,
+                         const void* W_up, const void* W_down, const void* route,
+                         void* Y, void* hip_stream);
 
 /* Fused, recompute-based backward (appendix algorithms "Backward (dQ,dR)" and
  * "Backward (dK,dU,dV)"; the derivative through eq:routing is taken here too).

@@ -6,6 +6,33 @@
 #include "mhffn_device.h"
 #include "mhffn_internal.h"
 
+#include <mutex>
+
+// Scratch of mhffn_forward_static: one copy per GPU that the library runs on, held until
+// the process ends.  In host code this name is only a handle for hipGetSymbolAddress, never
+// a device address; kernels get the per-device address resolved below.
+static __device__ __align__(256) unsigned char scratch[MHFFN_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+// Address of `scratch` on the calling thread's current device, resolved once per device.
+int static_scratch_address(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return MHFFN_ERR_LAUNCH;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return MHFFN_ERR_LAUNCH;
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return MHFFN_OK;
+}
+}  // namespace
+
 namespace mhffn {
 LdsKernelEntry*& lds_kernel_list() {
   static LdsKernelEntry* head = nullptr;   // constant-initialised: safe during static initialisation
@@ -82,6 +109,7 @@ const char* mhffn_status_string(int status) {
     case MHFFN_ERR_ALIGN: return "pointer or stride not 16-byte aligned (workspace: 256)";
     case MHFFN_ERR_WORKSPACE: return "workspace missing or too small";
     case MHFFN_ERR_LAUNCH: return "HIP kernel launch failed";
+    case MHFFN_ERR_STATIC_SCRATCH: return "problem needs more scratch than the library's static buffer holds";
     default: return "unknown status";
   }
 }
@@ -91,7 +119,8 @@ const char* mhffn_version(void) { return "mhffn-gfx950 0.2"; }
 int mhffn_init(void) {
   for (mhffn::LdsKernelEntry* e = mhffn::lds_kernel_list(); e; e = e->next)
     if (e->ensure() != hipSuccess) return MHFFN_ERR_LAUNCH;
-  return MHFFN_OK;
+  void* p = nullptr;
+  return static_scratch_address(&p);
 }
 
 size_t mhffn_workspace_bytes(const mhffn_desc* desc, int op) {
@@ -116,9 +145,12 @@ size_t mhffn_workspace_bytes(const mhffn_desc* desc, int op) {
   }
 }
 
-int mhffn_forward(const mhffn_desc* desc, const void* X, const void* W_gate, const void* W_up,
-                  const void* W_down, const void* route, void* Y, void* workspace,
-                  size_t workspace_bytes, void* hip_stream) {
+namespace {
+// Common part of mhffn_forward and mhffn_forward_static.  `static_scratch`: take the scratch
+// from the library's static device buffer instead of the caller's workspace.
+int forward_impl(const mhffn_desc* desc, const void* X, const void* W_gate, const void* W_up,
+                 const void* W_down, const void* route, void* Y, void* workspace,
+                 size_t workspace_bytes, void* hip_stream, bool static_scratch) {
   Problem p;
   int rc = check_desc(desc, &p);
   if (rc) return rc;
@@ -135,14 +167,38 @@ int mhffn_forward(const mhffn_desc* desc, const void* X, const void* W_gate, con
   if (p.N == 0) return MHFFN_OK;
   if (desc->dtype == MHFFN_BF16) {
     // non-zero only for small N, where the intermediate dimension is split over workgroups
-    rc = check_workspace(mhffn::fwd_bf16_workspace_bytes(p), workspace, workspace_bytes);
-    if (rc) return rc;
+    const size_t need = mhffn::fwd_bf16_workspace_bytes(p);
+    if (static_scratch) {
+      if (need > (size_t)MHFFN_STATIC_SCRATCH_BYTES) return MHFFN_ERR_STATIC_SCRATCH;
+      workspace = nullptr;
+      if (need) {
+        rc = static_scratch_address(&workspace);
+        if (rc) return rc;
+      }
+    } else {
+      rc = check_workspace(need, workspace, workspace_bytes);
+      if (rc) return rc;
+    }
   }
   const int e = (desc->dtype == MHFFN_BF16)
                     ? mhffn::launch_fwd_bf16(p, X, W_gate, W_up, W_down, route, Y, workspace,
                                              hip_stream)
                     : mhffn::launch_fwd_f32(p, X, W_gate, W_up, W_down, route, Y, hip_stream);
   return e == 0 ? MHFFN_OK : MHFFN_ERR_LAUNCH;
+}
+}  // namespace
+
+int mhffn_forward(const mhffn_desc* desc, const void* X, const void* W_gate, const void* W_up,
+                  const void* W_down, const void* route, void* Y, void* workspace,
+                  size_t workspace_bytes, void* hip_stream) {
+  return forward_impl(desc, X, W_gate, W_up, W_down, route, Y, workspace, workspace_bytes,
+                      hip_stream, false);
+}
+
+int mhffn_forward_static(const mhffn_desc* desc, const void* X, const void* W_gate,
+                         const void* W_up, const void* W_down, const void* route, void* Y,
+                         void* hip_stream) {
+  return forward_impl(desc, X, W_gate, W_up, W_down, route, Y, nullptr, 0, hip_stream, true);
 }
 
 int mhffn_backward(const mhffn_desc* desc, const void* X, const void* W_gate, const void* W_up,

@@ -18,7 +18,7 @@ OP_FORWARD, OP_BACKWARD, OP_UNFUSED_FORWARD, OP_UNFUSED_BACKWARD = 0, 1, 2, 3
 OP_MODULE_FORWARD, OP_MODULE_BACKWARD = 4, 5
 EXPORTS = ("mhffn_workspace_bytes", "mhffn_forward", "mhffn_backward", "mhffn_backward_phases",
            "mhffn_reference_unfused", "mhffn_module_forward", "mhffn_module_backward",
-           "mhffn_status_string", "mhffn_version", "mhffn_init")
+           "mhffn_status_string", "mhffn_version", "mhffn_init", "mhffn_forward_static")
 
 
 class Desc(ctypes.Structure):
@@ -54,6 +54,8 @@ def load():
     lib.mhffn_workspace_bytes.restype = sz
     lib.mhffn_forward.argtypes = [dp] + [vp] * 6 + [vp, sz, vp]
     lib.mhffn_forward.restype = ctypes.c_int
+    lib.mhffn_forward_static.argtypes = [dp] + [vp] * 6 + [vp]
+    lib.mhffn_forward_static.restype = ctypes.c_int
     lib.mhffn_backward.argtypes = [dp] + [vp] * 11 + [vp, sz, vp]
     lib.mhffn_backward.restype = ctypes.c_int
     lib.mhffn_backward_phases.argtypes = [dp] + [vp] * 11 + [vp, sz, vp, ctypes.POINTER(vp),
@@ -193,6 +195,19 @@ def forward(X, W_gate, W_up, W_down, route, eps=1e-6, route_mode=ROUTE_PARAMS, o
     if rc != OK:
         raise MhffnError(rc, "mhffn_forward")
     return Y
+
+
+def forward_static(X, W_gate, W_up, W_down, route, out, eps=1e-6, route_mode=ROUTE_PARAMS,
+                   stream=None):
+    """mhffn_forward_static: the fused forward into the caller's `out`, with the scratch in the
+    library's static device buffer.  Nothing is allocated here either."""
+    _check_params(X, W_gate, W_up, W_down, route, route_mode)
+    d = make_desc(X, W_gate, route_mode, eps, out)
+    rc = load().mhffn_forward_static(ctypes.byref(d), _p(X), _p(W_gate), _p(W_up), _p(W_down),
+                                     _p(route), _p(out), _stream(stream))
+    if rc != OK:
+        raise MhffnError(rc, "mhffn_forward_static")
+    return out
 
 
 def _grad_outputs(X, W_gate, W_up, W_down, route, want, out, ld_x):
