@@ -63,6 +63,21 @@ class HipEvents:
         return float(ms.value)
 
 
+def load_traffic(workload, forward_only):
+    """{kernel key: HBM bytes per launch} for `workload` from profiles/hbm_traffic.txt
+    (lines: workload step kernel-key read-bytes written-bytes source-file)."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
+    out = {}
+    if not os.path.exists(path):
+        return out
+    step = "fwd" if forward_only else "fwdbwd"
+    for line in open(path):
+        f = line.split()
+        if len(f) >= 5 and not line.startswith("#") and f[0] == workload and f[1] == step:
+            out[f[2]] = float(f[3]) + float(f[4])
+    return out
+
+
 def cpu_baseline(w, d, budget_heads=16, budget_tokens=6144):
     """The fp64 oracle, as it stands, on a bounded sample of the workload:
     `budget_heads` whole heads x the first `budget_tokens` tokens, forward + backward."""
@@ -89,6 +104,80 @@ def cpu_baseline(w, d, budget_heads=16, budget_tokens=6144):
                   "(%.1f s; 11 algorithmic units counted, 14 executed)" % (hs, n, t2 - t0),
         "fwd_s": round(t1 - t0, 3), "bwd_s": round(t2 - t1, 3),
     }
+
+
+def time_config(hip, name, tokens=0, forward_only=True, steps=10, warmup=2):
+    """One compact row for a configuration other than the headline one: average kernel
+    durations over `steps` runs (HIP events on the launch stream), outside the headline's
+    timed region."""
+    import torch
+    from paper_2512_06989_amd import inputs, mhffn
+    from paper_2512_06989_amd.device import device_inputs
+    w = inputs.WORKLOADS[name]
+    if tokens:
+        w = w.with_tokens(tokens)
+    d = inputs.make_inputs(w, seed=0, with_dy=not forward_only)
+    g = device_inputs(d, w.dtype)
+    a = [g[k] for k in ("X", "W_gate", "W_up", "W_down", "W_r")]
+    desc = mhffn.make_desc(g["X"], g["W_gate"], mhffn.ROUTE_PARAMS, w.eps)
+    fws_b = mhffn.workspace_bytes(desc, mhffn.OP_FORWARD)
+    bws_b = 0 if forward_only else mhffn.workspace_bytes(desc, mhffn.OP_BACKWARD)
+    fws = torch.empty(max(fws_b, 256), dtype=torch.uint8, device="cuda")
+    bws = torch.empty(max(bws_b, 256), dtype=torch.uint8, device="cuda")
+    Y = torch.empty_like(g["X"])
+    grads = None if forward_only else {k: torch.empty_like(v) for k, v in zip(
+        ("dX", "dW_gate", "dW_up", "dW_down", "d_route"), a)}
+    hbm_bound = w.n_tokens <= 128
+    # a weight-streaming shape must not be served from the 256 MB Infinity Cache
+    wsets = [a[1:4]] + ([[t.clone() for t in a[1:4]] for _ in range(7)] if hbm_bound else [])
+    stream = torch.cuda.current_stream().cuda_stream
+    evs = [hip.create(3) for _ in range(warmup + steps)]
+    for i, ev in enumerate(evs):     # back to back, as in a serving or training loop
+        ws_i = wsets[i % len(wsets)]
+        hip.record(ev[0], stream)
+        mhffn.forward(a[0], *ws_i, a[4], w.eps, out=Y, workspace=fws)
+        hip.record(ev[1], stream)
+        if not forward_only:
+            mhffn.backward(*a, g["dY"], w.eps, workspace=bws, out=grads)
+        hip.record(ev[2], stream)
+    torch.cuda.synchronize()
+    t_f = [hip.elapsed_ms(ev[0], ev[1]) for ev in evs[warmup:]]
+    t_b = [hip.elapsed_ms(ev[1], ev[2]) for ev in evs[warmup:]]
+    f_ms, b_ms = sum(t_f) / len(t_f), sum(t_b) / len(t_b)
+    unit = w.unit_flops()
+    row = {"workload": w.name, "n_tokens": w.n_tokens, "d_model": w.d_model, "n_sub": w.n_sub,
+           "step": "forward" if forward_only else "forward + backward",
+           "forward_ms": round(f_ms, 5),
+           "forward_workspace_bytes": fws_b}
+    if hbm_bound:
+        nbytes = (3 * w.d_model * w.d_ff + w.d_model * w.n_sub + 2 * w.n_tokens * w.d_model) * 2
+        gbs = nbytes / (f_ms * 1e-3) / 1e9
+        row.update({"bound": "hbm", "forward_GBps": round(gbs, 1), "frac": round(gbs / PEAK_HBM_GBS, 4),
+                    "algorithmic_bytes": nbytes})
+    else:
+        tf = 3.0 * unit / (f_ms * 1e-3) / 1e12
+        row.update({"bound": "mfma", "forward_TFLOPs": round(tf, 1), "frac": round(tf / PEAK_BF16_TFLOPS, 4)})
+    if not forward_only:
+        tb = 8.0 * unit / (b_ms * 1e-3) / 1e12
+        ts = 11.0 * unit / ((f_ms + b_ms) * 1e-3) / 1e12
+        row.update({"backward_ms": round(b_ms, 5), "backward_TFLOPs": round(tb, 1),
+                    "backward_frac": round(tb / PEAK_BF16_TFLOPS, 4),
+                    "step_TFLOPs": round(ts, 1), "step_frac": round(ts / PEAK_BF16_TFLOPS, 4),
+                    "backward_workspace_bytes": bws_b})
+    row["tokens_per_s"] = round(w.n_tokens / ((f_ms + (0 if forward_only else b_ms)) * 1e-3), 1)
+    return row
+
+
+def allocator_high_water(fn):
+    """Peak of torch's device allocator above its level before `fn` (buffers that fn allocates
+    itself: the binding's workspace and outputs)."""
+    import torch
+    torch.cuda.synchronize()
+    torch.cuda.reset_peak_memory_stats()
+    before = torch.cuda.memory_allocated()
+    fn()
+    torch.cuda.synchronize()
+    return int(torch.cuda.max_memory_allocated() - before)
 
 
 def module_bench(args, w):
@@ -220,6 +309,9 @@ def main():
                     help="skip the unfused GPU baseline comparison")
     ap.add_argument("--forward-only", action="store_true",
                     help="time the forward alone (step = forward); for profiling")
+    ap.add_argument("--no-configs", dest="configs", action="store_false",
+                    help="skip the compact rows for the other configurations (128M forward, 370M "
+                         "forward + backward, inference sweep)")
     ap.add_argument("--module", action="store_true",
                     help="time the whole module (W_in and W_out projections around the path) "
                          "instead; prints its own JSON line")
@@ -318,11 +410,10 @@ def main():
                     "bwd_route": "bwd_route_*"}
 
     # HBM bytes per launch measured with rocprofv3 (FETCH_SIZE + WRITE_SIZE, each scaled by
-    # what the counter reads for a 256 MiB copy); from profiles/mhffn_fwd_bwd_1p3b.md and
-    # profiles/mhffn_fwd_sweep_1p3b.md.  Only valid for the workload they were taken on.
-    measured_traffic = {}
-    if w.name == "1p3b_fwdbwd" and not args.forward_only:
-        measured_traffic = {"fwd": 273.6e6, "bwd_tok": 496.3e6, "bwd_wgt": 453.1e6}
+    # what the counter reads for a 256 MiB copy): read from profiles/hbm_traffic.txt, which is
+    # written together with the profile summaries.  Only valid for the workload and step they
+    # were taken on; null where there is no measurement.
+    measured_traffic = load_traffic(w.name, args.forward_only)
 
     def roof(k):
         if k == "fwd" and hbm_bound:
@@ -402,6 +493,28 @@ def main():
     if not args.forward_only:
         out["roofline_bwd_tok"] = roof("bwd_tok")
         out["roofline_bwd_wgt"] = roof("bwd_wgt")
+    if args.unfused and not args.forward_only:
+        # allocator high-water marks of one call each, outputs and scratch allocated by the
+        # binding (what a caller without buffers of its own pays)
+        out["peak_activation_bytes"]["allocator_high_water"] = {
+            "fused_forward": allocator_high_water(lambda: mhffn.forward(X, Wg, Wu, Wd, Wr, w.eps)),
+            "unfused_forward": allocator_high_water(lambda: mhffn.reference_unfused(X, Wg, Wu, Wd, Wr, w.eps)),
+            "fused_forward_backward": allocator_high_water(
+                lambda: (mhffn.forward(X, Wg, Wu, Wd, Wr, w.eps), mhffn.backward(X, Wg, Wu, Wd, Wr, dY, w.eps))),
+            "unfused_forward_backward": allocator_high_water(
+                lambda: mhffn.reference_unfused(X, Wg, Wu, Wd, Wr, w.eps, dY=dY)),
+        }
+    if args.configs and w.name == "1p3b_fwdbwd" and not args.forward_only and not args.tokens:
+        # the other configurations, a few seconds in all, outside the timed region above
+        del g, X, Y, dY, grads, ws, fwd_ws
+        torch.cuda.empty_cache()
+        out["configs"] = [
+            time_config(hip, "128m_fwd"),
+            time_config(hip, "370m_fwdbwd", forward_only=False),
+            time_config(hip, "1p3b_sweep", tokens=64, steps=40, warmup=8),
+            time_config(hip, "1p3b_sweep", tokens=1024, steps=20, warmup=4),
+            time_config(hip, "1p3b_sweep", tokens=32768),
+        ]
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, d)
     print(json.dumps(out))
