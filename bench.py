@@ -168,6 +168,47 @@ def time_config(hip, name, tokens=0, forward_only=True, steps=10, warmup=2):
     return row
 
 
+def mfma_calibration(hip, launches=40, iters=2000):
+    """Sustained rate of bare bf16 MFMA loops on this machine (calibration kernels of
+    libmhffn_calib.so, about 0.15 s of back-to-back launches per mode after as much warm-up):
+    with constant operands and with fresh pseudo-random operands for every product.  The
+    second is what power management leaves of the published peak for data like the workload's."""
+    import torch
+    from paper_2512_06989_amd import build as lib_build
+    if not os.path.exists(lib_build.CALIB_LIB):
+        return None
+    lib = ctypes.CDLL(lib_build.CALIB_LIB)
+    lib.mhffn_calib_mfma_launch.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_void_p,
+                                            ctypes.c_void_p, ctypes.c_void_p]
+    lib.mhffn_calib_mfma_flops.restype = ctypes.c_double
+    lib.mhffn_calib_mfma_flops.argtypes = [ctypes.c_int, ctypes.c_int]
+    n_wg = torch.cuda.get_device_properties(0).multi_processor_count
+    sink = torch.empty(n_wg * 512, dtype=torch.float32, device="cuda")
+    clocks = torch.zeros(n_wg * 16, dtype=torch.int64, device="cuda")
+    stream = torch.cuda.current_stream().cuda_stream
+    out = {}
+    for mode, key in ((0, "constant_operands"), (1, "random_operands")):
+        def launch():
+            rc = lib.mhffn_calib_mfma_launch(mode, n_wg, iters, sink.data_ptr(), clocks.data_ptr(), stream)
+            if rc != 0:
+                raise RuntimeError("calibration launch failed: %d" % rc)
+        for _ in range(launches):
+            launch()
+        ev = hip.create(2)
+        hip.record(ev[0], stream)
+        for _ in range(launches):
+            launch()
+        hip.record(ev[1], stream)
+        torch.cuda.synchronize()
+        ms = hip.elapsed_ms(ev[0], ev[1])
+        c = clocks.cpu().numpy().reshape(-1, 2)
+        tf = lib.mhffn_calib_mfma_flops(n_wg, iters) * launches / (ms * 1e-3) / 1e12
+        out[key] = {"TFLOPs": round(tf, 1), "frac_of_peak": round(tf / PEAK_BF16_TFLOPS, 4),
+                    "clock_GHz": round(float(c[:, 0].sum()) / (float(c[:, 1].sum()) * 10.0), 3)}
+    out["kernel"] = "v_mfma_f32_32x32x16_bf16 back to back, 2 waves per SIMD on %d CUs, no memory traffic" % n_wg
+    return out
+
+
 def allocator_high_water(fn):
     """Peak of torch's device allocator above its level before `fn` (buffers that fn allocates
     itself: the binding's workspace and outputs)."""
@@ -310,8 +351,8 @@ def main():
     ap.add_argument("--forward-only", action="store_true",
                     help="time the forward alone (step = forward); for profiling")
     ap.add_argument("--no-configs", dest="configs", action="store_false",
-                    help="skip the compact rows for the other configurations (128M forward, 370M "
-                         "forward + backward, inference sweep)")
+                    help="skip the MFMA calibration and the compact rows for the other configurations "
+                         "(128M forward, 370M forward + backward, inference sweep)")
     ap.add_argument("--module", action="store_true",
                     help="time the whole module (W_in and W_out projections around the path) "
                          "instead; prints its own JSON line")
@@ -504,6 +545,11 @@ def main():
             "unfused_forward_backward": allocator_high_water(
                 lambda: mhffn.reference_unfused(X, Wg, Wu, Wd, Wr, w.eps, dY=dY)),
         }
+    if args.configs:
+        # context for the roofline fractions: what bare MFMA loops sustain on this machine
+        cal = mfma_calibration(hip)
+        if cal:
+            out["mfma_sustained"] = cal
     if args.configs and w.name == "1p3b_fwdbwd" and not args.forward_only and not args.tokens:
         # the other configurations, a few seconds in all, outside the timed region above
         del g, X, Y, dY, grads, ws, fwd_ws
