@@ -33,6 +33,35 @@
 namespace mhffn {
 namespace {
 
+// Tile layout of the kernels in this file with 32x32x16 products (token-major kernel, gating
+// scratch, routing-gradient kernel).  d_h = 128 and 256: the general swizzled tile.  d_h = 64
+// (rows of 128 bytes, two rows per 256-byte line): the eight chunks of a row are permuted by
+//     s(row) = b1 | b2 << 1 | (b1 ^ b3) << 2        (b_i = bit i of the row number),
+// with which the row reads (one row per lane, lane groups of a 16-byte read) and the
+// transposing reads (rows 4g + i/4 and + 8 in the two 32-byte windows of a lane half) are
+// both free of bank conflicts; with the general d_h = 64 layout the transposing reads of this
+// geometry took twice their cycles.
+template <int DH>
+__device__ __forceinline__ int btile_off(int row, int chunk) {
+  if constexpr (DH == 64) {
+    const int s = ((row >> 1) & 1) | (((row >> 2) & 1) << 1) | ((((row >> 1) ^ (row >> 3)) & 1) << 2);
+    return row * 128 + ((chunk ^ s) << 4);
+  } else {
+    return tile_off_dh<DH>(row, chunk);
+  }
+}
+template <int DH>
+__device__ __forceinline__ int btile_off8(int row, int col) {
+  return btile_off<DH>(row, col >> 3) + ((col & 4) << 1);
+}
+template <int DH>
+__device__ __forceinline__ bf16x8 btile_read_tr(const unsigned char* tile, int r0, int c0, int lane) {
+  const int li = lane & 15;
+  const int row = r0 + (li >> 2);
+  const int col = c0 + 16 * ((lane >> 4) & 1) + 4 * (li & 3);
+  return join_tr(lds_read_tr16(tile + btile_off8<DH>(row, col)), lds_read_tr16(tile + btile_off8<DH>(row + 8, col)));
+}
+
 #define MHFFN_SB() __builtin_amdgcn_sched_barrier(0)
 
 constexpr int kDh = 128;
@@ -179,11 +208,11 @@ __global__ __launch_bounds__(64 * NW) void bwd_tok_kernel(BwdArgs a) {
     const uint16_t* Wr = reinterpret_cast<const uint16_t*>(a.route) + (size_t)h * DH * E;
     for (int idx = tid; idx < DH * E; idx += THREADS) {
       const int j = idx / E, e = idx - j * E;
-      *reinterpret_cast<uint16_t*>(scratch + tile_off_dh<DH>(e, j >> 3) + (j & 7) * 2) = Wr[idx];
+      *reinterpret_cast<uint16_t*>(scratch + btile_off<DH>(e, j >> 3) + (j & 7) * 2) = Wr[idx];
     }
     for (int idx = tid; idx < (32 * EB - E) * DH; idx += THREADS) {
       const int e = E + idx / DH, j = idx % DH;
-      *reinterpret_cast<uint16_t*>(scratch + tile_off_dh<DH>(e, j >> 3) + (j & 7) * 2) = 0;
+      *reinterpret_cast<uint16_t*>(scratch + btile_off<DH>(e, j >> 3) + (j & 7) * 2) = 0;
     }
     __syncthreads();
     float zsum[TB];
@@ -196,7 +225,7 @@ __global__ __launch_bounds__(64 * NW) void bwd_tok_kernel(BwdArgs a) {
           f32x16 acc = {0};
 #pragma unroll
           for (int ks = 0; ks < KS; ++ks) {
-            const bf16x8 af = *reinterpret_cast<const bf16x8*>(scratch + tile_off_dh<DH>(32 * eb + r, 2 * ks + g));
+            const bf16x8 af = *reinterpret_cast<const bf16x8*>(scratch + btile_off<DH>(32 * eb + r, 2 * ks + g));
             acc = mfma32(af, q[tb][ks], acc);
           }
 #pragma unroll
@@ -253,7 +282,7 @@ __global__ __launch_bounds__(64 * NW) void bwd_tok_kernel(BwdArgs a) {
     for (int i = 0; i < CH; ++i) {
       const int chunk = tid + THREADS * i;
       if (!kAllLoad && chunk >= CHUNKS) continue;
-      const int off = tile_off_dh<DH>(chunk / CPR, chunk % CPR);
+      const int off = btile_off<DH>(chunk / CPR, chunk % CPR);
       *reinterpret_cast<u32x4*>(st + off) = kreg[i];
       *reinterpret_cast<u32x4*>(st + kTileBytes + off) = ureg[i];
       *reinterpret_cast<u32x4*>(st + 2 * kTileBytes + off) = vreg[i];
@@ -324,7 +353,7 @@ __global__ __launch_bounds__(64 * NW) void bwd_tok_kernel(BwdArgs a) {
       bf16x8 op[NOP];
       auto issue = [&](auto C_) {
         constexpr int c = decltype(C_)::value, ks = c / 3, which = c % 3;
-        op[c] = lds_read_b128_untracked<which * kTileBytes>(sto + tile_off_dh<DH>(r, 2 * ks + g));
+        op[c] = lds_read_b128_untracked<which * kTileBytes>(sto + btile_off<DH>(r, 2 * ks + g));
       };
       static_for<0, 6>(issue);
       static_for<0, NOP>([&](auto C_) {
@@ -384,8 +413,8 @@ __global__ __launch_bounds__(64 * NW) void bwd_tok_kernel(BwdArgs a) {
       auto issue2 = [&](auto C_) {
         constexpr int c = decltype(C_)::value, which = c & 1, jb = (c >> 1) % JB, t2 = c / (2 * JB);
         constexpr int OFF = which * kTileBytes + t2 * 16 * 2 * DH;   // 16 rows further: same swizzle
-        lo[c] = lds_read_tr16_untracked<OFF>(sto + tile_off8_dh<DH>(trow, 32 * jb + tcol));
-        hi[c] = lds_read_tr16_untracked<OFF>(sto + tile_off8_dh<DH>(trow + 8, 32 * jb + tcol));
+        lo[c] = lds_read_tr16_untracked<OFF>(sto + btile_off8<DH>(trow, 32 * jb + tcol));
+        hi[c] = lds_read_tr16_untracked<OFF>(sto + btile_off8<DH>(trow + 8, 32 * jb + tcol));
       };
       static_for<0, W2>(issue2);
       static_for<0, NI>([&](auto C_) {
@@ -883,10 +912,24 @@ size_t wgt_split_bytes(const Problem& p) {
 // tiles for the gradient products), written plainly: the q / dY tiles go through
 // registers into two alternating LDS buffers, one barrier per block.  At d_h = 256 the resident operands (96) and the accumulators
 // (192 registers) leave room for one wave per SIMD only; the launcher then uses
-// workgroups of 4 waves.  For d_h >= 128 MFMA row m of a 16-token block is token rho(m) as in
-// bwd_wgt16_kernel (conflict-free row reads); at d_h = 64, where two rows share a 256-byte
-// line, it is token m.
+// workgroups of 4 waves.  Tile layout as in bwd_wgt16_kernel, for the same two kinds of reads:
+// the 16-byte chunks of a 256-byte line are permuted by 2 (row % 8) at d_h = 256 (a row is two
+// lines), the eight chunks of a 128-byte row by row & 6 at d_h = 64 (two rows share a line);
+// tokens stay in MFMA row order.  Row reads and transposing reads are then both free of bank
+// conflicts (with the general tile layout of the other kernels the row reads at d_h = 64 and
+// the transposing reads at d_h = 256 took twice their cycles in this lane geometry).
 // ---------------------------------------------------------------------------
+template <int DH>
+__device__ __forceinline__ int wdh_off(int row, int chunk) {
+  static_assert(DH == 64 || DH == 256, "head widths of this kernel");
+  if constexpr (DH == 64) return row * 128 + ((chunk ^ (row & 6)) << 4);
+  else return row * 512 + ((chunk & ~15) << 4) + (((chunk & 15) ^ ((row & 7) << 1)) << 4);
+}
+template <int DH>
+__device__ __forceinline__ int wdh_off8(int row, int col) {
+  return wdh_off<DH>(row, col >> 3) + ((col & 4) << 1);
+}
+
 constexpr int kDhWindow = 6;   // operands in flight ahead of the one being consumed
 // last stream position issued when item c is consumed; LDS read instructions behind the
 // positions after c up to there (a row operand is one read, a transposed window two)
@@ -910,7 +953,6 @@ __global__ __launch_bounds__(64 * NW, DH == 64 ? 2 : 1) void bwd_wgt_dh_kernel(B
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];   // 2 x (q tile | dY tile)
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int cn = lane & 15, gq = lane >> 4;
-  auto rho = [](int m) { return DH >= 128 ? ((m & 9) | ((m & 2) << 1) | ((m & 4) >> 1)) : m; };
   const int nblk = a.E * a.de / 16;              // 16-neuron blocks per head
   const int wg_per_head = (nblk + NW - 1) / NW;
   const int64_t item_s = xcd_work_item(blockIdx.x, a.n_items);
@@ -970,7 +1012,7 @@ __global__ __launch_bounds__(64 * NW, DH == 64 ? 2 : 1) void bwd_wgt_dh_kernel(B
     for (int tb = 0; tb < 2; ++tb)
 #pragma unroll
       for (int v = 0; v < 4; ++v) {
-        const int64_t t = b * 32 + 16 * tb + rho(4 * gq + v);
+        const int64_t t = b * 32 + 16 * tb + 4 * gq + v;
         rnext[S][tb][v] = (t < N) ? Rw[t] : 0.f;
       }
   };
@@ -981,7 +1023,7 @@ __global__ __launch_bounds__(64 * NW, DH == 64 ? 2 : 1) void bwd_wgt_dh_kernel(B
     for (int i = 0; i < CH; ++i) {
       const int chunk = tid + THREADS * i;
       if (!kAllLoad && chunk >= CHUNKS) continue;
-      const int off = tile_off_dh<DH>(chunk / CPR, chunk % CPR);
+      const int off = wdh_off<DH>(chunk / CPR, chunk % CPR);
       *reinterpret_cast<u32x4*>(dst + off) = xreg[S][i];
       *reinterpret_cast<u32x4*>(dst + kTileBytes + off) = yreg[S][i];
     }
@@ -1008,9 +1050,9 @@ __global__ __launch_bounds__(64 * NW, DH == 64 ? 2 : 1) void bwd_wgt_dh_kernel(B
     // All LDS operands of the step form one stream, issued untracked kDhWindow items ahead
     // of their use with counted waits (the compiler, left alone, waits for each read right
     // after issuing it):
-    //   items 0 .. NA-1   rows of the q / dY tiles: token row 16tb + rho(cn), columns 32ks + 8gq ..
+    //   items 0 .. NA-1   rows of the q / dY tiles: token row 16tb + cn, columns 32ks + 8gq ..
     //   items NA ..       transposed windows, dY^T and q^T alternating: lane (cn, gq) points at
-    //                     token row rho(4gq + cn/4) (and + 16), columns 16jb + 4(cn%4) ..
+    //                     token row 4gq + cn/4 (and + 16), columns 16jb + 4(cn%4) ..
     const unsigned qb = lds_addr_of(qt);
     constexpr int NA = 4 * KS, NTOT = NA + 2 * JB;
     bf16x8 opa[NA];
@@ -1019,10 +1061,10 @@ __global__ __launch_bounds__(64 * NW, DH == 64 ? 2 : 1) void bwd_wgt_dh_kernel(B
       constexpr int P = decltype(P_)::value;
       if constexpr (P < NA) {
         constexpr int tb = P / (2 * KS), ks = (P / 2) % KS, which = P & 1;   // 0: q, 1: dY
-        opa[P] = lds_read_b128_untracked<which * kTileBytes>(qb + tile_off_dh<DH>(16 * tb + rho(cn), 4 * ks + gq));
+        opa[P] = lds_read_b128_untracked<which * kTileBytes>(qb + wdh_off<DH>(16 * tb + cn, 4 * ks + gq));
       } else {
         constexpr int J = P - NA, jb = J >> 1, TO = (J & 1) ? 0 : kTileBytes;  // even: dY^T, odd: q^T
-        const unsigned ad = qb + tile_off8_dh<DH>(rho(4 * gq + (cn >> 2)), 16 * jb + 4 * (cn & 3));
+        const unsigned ad = qb + wdh_off8<DH>(4 * gq + (cn >> 2), 16 * jb + 4 * (cn & 3));
         xlo[J] = lds_read_tr16_untracked<TO>(ad);
         xhi[J] = lds_read_tr16_untracked<TO + 16 * 2 * DH>(ad);   // 16 rows further: same swizzle
       }
@@ -1046,7 +1088,7 @@ __global__ __launch_bounds__(64 * NW, DH == 64 ? 2 : 1) void bwd_wgt_dh_kernel(B
         Ad[tb] = mfma16(opa[C], Vf[ks], Ad[tb]);
       }
     });
-    // element (tb, v): token 16tb + rho(4gq + v), neuron cn; it becomes contraction slot
+    // element (tb, v): token 16tb + 4gq + v, neuron cn; it becomes contraction slot
     // 4tb + v of the gradient products
     float ag[8], dm[8], dn[8];
 #pragma unroll
@@ -1171,7 +1213,7 @@ __global__ __launch_bounds__(256) void bwd_route_partial_kernel(BwdArgs a) {
       const int64_t t = tok0 + chunk / CPR;
       u32x4 v = {0, 0, 0, 0};
       if (t < N) v = *reinterpret_cast<const u32x4*>(a.X + t * a.ldx + h * DH + (chunk % CPR) * 8);
-      *reinterpret_cast<u32x4*>(tile + tile_off_dh<DH>(chunk / CPR, chunk % CPR)) = v;
+      *reinterpret_cast<u32x4*>(tile + btile_off<DH>(chunk / CPR, chunk % CPR)) = v;
     }
     // dp operands
     bf16x8 bp[EB][2];
@@ -1197,7 +1239,7 @@ __global__ __launch_bounds__(256) void bwd_route_partial_kernel(BwdArgs a) {
     for (int t2 = 0; t2 < 2; ++t2) {
 #pragma unroll
       for (int jb = 0; jb < JB; ++jb) {
-        const bf16x8 qT = tile_read_tr_dh<DH>(tile, 16 * t2 + 4 * g, 32 * jb, lane);
+        const bf16x8 qT = btile_read_tr<DH>(tile, 16 * t2 + 4 * g, 32 * jb, lane);
 #pragma unroll
         for (int eb = 0; eb < EB; ++eb) acc[eb][jb] = mfma32(qT, bp[eb][t2], acc[eb][jb]);
       }
