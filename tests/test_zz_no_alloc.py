@@ -25,9 +25,11 @@ def test_two_calls_in_a_row_second_one_smaller():
         assert 0 < mhffn.workspace_bytes(d, mhffn.OP_FORWARD) <= (40 << 20)
         want = mhffn.forward(*a, w.eps)
         got = torch.full_like(g["X"], 7.0)
-        before = torch.cuda.memory_allocated()
+        # number of allocation requests the caching allocator has served so far (monotonic: a
+        # tensor freed by the garbage collector in between does not change it)
+        before = torch.cuda.memory_stats()["allocation.all.allocated"]
         mhffn.forward_static(*a, got, w.eps)
-        assert torch.cuda.memory_allocated() == before
+        assert torch.cuda.memory_stats()["allocation.all.allocated"] == before
         torch.cuda.synchronize()
         assert torch.equal(got, want), N
 
