@@ -757,14 +757,341 @@ __global__ __launch_bounds__(64 * kPipeWaves) void fwd_bf16_flow_kernel(FwdArgs 
   }
 }
 
+// ---------------------------------------------------------------------------
+// Decode-sized inputs at d_h = 128 (at most 32 * NB tokens, NB in {1, 2, 4}): the launch is a
+// weight-streaming problem (every weight byte is used once by a handful of tokens) and its
+// floor is the time the memory system needs to deliver the weights.  About one workgroup
+// per CU takes one head and a contiguous share of its tiles.  A wave that asks for more
+// bytes than its CU may have in flight is held at the load instruction until older requests
+// return, so a wave that both requests and computes does neither for most of the time;
+// here the two are different waves:
+//   * waves 4-7 only move weights: plain coalesced 16-byte loads into two register sets of
+//     two tiles each (96 KB per CU in flight, re-requested set by set: the registers, not
+//     LDS stages, hold the bytes in flight; more sets in flight were measured and are no
+//     faster), each set stored into its own LDS buffer when it has arrived;
+//   * waves 0-3 (one per SIMD, beside one loading wave) compute: token block = wave % NB,
+//     tile group = wave / NB; a wave takes the tiles of the buffer that belong to its group
+//     while the loading waves fill the other buffer; one workgroup barrier per buffer;
+//   * the per-group partial outputs are summed through LDS in the fixed order of the groups
+//     by all 512 threads, which also store them.
+// Arithmetic, lane layouts and the swizzled tile image are those of the kernels above.
+// ---------------------------------------------------------------------------
+constexpr int kDecodeTile = 3 * kPipeTile;           // K | U | V image of one tile, 24 KB
+constexpr int kDecodeThreads = 512;
+constexpr int kDecodeBuf = 2 * kDecodeTile;          // one LDS buffer: two tiles
+constexpr int kDecodeSetTiles = 2;                   // tiles per register set (one buffer's worth)
+constexpr int kDecodeRegSets = 2;                    // register sets of the loading waves: 96 KB per CU in flight
+// LDS: two buffers | 1/r [64][32 NB] fp32 | token rows [NB][32][128] bf16
+constexpr int decode_lds_bytes(int nb) { return 2 * kDecodeBuf + kPipeMaxSubStatic * 32 * nb * 4 + nb * kPipeTile; }
+static_assert(decode_lds_bytes(4) <= (int)kLdsBytesPerWorkgroup, "decode kernel LDS");
+
+template <int NB>
+__global__ __launch_bounds__(kDecodeThreads) void fwd_bf16_decode_kernel(FwdArgs a) {
+  constexpr int NG = 4 / NB;                         // tile groups among the four computing waves
+  constexpr int BT = 32 * NB;                        // token slots of the workgroup
+  constexpr int CT = 256;                            // threads of either role
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  unsigned char* buf0 = smem;
+  unsigned char* buf1 = smem + kDecodeBuf;
+  float* Rs = reinterpret_cast<float*>(smem + 2 * kDecodeBuf);         // [64][BT], 1/r
+  unsigned char* Qs = smem + 2 * kDecodeBuf + kPipeMaxSubStatic * BT * 4;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int r = lane & 31, g = lane >> 5;
+  const int item = (int)xcd_work_item(blockIdx.x, a.n_items);
+  if (item >= (int)a.n_items) return;  // whole workgroup leaves together
+  const int split = item % a.n_split;
+  const int h = item / a.n_split;
+  const int E = a.E;
+  const bool loader = wave >= 4;
+  const int rt = tid & (CT - 1);                     // thread index inside its role
+  const int tb = wave % NB, grp = (wave & 3) / NB;   // computing waves: token block, tile group
+  const int tiles_per_sub = a.de / kBI;
+  const int t_begin = split * a.tiles_per_split;
+  const int T = min(E * tiles_per_sub, t_begin + a.tiles_per_split) - t_begin;
+  const int n_sets = (T + kDecodeSetTiles - 1) / kDecodeSetTiles;
+  // Two sets per round, every round alike (a round that skipped its second set would leave
+  // the number of loads between two uses of a register set unknown to the compiler, and its
+  // waits would drain the whole stream): an odd number of sets is preceded by an empty set
+  // -1, copies of tile 0 that are stored and never used.
+  const int s_first = -(n_sets & 1);
+  const size_t head_off = ((size_t)h * E * a.de + (size_t)t_begin * kBI) * kDh;
+  const uint16_t* Kh = a.Wg + head_off;
+  const uint16_t* Uh = a.Wu + head_off;
+  const uint16_t* Vh = a.Wd + head_off;
+
+  // ---- loading waves: thread = chunks (row rt/16 and rt/16 + 16, chunk rt%16) of every
+  // tile.  Requests are unconditional (a tile index outside the share is clamped and the
+  // copy is never used), so the number of loads in flight behind a set is a constant.
+  const int srow = rt >> 4, schunk = rt & 15;
+  const unsigned s_goff = (unsigned)(srow * kDh + schunk * 8);          // elements inside a tile
+  const int s_loff = tile_off(srow, schunk);                            // bytes; row + 16: + 4096
+  u32x4 st[kDecodeRegSets][kDecodeSetTiles][6];
+  auto request = [&](int s, auto S_) {
+    constexpr int S = decltype(S_)::value;
+#pragma unroll
+    for (int j = 0; j < kDecodeSetTiles; ++j) {
+      const unsigned off = (unsigned)min(max(s * kDecodeSetTiles + j, 0), T - 1) * (kBI * kDh) + s_goff;
+      st[S][j][0] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(Kh + off));
+      st[S][j][1] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(Kh + off + 16 * kDh));
+      st[S][j][2] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(Uh + off));
+      st[S][j][3] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(Uh + off + 16 * kDh));
+      st[S][j][4] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(Vh + off));
+      st[S][j][5] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(Vh + off + 16 * kDh));
+    }
+  };
+  auto store_set = [&](auto S_, unsigned char* buf) {
+    constexpr int S = decltype(S_)::value;
+#pragma unroll
+    for (int jj = 0; jj < kDecodeSetTiles; ++jj) {
+      unsigned char* slot = buf + jj * kDecodeTile + s_loff;
+#pragma unroll
+      for (int i = 0; i < 6; ++i)
+        *reinterpret_cast<u32x4*>(slot + (i >> 1) * kPipeTile + (i & 1) * 4096) = st[S][jj][i];
+    }
+  };
+  using I0 = std::integral_constant<int, 0>;
+  using I1 = std::integral_constant<int, 1>;
+
+  const unsigned char* qrow = Qs + tb * kPipeTile;   // + tile_off(r, 2 ks + g): a lane's operand of step ks
+  const int tok = tb * 32 + r;
+  f32x16 O[4];
+#pragma unroll
+  for (int jb = 0; jb < 4; ++jb) O[jb] = f32x16{0};
+
+  // The two roles are two code paths with the same sequence of workgroup barriers: two before
+  // the rounds (token rows and gating operand staged | 1/r complete), one per set, one after
+  // the last set.  Set s lives in buffer and register set (s - s_first) % 2.  A loading wave
+  // stores a set, passes the barrier that hands it over, and only then asks for the set that
+  // takes the freed registers: that request is the instruction at which it is held, and the
+  // computing waves work on the handed-over buffer meanwhile.  The stream does not wait for
+  // the gating phase and the gating phase does not wait for the stream: one set is requested
+  // before the first barrier; between the two barriers the loading waves request the second
+  // and store the first into buffer 0 (the gating operand lies in buffer 1).
+  if (loader) {
+    request(s_first, I0{});
+    __syncthreads();
+    request(s_first + 1, I1{});
+    MHFFN_SB();   // the request stays ahead of the wait for the first set
+    store_set(I0{}, buf0);
+    __syncthreads();
+    request(s_first + 2, I0{});
+    MHFFN_SB();
+    store_set(I1{}, buf1);
+    __syncthreads();
+    request(s_first + 3, I1{});
+    MHFFN_SB();
+    for (int s = s_first + 2; s < n_sets; s += 2) {
+      store_set(I0{}, buf0);
+      __syncthreads();
+      request(s + 2, I0{});
+      MHFFN_SB();
+      store_set(I1{}, buf1);
+      __syncthreads();
+      request(s + 3, I1{});
+      MHFFN_SB();
+    }
+    __syncthreads();
+  } else {
+    // ---- token rows into LDS as NB tile images [32 tokens][128], and the gating operand
+    // W_r^T as [64][128] in two tile images (in buffer 1; rows E.. keep whatever the memory
+    // held: a row of the product depends on its own row of the operand only, and rows E..
+    // are masked below)
+    constexpr int kWrIter = kDh * kPipeMaxSubStatic / 8 / CT;   // 4
+    constexpr int kRIter = BT * kPipeMaxSubStatic / CT;         // 8, 16, 32
+    u32x4 xv[2 * NB];
+#pragma unroll
+    for (int i = 0; i < 2 * NB; ++i) {
+      const int t_row = i * 16 + srow;
+      xv[i] = *reinterpret_cast<const u32x4*>(a.X + (int64_t)(t_row < a.N ? t_row : 0) * a.ldx + h * kDh + schunk * 8);
+    }
+    if (a.route_mode == 0) {
+      const uint16_t* Wr = reinterpret_cast<const uint16_t*>(a.route) + (size_t)h * kDh * E;
+      u32x4 wv[kWrIter];
+#pragma unroll
+      for (int it = 0; it < kWrIter; ++it) {
+        const int c = rt + it * CT;
+        wv[it] = *reinterpret_cast<const u32x4*>(Wr + 8 * (c < kDh * E / 8 ? c : 0));
+      }
+      auto wr_off = [&](int e, int j) { return (e >> 5) * kPipeTile + tile_off(e & 31, j >> 3) + (j & 7) * 2; };
+#pragma unroll
+      for (int it = 0; it < kWrIter; ++it) {
+        const int c = rt + it * CT;
+        if (c < kDh * E / 8) {
+          int j = (8 * c) / E, e = 8 * c - j * E;
+#pragma unroll
+          for (int i = 0; i < 8; ++i) {
+            *reinterpret_cast<uint16_t*>(buf1 + wr_off(e, j)) = (uint16_t)(wv[it][i >> 1] >> (16 * (i & 1)));
+            if (++e == E) { e = 0; ++j; }
+          }
+        }
+      }
+    } else {
+      const float* R = reinterpret_cast<const float*>(a.route);
+      float rv[kRIter];
+#pragma unroll
+      for (int it = 0; it < kRIter; ++it) {
+        const int idx = rt + it * CT;
+        const int tl = idx / E, e = idx - tl * E;
+        const bool ok = idx < BT * E && tl < a.N;
+        rv[it] = R[ok ? ((size_t)tl * a.H + h) * E + e : 0];
+      }
+#pragma unroll
+      for (int it = 0; it < kRIter; ++it) {
+        const int idx = rt + it * CT;
+        const int tl = idx / E, e = idx - tl * E;
+        if (idx < BT * E) Rs[e * BT + tl] = inv_weight(tl < a.N ? rv[it] : 0.f);
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < 2 * NB; ++i) {
+      const int t_row = i * 16 + srow;
+      *reinterpret_cast<u32x4*>(Qs + (t_row >> 5) * kPipeTile + tile_off(t_row & 31, schunk)) =
+          (t_row < a.N) ? xv[i] : u32x4{0, 0, 0, 0};
+    }
+    __syncthreads();
+    if (grp == 0 && a.route_mode == 0) {
+      const bool two = E > 32;
+      f32x16 acc[2] = {f32x16{0}, f32x16{0}};
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) {
+        const bf16x8 qk = *reinterpret_cast<const bf16x8*>(qrow + tile_off(r, 2 * ks + g));
+        const bf16x8 a0 = *reinterpret_cast<const bf16x8*>(buf1 + tile_off(r, 2 * ks + g));
+        acc[0] = mfma32(a0, qk, acc[0]);
+        if (two) {
+          const bf16x8 a1 = *reinterpret_cast<const bf16x8*>(buf1 + kPipeTile + tile_off(r, 2 * ks + g));
+          acc[1] = mfma32(a1, qk, acc[1]);
+        }
+      }
+      float sg[2][16];
+      float zsum = 0.f;
+#pragma unroll
+      for (int eb = 0; eb < 2; ++eb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int e = 32 * eb + 8 * (v / 4) + 4 * g + (v % 4);
+          sg[eb][v] = (e < E) ? sigmoid_fast(acc[eb][v]) : 0.f;
+          zsum += sg[eb][v];
+        }
+      const float inv = 1.0f / (zsum + __shfl_xor(zsum, 32) + a.eps);
+      float* rs_lane = Rs + tok;
+#pragma unroll
+      for (int eb = 0; eb < 2; ++eb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int e = 32 * eb + 8 * (v / 4) + 4 * g + (v % 4);
+          rs_lane[e * BT] = inv_weight(sg[eb][v] * inv);   // rows E..63 exist and are never read
+        }
+    }
+    __syncthreads();  // 1/r complete; buffer 1 is free again
+
+    // the tiles of one buffer that belong to this wave's group (tile_base: index of the
+    // buffer's first tile inside the workgroup's share; outside the share: nothing to do)
+    auto compute = [&](const unsigned char* buf, int tile_base) {
+#pragma unroll
+      for (int jj = 0; jj < kDecodeSetTiles; ++jj) {
+        const int t = tile_base + jj;
+        if (NG > 1 && jj != grp) continue;             // one group: both tiles; else tile `grp` (groups 2, 3 idle)
+        if ((unsigned)t >= (unsigned)T) continue;
+        const unsigned char* sl = buf + jj * kDecodeTile;
+        const float rw = Rs[((t_begin + t) / tiles_per_sub) * BT + tok];
+        f32x16 accM = f32x16{0}, accN = f32x16{0};
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) {
+          const bf16x8 qk = *reinterpret_cast<const bf16x8*>(qrow + tile_off(r, 2 * ks + g));
+          const bf16x8 ak = *reinterpret_cast<const bf16x8*>(sl + tile_off(r, 2 * ks + g));
+          const bf16x8 au = *reinterpret_cast<const bf16x8*>(sl + kPipeTile + tile_off(r, 2 * ks + g));
+          accM = mfma32(ak, qk, accM);
+          accN = mfma32(au, qk, accN);
+        }
+        bf16x8 bfrag[2];
+#pragma unroll
+        for (int t2 = 0; t2 < 2; ++t2) {
+          float tt[8], ss[8];
+#pragma unroll
+          for (int i = 0; i < 8; ++i) tt[i] = __builtin_amdgcn_exp2f(-MHFFN_LOG2E * accM[8 * t2 + i]);
+#pragma unroll
+          for (int i = 0; i < 8; ++i) ss[i] = __builtin_amdgcn_rcpf(__builtin_fmaf(tt[i], rw, rw));
+          u32x4 pk;
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const float a0 = (accM[8 * t2 + 2 * i] * accN[8 * t2 + 2 * i]) * ss[2 * i];
+            const float a1 = (accM[8 * t2 + 2 * i + 1] * accN[8 * t2 + 2 * i + 1]) * ss[2 * i + 1];
+            pk[i] = pack_bf16(a0, a1);
+          }
+          bfrag[t2] = __builtin_bit_cast(bf16x8, pk);
+        }
+#pragma unroll
+        for (int t2 = 0; t2 < 2; ++t2)
+#pragma unroll
+          for (int jb = 0; jb < 4; ++jb)
+            O[jb] = mfma32(tile_read_tr(sl + 2 * kPipeTile, 16 * t2 + 4 * g, 32 * jb, lane), bfrag[t2], O[jb]);
+      }
+    };
+    compute(buf0, kDecodeSetTiles * s_first);
+    __syncthreads();
+    for (int s = s_first + 2; s < n_sets; s += 2) {
+      compute(buf1, kDecodeSetTiles * (s - 1));
+      __syncthreads();
+      compute(buf0, kDecodeSetTiles * s);
+      __syncthreads();
+    }
+    compute(buf1, kDecodeSetTiles * (n_sets - 1));   // the number of sets from s_first on is even: the last one is in buffer 1
+    __syncthreads();
+  }
+
+  // ---- sum over the groups in the fixed order 0, 1, ..: every computing wave leaves its
+  // accumulators in LDS as [wave][quad 4 jb + vq][lane] f32x4 (wave = group * NB + token
+  // block), then all threads share out the quads, add and store (16 bytes per lane: 4
+  // consecutive columns of Y) ------------------------------------------------------------
+  f32x4* red = reinterpret_cast<f32x4*>(smem);
+  if (!loader) {
+    f32x4* dst = red + (size_t)(wave * 16) * 64 + lane;
+#pragma unroll
+    for (int jb = 0; jb < 4; ++jb)
+#pragma unroll
+      for (int vq = 0; vq < 4; ++vq)
+        dst[(4 * jb + vq) * 64] = f32x4{O[jb][4 * vq], O[jb][4 * vq + 1], O[jb][4 * vq + 2], O[jb][4 * vq + 3]};
+  }
+  __syncthreads();
+  constexpr int QPT = 2 * NB;                        // quads per thread: 16 NB quads per lane, 8 waves
+  if (tok >= a.N) return;
+  const int qbase = (wave / NB) * QPT;               // wave / NB runs over 8 / NB values
+#pragma unroll
+  for (int qi = 0; qi < QPT; ++qi) {
+    const int q4 = qbase + qi;
+    f32x4 sum = red[(size_t)(tb * 16 + q4) * 64 + lane];
+#pragma unroll
+    for (int gg = 1; gg < NG; ++gg) sum += red[(size_t)((gg * NB + tb) * 16 + q4) * 64 + lane];
+    const int col = 32 * (q4 >> 2) + 8 * (q4 & 3) + 4 * g;
+    if (a.n_split > 1) {
+      *reinterpret_cast<f32x4*>(a.P + (((size_t)split * a.N + tok) * a.H + h) * kDh + col) = sum;
+    } else {
+      u32x2 pkw;
+      pkw[0] = pack_bf16(sum[0], sum[1]);
+      pkw[1] = pack_bf16(sum[2], sum[3]);
+      *reinterpret_cast<u32x2*>(a.Y + (int64_t)tok * a.ldy + h * kDh + col) = pkw;
+    }
+  }
+}
+
 // Y[tok][col] = bf16(sum_s P[s][tok][col]), fixed order
 __global__ void fwd_bf16_reduce_kernel(FwdArgs a) {
   const int64_t dm = (int64_t)a.H * a.dh;
   const int64_t idx = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
   if (idx >= a.N * dm) return;
   f32x4 sum = {0.f, 0.f, 0.f, 0.f};
-  for (int s = 0; s < a.n_split; ++s)
-    sum += *reinterpret_cast<const f32x4*>(a.P + (size_t)s * a.N * dm + idx);
+  const size_t stride = (size_t)a.N * dm;
+  int s = 0;
+  for (; s + 8 <= a.n_split; s += 8) {   // eight loads in flight, summed in the order of s
+    f32x4 v[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] = *reinterpret_cast<const f32x4*>(a.P + (size_t)(s + i) * stride + idx);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) sum += v[i];
+  }
+  for (; s < a.n_split; ++s)
+    sum += *reinterpret_cast<const f32x4*>(a.P + (size_t)s * stride + idx);
   const int64_t tok = idx / dm, col = idx % dm;
   u32x2 pk;
   pk[0] = pack_bf16(sum[0], sum[1]);
@@ -778,10 +1105,24 @@ __global__ void fwd_bf16_reduce_kernel(FwdArgs a) {
 // is a weight-streaming kernel, and its deep ring of direct loads is what keeps
 // enough bytes in flight.  The older kernel (more than 64 sub-networks) aims for
 // two smaller workgroups per CU.
-struct SplitPlan { int bm, n_split, tiles_per_split; bool pipe; };
+struct SplitPlan { int bm, n_split, tiles_per_split; bool pipe; int decode_nb; };
+constexpr int kDecodeMaxTokens = 128;
 SplitPlan plan_split(const Problem& p) {
   SplitPlan s;
   s.pipe = p.dh == kDh && p.E <= kPipeMaxSub;
+  s.decode_nb = 0;
+  if (s.pipe && p.N <= kDecodeMaxTokens) {
+    // decode kernel: about one workgroup per CU, each a head and a share of its tiles
+    s.decode_nb = p.N <= 32 ? 1 : p.N <= 64 ? 2 : 4;
+    s.bm = 32 * s.decode_nb;
+    const int T = p.E * (p.de / kBI);
+    int want = 256 / p.H;
+    if (want < 1) want = 1;
+    if (want > T) want = T;
+    s.tiles_per_split = (T + want - 1) / want;
+    s.n_split = (T + s.tiles_per_split - 1) / s.tiles_per_split;
+    return s;
+  }
   s.bm = (!s.pipe && p.N <= 128) ? 64 : 256;
   if (p.dh == 256) s.bm = 128;   // 4 waves of up to 512 registers (see launch_fwd_bf16)
   const int64_t base = ((p.N + s.bm - 1) / s.bm) * p.H;
@@ -836,6 +1177,25 @@ int launch_pipe(const Problem& p, FwdArgs a, const SplitPlan& sp, hipStream_t st
   return (int)hipGetLastError();
 }
 
+template <int NB>
+int launch_decode(const Problem& p, FwdArgs a, const SplitPlan& sp, hipStream_t stream) {
+  a.n_tiles = 1;
+  a.n_split = sp.n_split;
+  a.tiles_per_split = sp.tiles_per_split;
+  a.n_items = (int64_t)p.H * sp.n_split;
+  const size_t lds = (size_t)decode_lds_bytes(NB);
+  if (hipError_t e0 = LdsLimit<&fwd_bf16_decode_kernel<NB>, (int)kLdsBytesPerWorkgroup>::ensure(); e0 != hipSuccess)
+    return (int)e0;
+  hipLaunchKernelGGL(fwd_bf16_decode_kernel<NB>, dim3((unsigned)xcd_grid_size(a.n_items)),
+                     dim3(kDecodeThreads), lds, stream, a);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess || sp.n_split == 1) return (int)e;
+  const int64_t n4 = p.N * p.H * kDh / 4;
+  hipLaunchKernelGGL(fwd_bf16_reduce_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0,
+                     stream, a);
+  return (int)hipGetLastError();
+}
+
 }  // namespace
 
 size_t fwd_bf16_workspace_bytes(const Problem& p) {
@@ -861,6 +1221,9 @@ int launch_fwd_bf16(const Problem& p, const void* X, const void* Wg, const void*
   hipStream_t st = static_cast<hipStream_t>(stream);
   // 8 waves x 32 tokens (two waves per SIMD) measured 25% faster than 4 waves x
   // 64 tokens at the 1.3B shape: the second wave hides LDS and barrier latency.
+  if (sp.decode_nb == 1) return launch_decode<1>(p, a, sp, st);
+  if (sp.decode_nb == 2) return launch_decode<2>(p, a, sp, st);
+  if (sp.decode_nb == 4) return launch_decode<4>(p, a, sp, st);
   if (sp.pipe) return launch_pipe(p, a, sp, st);
   if (p.dh == 64) {
     if (sp.bm == 64) return launch_variant<64, 1, 2>(p, a, sp, st);
@@ -877,6 +1240,7 @@ int launch_fwd_bf16(const Problem& p, const void* X, const void* Wg, const void*
 
 size_t fwd_bf16_lds_bytes(const Problem& p) {
   const SplitPlan sp = plan_split(p);
+  if (sp.decode_nb) return (size_t)decode_lds_bytes(sp.decode_nb);
   if (sp.pipe) return (size_t)3 * kPipeRing + (size_t)p.E * kPipeBM * sizeof(float);
   return (size_t)kStages * fwd_stage_bytes(p.dh) + (size_t)p.E * sp.bm * sizeof(float);
 }

@@ -4,7 +4,7 @@ import pytest
 
 from oracle import mhffn_oracle as orc
 from paper_2512_06989_amd import inputs, mhffn
-from tests.helpers import TOL, device_inputs, relerr, small_workload, to_host
+from tests.helpers import TOL, check_parity, device_inputs, relerr, small_workload, to_host
 
 pytestmark = pytest.mark.gpu
 
@@ -52,6 +52,41 @@ def test_bf16_small_shapes_params_mode(N, H, E, de):
     w = small_workload("bf16_small", N, H, E, de, "bf16")
     d, Y = run_forward(w, seed=N + E)
     assert relerr(Y, oracle_forward(d, w)) <= TOL["bf16"]
+
+
+@pytest.mark.parametrize("N,H,E,de,weights", [
+    (1, 1, 1, 32, False), (17, 3, 5, 64, False), (32, 16, 44, 128, False), (33, 2, 64, 32, False),
+    (64, 16, 44, 128, False), (64, 5, 7, 384, True), (65, 2, 3, 96, False), (100, 6, 16, 128, True),
+    (128, 16, 22, 384, False), (96, 1, 33, 32, True),
+    # more heads than workgroup slots: one workgroup per head, no partial outputs
+    (5, 300, 2, 32, False), (40, 260, 1, 64, True)])
+def test_bf16_decode_sized_inputs(N, H, E, de, weights):
+    """Up to 128 tokens at d_h = 128: the weight-streaming kernel (one to four token blocks,
+    tiles of a batch worked on side by side, partial sums over tile groups and over
+    workgroups), every row against the oracle."""
+    w = small_workload("bf16_decode", N, H, E, de, "bf16")
+    d, Y = run_forward(w, seed=N + E, route_weights=weights)
+    check_parity({"Y": Y}, {"Y": oracle_forward(d, w, route_weights=weights)}, TOL["bf16"], 128,
+                 "decode N=%d" % N)
+
+
+def test_decode_sized_strided_rows_and_run_to_run():
+    import torch
+    w = small_workload("decode_strided", 50, 4, 9, 64, "bf16")
+    d = inputs.make_inputs(w, seed=21, with_dy=False)
+    g = device_inputs(d, w.dtype)
+    dm = w.d_model
+    Xp = torch.zeros(w.n_tokens, dm + 64, dtype=torch.bfloat16, device="cuda")
+    Xp[:, :dm] = g["X"]
+    out = []
+    for _ in range(2):
+        Yp = torch.full((w.n_tokens, dm + 128), 7.0, dtype=torch.bfloat16, device="cuda")
+        mhffn.forward(Xp[:, :dm], g["W_gate"], g["W_up"], g["W_down"], g["W_r"], w.eps, out=Yp[:, :dm])
+        torch.cuda.synchronize()
+        assert torch.all(Yp[:, dm:] == 7.0)
+        out.append(to_host(Yp[:, :dm]))
+    assert np.array_equal(out[0], out[1])
+    check_parity({"Y": out[0]}, {"Y": oracle_forward(d, w)}, TOL["bf16"], 128, "decode strided")
 
 
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
