@@ -577,6 +577,15 @@ def main():
         cal = mfma_calibration(hip)
         if cal:
             out["mfma_sustained"] = cal
+            # the same rates against what a bare MFMA loop with data like the workload's sustains
+            # here (context only: `frac` stays the fraction of the published peak)
+            sus = cal["random_operands"]["TFLOPs"]
+            for key in ("roofline", "roofline_fwd", "roofline_bwd_tok", "roofline_bwd_wgt"):
+                r = out.get(key)
+                if r and r.get("bound") == "mfma" and sus > 0:
+                    r["frac_of_sustained_mfma"] = round(r["achieved"] / sus, 4)
+                    if "executed_frac" in r:
+                        r["executed_frac_of_sustained_mfma"] = round(r["executed_frac"] * PEAK_BF16_TFLOPS / sus, 4)
     if args.configs and w.name == "1p3b_fwdbwd" and not args.forward_only and not args.tokens:
         # the other configurations, a few seconds in all, outside the timed region above
         del g, X, Y, dY, grads, ws, fwd_ws
