@@ -455,22 +455,20 @@ __global__ __launch_bounds__(64 * kPipeWaves) void fwd_bf16_flow_kernel(FwdArgs 
       if (c < kDh * E / 8) wv[it] = *reinterpret_cast<const u32x4*>(Wr + 8 * c);
     }
     first_requests();
+    // (rows E.. of the operand keep whatever the memory held: a row of the product depends on
+    // its own row of the operand only, and rows E.. are masked below)
 #pragma unroll
     for (int it = 0; it < kWrIter; ++it) {
       const int c = tid + it * THREADS;
       if (c < kDh * E / 8) {
+        int j = (8 * c) / E, e = 8 * c - j * E;
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-          const int idx = 8 * c + i;
-          const int j = idx / E, e = idx - j * E;
           const uint16_t w = (uint16_t)(wv[it][i >> 1] >> (16 * (i & 1)));
           *reinterpret_cast<uint16_t*>(smem + wr_off(e, j >> 3) + (j & 7) * 2) = w;
+          if (++e == E) { e = 0; ++j; }
         }
       }
-    }
-    for (int idx = tid; idx < (32 * EB - E) * kDh; idx += THREADS) {
-      const int e = E + idx / kDh, j = idx % kDh;
-      *reinterpret_cast<uint16_t*>(smem + wr_off(e, j >> 3) + (j & 7) * 2) = 0;
     }
     __syncthreads();
     if (active) {
@@ -497,13 +495,14 @@ __global__ __launch_bounds__(64 * kPipeWaves) void fwd_bf16_flow_kernel(FwdArgs 
           zsum += sg[eb][v];
         }
       const float inv = 1.0f / (zsum + __shfl_xor(zsum, 32) + a.eps);
+      float* rs_lane = Rs + wtok + r;   // 64 rows are allocated: rows E.. are written and never read
 #pragma unroll
-      for (int eb = 0; eb < 2; ++eb)
+      for (int eb = 0; eb < 2; ++eb) {
+        if (eb >= EB) break;
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int e = 32 * eb + 8 * (v / 4) + 4 * g + (v % 4);
-          if (e < E) Rs[e * BM + wtok + r] = inv_weight(sg[eb][v] * inv);
-        }
+        for (int v = 0; v < 16; ++v)
+          rs_lane[(32 * eb + 8 * (v / 4) + 4 * g + (v % 4)) * BM] = inv_weight(sg[eb][v] * inv);
+      }
     }
   } else {
     first_requests();
@@ -1164,7 +1163,7 @@ int launch_pipe(const Problem& p, FwdArgs a, const SplitPlan& sp, hipStream_t st
   a.n_split = sp.n_split;
   a.tiles_per_split = sp.tiles_per_split;
   a.n_items = a.n_tiles * p.H * sp.n_split;
-  const size_t lds = (size_t)3 * kPipeRing + (size_t)p.E * kPipeBM * sizeof(float);
+  const size_t lds = (size_t)3 * kPipeRing + (size_t)kPipeMaxSub * kPipeBM * sizeof(float);   // 1/r: 64 rows
   if (hipError_t e0 = LdsLimit<&fwd_bf16_flow_kernel, (int)kLdsBytesPerWorkgroup>::ensure(); e0 != hipSuccess)
     return (int)e0;
   hipLaunchKernelGGL(fwd_bf16_flow_kernel, dim3((unsigned)xcd_grid_size(a.n_items)),
@@ -1241,7 +1240,7 @@ int launch_fwd_bf16(const Problem& p, const void* X, const void* Wg, const void*
 size_t fwd_bf16_lds_bytes(const Problem& p) {
   const SplitPlan sp = plan_split(p);
   if (sp.decode_nb) return (size_t)decode_lds_bytes(sp.decode_nb);
-  if (sp.pipe) return (size_t)3 * kPipeRing + (size_t)p.E * kPipeBM * sizeof(float);
+  if (sp.pipe) return (size_t)3 * kPipeRing + (size_t)kPipeMaxSub * kPipeBM * sizeof(float);
   return (size_t)kStages * fwd_stage_bytes(p.dh) + (size_t)p.E * sp.bm * sizeof(float);
 }
 
