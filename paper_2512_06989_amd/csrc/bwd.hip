@@ -1203,38 +1203,50 @@ __global__ __launch_bounds__(256) void bwd_route_partial_kernel(BwdArgs a) {
 #pragma unroll
     for (int jb = 0; jb < JB; ++jb) acc[eb][jb] = f32x16{0};
 
-  for (int64_t it = 0; it < iters; ++it) {
-    const int64_t b = it * kRouteParts + part;
-    const int64_t tok0 = b * 32;   // may lie beyond N: then everything loaded is zero
-    // X tile -> this wave's LDS tile
+  // Every wave owns its LDS tile and its token blocks: no workgroup barrier is needed, and the
+  // loads of the next block are requested before the products of the current one.
+  constexpr int XC = 32 * CPR / 64;               // 16-byte chunks of the X tile per lane
+  u32x4 xv[XC];
+  float dv[EB][2][8];
+  auto request = [&](int64_t it) {
+    const int64_t tok0 = (it * kRouteParts + part) * 32;   // may lie beyond N: then everything loaded is zero
 #pragma unroll
-    for (int i = 0; i < 32 * CPR / 64; ++i) {
+    for (int i = 0; i < XC; ++i) {
       const int chunk = lane + 64 * i;
       const int64_t t = tok0 + chunk / CPR;
-      u32x4 v = {0, 0, 0, 0};
-      if (t < N) v = *reinterpret_cast<const u32x4*>(a.X + t * a.ldx + h * DH + (chunk % CPR) * 8);
-      *reinterpret_cast<u32x4*>(tile + btile_off<DH>(chunk / CPR, chunk % CPR)) = v;
+      xv[i] = u32x4{0, 0, 0, 0};
+      if (t < N) xv[i] = *reinterpret_cast<const u32x4*>(a.X + t * a.ldx + h * DH + (chunk % CPR) * 8);
     }
-    // dp operands
-    bf16x8 bp[EB][2];
 #pragma unroll
     for (int eb = 0; eb < EB; ++eb) {
       const int e = 32 * eb + r;
 #pragma unroll
-      for (int t2 = 0; t2 < 2; ++t2) {
-        float v[8];
+      for (int t2 = 0; t2 < 2; ++t2)
 #pragma unroll
         for (int s8 = 0; s8 < 8; ++s8) {
           const int64_t t = tok0 + 16 * t2 + 8 * (s8 >> 2) + 4 * g + (s8 & 3);
-          v[s8] = (e < E && t < N) ? DPh[(size_t)e * N + t] : 0.f;
+          dv[eb][t2][s8] = (e < E && t < N) ? DPh[(size_t)e * N + t] : 0.f;
         }
+    }
+  };
+  request(0);
+  for (int64_t it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int i = 0; i < XC; ++i) {
+      const int chunk = lane + 64 * i;
+      *reinterpret_cast<u32x4*>(tile + btile_off<DH>(chunk / CPR, chunk % CPR)) = xv[i];
+    }
+    bf16x8 bp[EB][2];
+#pragma unroll
+    for (int eb = 0; eb < EB; ++eb)
+#pragma unroll
+      for (int t2 = 0; t2 < 2; ++t2) {
         u32x4 pk;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) pk[i] = pack_bf16(v[2 * i], v[2 * i + 1]);
+        for (int i = 0; i < 4; ++i) pk[i] = pack_bf16(dv[eb][t2][2 * i], dv[eb][t2][2 * i + 1]);
         bp[eb][t2] = __builtin_bit_cast(bf16x8, pk);
       }
-    }
-    __syncthreads();
+    if (it + 1 < iters) request(it + 1);
 #pragma unroll
     for (int t2 = 0; t2 < 2; ++t2) {
 #pragma unroll
@@ -1244,7 +1256,6 @@ __global__ __launch_bounds__(256) void bwd_route_partial_kernel(BwdArgs a) {
         for (int eb = 0; eb < EB; ++eb) acc[eb][jb] = mfma32(qT, bp[eb][t2], acc[eb][jb]);
       }
     }
-    __syncthreads();
   }
   float* out = a.WRws + ((size_t)h * kRouteParts + part) * DH * E;
 #pragma unroll
@@ -1269,7 +1280,15 @@ __global__ void bwd_route_reduce_kernel(BwdArgs a) {
   const int h = (int)(idx / per_head);
   const int64_t o = idx % per_head;
   float sum = 0.f;
-  for (int s = 0; s < a.n_split; ++s) sum += a.WRws[((size_t)h * a.n_split + s) * per_head + o];
+  int s = 0;
+  for (; s + 8 <= a.n_split; s += 8) {   // eight loads in flight, summed in the order of s
+    float v[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] = a.WRws[((size_t)h * a.n_split + s + i) * per_head + o];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) sum += v[i];
+  }
+  for (; s < a.n_split; ++s) sum += a.WRws[((size_t)h * a.n_split + s) * per_head + o];
   reinterpret_cast<uint16_t*>(a.d_route)[idx] = (uint16_t)(pack_bf16(sum, 0.f) & 0xFFFFu);
 }
 
