@@ -124,10 +124,11 @@ typedef struct {
  * workgroups per token tile and their fp32 partial outputs, n_split * N *
  * d_model * 4 bytes (a few output-sized buffers, never d_ff-sized ones), pass
  * through the workspace; ask this function rather than relying on the rule.  For MHFFN_OP_BACKWARD it is the gating weights R and
- * their gradient as [H][E][N] fp32, the partial sums of dW_r, and, for shapes
- * whose weights alone cannot fill the chip, fp32 partial weight gradients of a
- * few token segments (all summed in a fixed order: results are bit-identical
- * from run to run).  For the unfused ops it is the three
+ * their gradient as [H][E][N] fp32, the partial sums of dW_r, and, for the
+ * neuron groups that would otherwise leave CUs idle in the last round of
+ * workgroups, fp32 partial weight gradients of a few token segments (a multiple
+ * of the parameter count, not of the token count; all summed in a fixed order:
+ * results are bit-identical from run to run).  For the unfused ops it is the three
  * materialised [N][H][d_ff] activations plus the [N][H][E] weights, i.e. the
  * O((L*H + d_model)*d_ff) footprint of the naive multi-head FFN. */
 size_t mhffn_workspace_bytes(const mhffn_desc* desc, int op);

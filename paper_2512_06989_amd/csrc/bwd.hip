@@ -96,6 +96,11 @@ struct BwdArgs {
   float* WPws;
   int wsplit;
   int64_t blocks_per_seg;
+  // d_h = 128 weight-major kernel: the neuron groups of an XCD's share are `gpx` (of `n_groups`
+  // in all); the first `full_px` of them take all tokens and store their gradients, the
+  // others share the tokens out over `wsplit` workgroups each and leave fp32 partials
+  // [wsplit][3][8 * (gpx - full_px) groups][128 rows][128]
+  int gpx, full_px, n_groups;
   int64_t N, ldx, ldy, n_tiles, n_items;
   int H, E, de, dh, route_mode, n_split;
   float eps;
@@ -600,12 +605,29 @@ __global__ __launch_bounds__(kW16Threads) void bwd_wgt16_kernel(BwdArgs a) {
   auto w16_off8 = [&](int row, int col) { return w16_off(row, col >> 3) + ((col & 4) << 1); };
   const int nblk = a.E * a.de / 16;              // 16-neuron blocks per head
   const int wg_per_head = (nblk + kW16Waves - 1) / kW16Waves;
-  const int64_t item_s = xcd_work_item(blockIdx.x, a.n_items);
-  if (item_s >= a.n_items) return;
-  const int seg = (int)(item_s % a.wsplit);          // this workgroup's share of the tokens
-  const int64_t item = item_s / a.wsplit;
-  const int h = (int)(item / wg_per_head);
-  const int blk = (int)(item % wg_per_head) * kW16Waves + wave;
+  // Workgroups go to the XCDs round robin by blockIdx and are started in that order: XCD x
+  // takes neuron groups x gpx .. (x+1) gpx - 1 (so that its workgroups stream the same
+  // heads' token tiles through its L2), first the groups that take all tokens, one workgroup
+  // each, then, `wsplit` workgroups each, the groups of the last round, which would leave
+  // CUs idle if every group were one workgroup (704 groups on 256 CUs: 2.75 rounds).
+  const int xcd = blockIdx.x & 7, widx = blockIdx.x >> 3;
+  const int g_first = xcd * a.gpx;
+  const int n_here = min(a.n_groups - g_first, a.gpx);       // groups of this XCD
+  const int n_full = min(a.full_px, n_here);
+  int group, seg = 0, cgroup = 0;
+  bool split = false;
+  if (widx < n_full) {
+    group = g_first + widx;
+  } else {
+    const int j = widx - n_full, lt = j / a.wsplit;
+    if (n_full + lt >= n_here) return;   // whole workgroup leaves together
+    group = g_first + n_full + lt;
+    seg = j - lt * a.wsplit;
+    split = a.wsplit > 1;
+    cgroup = xcd * (a.gpx - a.full_px) + lt;
+  }
+  const int h = group / wg_per_head;
+  const int blk = (group % wg_per_head) * kW16Waves + wave;
   const bool active = blk < nblk;
   const int blk_c = active ? blk : nblk - 1;     // idle waves shadow a valid block, store nothing
   const int64_t N = a.N;
@@ -638,8 +660,8 @@ __global__ __launch_bounds__(kW16Threads) void bwd_wgt16_kernel(BwdArgs a) {
   // repeats the lower one into the unused half of the wave's slot)
   // Blocks are requested in order, each once: the per-lane source pointers just advance.
   const int64_t nb = (N + 31) / 32;                       // all blocks of 32 tokens
-  const int64_t b0 = seg * a.blocks_per_seg;              // this workgroup's blocks: b0 .. b1-1
-  const int64_t b1 = b0 + a.blocks_per_seg < nb ? b0 + a.blocks_per_seg : nb;
+  const int64_t b0 = split ? seg * a.blocks_per_seg : 0;  // this workgroup's blocks: b0 .. b1-1
+  const int64_t b1 = (split && b0 + a.blocks_per_seg < nb) ? b0 + a.blocks_per_seg : nb;
   const int rrow = lane & 31;   // r of the block's tokens in order (the upper half-wave repeats it)
   const uint16_t* xsrc = a.X + (b0 * 32 + drow) * a.ldx + dcol;
   const uint16_t* ysrc = a.dY + (b0 * 32 + drow) * a.ldy + dcol;
@@ -829,10 +851,10 @@ __global__ __launch_bounds__(kW16Threads) void bwd_wgt16_kernel(BwdArgs a) {
   asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(opc[0]), "+v"(opc[1]), "+v"(opc[2]), "+v"(opc[3]),
                                         "+v"(rvc[0]), "+v"(rvc[1]));
 
-  if (active && a.wsplit > 1) {
-    // fp32 partial gradients of this token segment: [seg][K | U | V][row][128]
-    const size_t rows = (size_t)a.H * nblk * 16;
-    float* dst = a.WPws + (((size_t)seg * 3) * rows + row0 + cn) * kDh + 4 * gq;
+  if (active && split) {
+    // fp32 partial gradients of this token segment: [seg][K | U | V][split group][wave][16][128]
+    const size_t rows = (size_t)8 * (a.gpx - a.full_px) * (kW16Waves * 16);
+    float* dst = a.WPws + (((size_t)seg * 3) * rows + ((size_t)cgroup * kW16Waves + wave) * 16 + cn) * kDh + 4 * gq;
 #pragma unroll
     for (int jb = 0; jb < 8; ++jb) {
       *reinterpret_cast<f32x4*>(dst + 16 * jb) = dK[jb];
@@ -877,6 +899,38 @@ __global__ void bwd_wgt_reduce_kernel(BwdArgs a, size_t count) {
   }
 }
 
+// The same for bwd_wgt16_kernel, whose partials cover only the neuron groups that share their
+// tokens out: thread = 4 columns of one row of those groups.
+__global__ void bwd_wgt16_reduce_kernel(BwdArgs a, size_t crows) {
+  const size_t idx = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
+  if (idx >= crows * kDh) return;
+  const size_t crow = idx / kDh;
+  const int col = (int)(idx % kDh);
+  const int cgroup = (int)(crow / (kW16Waves * 16)), wv = (int)(crow / 16) % kW16Waves, cn = (int)(crow % 16);
+  const int per = a.gpx - a.full_px;
+  const int xcd = cgroup / per, lt = cgroup % per;
+  const int g_first = xcd * a.gpx;
+  const int n_here = min(a.n_groups - g_first, a.gpx);
+  const int n_full = min(a.full_px, n_here);
+  if (n_full + lt >= n_here) return;
+  const int group = g_first + n_full + lt;
+  const int nblk = a.E * a.de / 16;
+  const int wg_per_head = (nblk + kW16Waves - 1) / kW16Waves;
+  const int h = group / wg_per_head, blk = (group % wg_per_head) * kW16Waves + wv;
+  if (blk >= nblk) return;
+  const size_t o = (((size_t)h * nblk + blk) * 16 + cn) * kDh + col;
+  uint16_t* outs[3] = {a.dWg, a.dWu, a.dWd};
+#pragma unroll
+  for (int which = 0; which < 3; ++which) {
+    if (!outs[which]) continue;
+    f32x4 sum = {0.f, 0.f, 0.f, 0.f};
+    for (int sgm = 0; sgm < a.wsplit; ++sgm)
+      sum += *reinterpret_cast<const f32x4*>(a.WPws + ((size_t)sgm * 3 + which) * crows * kDh + idx);
+    u32x2 pk = {pack_bf16(sum[0], sum[1]), pack_bf16(sum[2], sum[3])};
+    *reinterpret_cast<u32x2*>(outs[which] + o) = pk;
+  }
+}
+
 // Tokens are shared out only when that shortens the kernel by a fifth or more: its time goes in
 // rounds of 256 workgroups (one per CU), so S segments cost ceil(groups * S / 256) / S rounds.
 struct WgtSplit { int segs; int64_t blocks_per_seg; };
@@ -898,8 +952,50 @@ WgtSplit plan_wgt_split(const Problem& p) {
   if (w.segs < 1) { w.segs = 1; w.blocks_per_seg = nb > 0 ? nb : 1; }
   return w;
 }
+// d_h = 128: the groups of an XCD's share that fill whole rounds of its 32 CUs take all tokens;
+// the groups of the last, partly filled round share the tokens out over S workgroups each
+// when that pays: the round then takes ceil(tail S / 32) / S of a round instead of one, and
+// only those groups leave partials (1.3B shape: 88 groups per XCD = 64 + 24, S = 4: 2.75 rounds
+// instead of 3; 370M shape: 22 groups, S = 4: 0.75 instead of 1).
+struct Wgt16Plan { int n_groups, gpx, full_px, segs; int64_t blocks_per_seg; size_t crows; };
+Wgt16Plan plan_wgt16(const Problem& p) {
+  Wgt16Plan w;
+  const int64_t nb = (p.N + 31) / 32;
+  const int nblk = p.E * p.de / 16;
+  w.n_groups = p.H * ((nblk + kW16Waves - 1) / kW16Waves);
+  w.gpx = (w.n_groups + 7) / 8;
+  w.full_px = w.gpx;
+  w.segs = 1;
+  w.blocks_per_seg = nb > 0 ? nb : 1;
+  w.crows = 0;
+  constexpr int slots = 32;                       // CUs of an XCD, one workgroup each
+  const int full = (w.gpx / slots) * slots, tail = w.gpx - full;
+  if (tail == 0) return w;
+  // a round walks nb blocks of 32 tokens at about 1.4 us each; partials (196608 bytes per
+  // workgroup) are written and read once more, at about 4 TB/s, plus one more launch
+  const double round_us = 1.4 * (double)nb;
+  double best_net = 0.02 * round_us * (double)((w.gpx + slots - 1) / slots);   // at least 2 % of the kernel
+  for (int S = 2; S <= 8; ++S) {
+    if (nb / S < 16) break;
+    const double r = (double)((tail * S + slots - 1) / slots) / (double)S;
+    const double net = (1.0 - r) * round_us - (8.0 * tail * S * 196608.0 * 2.0 / 4e6 + 10.0);
+    if (net > best_net) { best_net = net; w.segs = S; }
+  }
+  if (w.segs > 1) {
+    w.full_px = full;
+    w.blocks_per_seg = (nb + w.segs - 1) / w.segs;
+    w.segs = (int)((nb + w.blocks_per_seg - 1) / w.blocks_per_seg);
+    w.crows = (size_t)8 * tail * (kW16Waves * 16);
+  }
+  return w;
+}
+
 size_t wgt_split_bytes(const Problem& p) {
   if (p.N == 0) return 0;
+  if (p.dh == kDh) {
+    const Wgt16Plan w16 = plan_wgt16(p);
+    return w16.segs > 1 ? (size_t)w16.segs * 3 * w16.crows * kDh * sizeof(float) : 0;
+  }
   const WgtSplit w = plan_wgt_split(p);
   return w.segs > 1 ? (size_t)w.segs * 3 * p.H * p.E * p.de * p.dh * sizeof(float) : 0;
 }
@@ -1329,20 +1425,21 @@ int launch_tok(const Problem& p, BwdArgs a, hipStream_t stream) {
 }
 
 int launch_wgt16(const Problem& p, BwdArgs a, hipStream_t stream) {
-  const int nblk = p.E * p.de / 16;
-  const int wg_per_head = (nblk + kW16Waves - 1) / kW16Waves;
-  const WgtSplit wsp = plan_wgt_split(p);
+  const Wgt16Plan wsp = plan_wgt16(p);
   a.wsplit = wsp.segs;
   a.blocks_per_seg = wsp.blocks_per_seg;
-  a.n_items = (int64_t)wg_per_head * p.H * wsp.segs;
+  a.gpx = wsp.gpx;
+  a.full_px = wsp.full_px;
+  a.n_groups = wsp.n_groups;
+  const unsigned grid = 8u * (unsigned)(wsp.full_px + (wsp.gpx - wsp.full_px) * wsp.segs);
+  a.n_items = grid;
   if (hipError_t e = LdsLimit<&bwd_wgt16_kernel, kFullLds>::ensure(); e != hipSuccess) return (int)e;
-  hipLaunchKernelGGL(bwd_wgt16_kernel, dim3((unsigned)xcd_grid_size(a.n_items)),
-                     dim3(kW16Threads), kW16LdsBytes, stream, a);
+  hipLaunchKernelGGL(bwd_wgt16_kernel, dim3(grid), dim3(kW16Threads), kW16LdsBytes, stream, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || wsp.segs == 1) return (int)e;
-  const size_t count = (size_t)p.H * p.E * p.de * kDh;
-  hipLaunchKernelGGL(bwd_wgt_reduce_kernel, dim3((unsigned)((count / 4 + 255) / 256)), dim3(256), 0,
-                     stream, a, count);
+  const size_t count4 = wsp.crows * kDh / 4;
+  hipLaunchKernelGGL(bwd_wgt16_reduce_kernel, dim3((unsigned)((count4 + 255) / 256)), dim3(256), 0,
+                     stream, a, wsp.crows);
   return (int)hipGetLastError();
 }
 
@@ -1459,6 +1556,7 @@ int launch_bwd(const Problem& p, int dtype, const void* X, const void* Wg, const
                                     align256((size_t)p.H * kRouteParts * p.dh * p.E * sizeof(float)));
   a.wsplit = 1;
   a.blocks_per_seg = (p.N + 31) / 32;
+  a.gpx = 0; a.full_px = 0; a.n_groups = 0;
   a.N = p.N; a.ldx = p.ldx; a.ldy = p.ldy;
   a.H = p.H; a.E = p.E; a.de = p.de; a.dh = p.dh; a.route_mode = p.route_mode; a.eps = p.eps;
   a.n_split = kRouteParts;

@@ -57,6 +57,32 @@ def test_bf16_small_shapes_params_mode(N, H, E, de):
     check_all(got, ref, TOL["bf16"], single_subnetwork=(E == 1))
 
 
+@pytest.mark.parametrize("N,H,E,de", [
+    # 300 neuron groups: 38 per XCD (32 that take all tokens + 6 that share them out over four
+    # workgroups each), 34 on the last XCD (32 + 2)
+    (2048, 20, 5, 384),
+    # 272 groups of which the last of every head has idle waves (126 blocks of 16 neurons), two
+    # token segments, a ragged last block of tokens
+    (1100, 17, 9, 224)])
+def test_weight_major_last_round_shares_tokens_out(N, H, E, de):
+    """Shapes whose neuron groups fill more than one round of workgroups per XCD with a partly
+    filled last round: those groups leave fp32 partials per token segment that a second kernel
+    adds up in fixed order; the others store their gradients directly.  Every weight row against
+    the oracle, bit-identical from run to run."""
+    from tests.helpers import check_parity
+    w = small_workload("bwd_rounds", N, H, E, de, "bf16", backward=True)
+    # the workspace holds more than R, dp and the dW_r partials: the token-segment partials
+    desc = mhffn.Desc(N, H, 128, E, de, 0, 0, mhffn.BF16, mhffn.ROUTE_PARAMS, w.eps)
+    a256 = lambda x: (x + 255) // 256 * 256
+    assert mhffn.workspace_bytes(desc, mhffn.OP_BACKWARD) > 2 * a256(N * H * E * 4) + a256(H * 64 * 128 * E * 4)
+    d, got = run_backward(w, seed=N, want=("dW_gate", "dW_up", "dW_down"))
+    _, again = run_backward(w, seed=N, want=("dW_gate", "dW_up", "dW_down"))
+    for k in got:
+        assert np.array_equal(got[k], again[k]), k
+    ref = orc.backward(d["X"], d["W_gate"], d["W_up"], d["W_down"], d["W_r"], d["dY"], w.eps)
+    check_parity(got, {k: ref[k] for k in got}, TOL["bf16"], w.d_head, "rounds")
+
+
 def test_bf16_weights_mode_returns_dr():
     w = small_workload("bwd_weights", 333, 2, 6, 64, "bf16", backward=True)
     d, got = run_backward(w, seed=4, route_weights=True)
