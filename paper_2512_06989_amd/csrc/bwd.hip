@@ -836,17 +836,28 @@ __global__ __launch_bounds__(kW16Threads) void bwd_wgt16_kernel(BwdArgs a) {
     for (int ks = 0; ks < 4; ++ks) opc[ks] = opn[ks];
     rvc[0] = rvn[0];
     rvc[1] = rvn[1];
+    // second barrier of the step: keeps the two halves of the workgroup half a step apart
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
   };
   using C0 = std::integral_constant<int, 0>;
   using C1 = std::integral_constant<int, 1>;
   using C2 = std::integral_constant<int, 2>;
   using C3 = std::integral_constant<int, 3>;
+  // Waves w and w + 4 share a SIMD.  Waves 4-7 pass one barrier more before the loop and waves
+  // 0-3 one more after it, so that a SIMD always has one wave in the first half of a step
+  // (recompute products and the arithmetic) and one in the second (gradient products): the
+  // arithmetic of one runs beside the products of the other.  The stage a request overwrites
+  // was last read two barriers before the request by either half.
+  if (wave >= 4) __builtin_amdgcn_s_barrier();
   for (int64_t b = b0; b < b1; b += 4) {
     step(b, C0{});
     if (b + 1 < b1) step(b + 1, C1{});
     if (b + 2 < b1) step(b + 2, C2{});
     if (b + 3 < b1) step(b + 3, C3{});
   }
+  if (wave < 4) __builtin_amdgcn_s_barrier();
   // drain the reads issued for a block that does not exist
   asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(opc[0]), "+v"(opc[1]), "+v"(opc[2]), "+v"(opc[3]),
                                         "+v"(rvc[0]), "+v"(rvc[1]));
