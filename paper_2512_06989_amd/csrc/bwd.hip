@@ -894,6 +894,10 @@ __global__ __launch_bounds__(kW16Threads) void bwd_wgt16_kernel(BwdArgs a) {
   }
 }
 
+// bwd_wgt256_kernel (d_h = 256, further down): a workgroup takes four blocks of 16 neurons
+constexpr int kW2Dh = 256;
+constexpr int kW2Blocks = 4;
+
 // dW[i] = bf16(sum_seg partial[seg][which][i]) for which = K, U, V; fixed order
 __global__ void bwd_wgt_reduce_kernel(BwdArgs a, size_t count) {
   const size_t idx = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
@@ -910,14 +914,15 @@ __global__ void bwd_wgt_reduce_kernel(BwdArgs a, size_t count) {
   }
 }
 
-// The same for bwd_wgt16_kernel, whose partials cover only the neuron groups that share their
-// tokens out: thread = 4 columns of one row of those groups.
+// The same for bwd_wgt16_kernel and bwd_wgt256_kernel, whose partials cover only the neuron
+// groups that share their tokens out: thread = 4 columns of one row of those groups.
 __global__ void bwd_wgt16_reduce_kernel(BwdArgs a, size_t crows) {
+  const int dh = a.dh, per_group = (dh == kW2Dh) ? kW2Blocks : kW16Waves;   // 16-neuron blocks per group
   const size_t idx = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
-  if (idx >= crows * kDh) return;
-  const size_t crow = idx / kDh;
-  const int col = (int)(idx % kDh);
-  const int cgroup = (int)(crow / (kW16Waves * 16)), wv = (int)(crow / 16) % kW16Waves, cn = (int)(crow % 16);
+  if (idx >= crows * dh) return;
+  const size_t crow = idx / dh;
+  const int col = (int)(idx % dh);
+  const int cgroup = (int)(crow / (per_group * 16)), wv = (int)(crow / 16) % per_group, cn = (int)(crow % 16);
   const int per = a.gpx - a.full_px;
   const int xcd = cgroup / per, lt = cgroup % per;
   const int g_first = xcd * a.gpx;
@@ -926,17 +931,17 @@ __global__ void bwd_wgt16_reduce_kernel(BwdArgs a, size_t crows) {
   if (n_full + lt >= n_here) return;
   const int group = g_first + n_full + lt;
   const int nblk = a.E * a.de / 16;
-  const int wg_per_head = (nblk + kW16Waves - 1) / kW16Waves;
-  const int h = group / wg_per_head, blk = (group % wg_per_head) * kW16Waves + wv;
+  const int wg_per_head = (nblk + per_group - 1) / per_group;
+  const int h = group / wg_per_head, blk = (group % wg_per_head) * per_group + wv;
   if (blk >= nblk) return;
-  const size_t o = (((size_t)h * nblk + blk) * 16 + cn) * kDh + col;
+  const size_t o = (((size_t)h * nblk + blk) * 16 + cn) * dh + col;
   uint16_t* outs[3] = {a.dWg, a.dWu, a.dWd};
 #pragma unroll
   for (int which = 0; which < 3; ++which) {
     if (!outs[which]) continue;
     f32x4 sum = {0.f, 0.f, 0.f, 0.f};
     for (int sgm = 0; sgm < a.wsplit; ++sgm)
-      sum += *reinterpret_cast<const f32x4*>(a.WPws + ((size_t)sgm * 3 + which) * crows * kDh + idx);
+      sum += *reinterpret_cast<const f32x4*>(a.WPws + ((size_t)sgm * 3 + which) * crows * dh + idx);
     u32x2 pk = {pack_bf16(sum[0], sum[1]), pack_bf16(sum[2], sum[3])};
     *reinterpret_cast<u32x2*>(outs[which] + o) = pk;
   }
@@ -973,7 +978,8 @@ Wgt16Plan plan_wgt16(const Problem& p) {
   Wgt16Plan w;
   const int64_t nb = (p.N + 31) / 32;
   const int nblk = p.E * p.de / 16;
-  w.n_groups = p.H * ((nblk + kW16Waves - 1) / kW16Waves);
+  const int per_group = (p.dh == kW2Dh) ? kW2Blocks : kW16Waves;   // 16-neuron blocks per workgroup
+  w.n_groups = p.H * ((nblk + per_group - 1) / per_group);
   w.gpx = (w.n_groups + 7) / 8;
   w.full_px = w.gpx;
   w.segs = 1;
@@ -996,16 +1002,21 @@ Wgt16Plan plan_wgt16(const Problem& p) {
     w.full_px = full;
     w.blocks_per_seg = (nb + w.segs - 1) / w.segs;
     w.segs = (int)((nb + w.blocks_per_seg - 1) / w.blocks_per_seg);
-    w.crows = (size_t)8 * tail * (kW16Waves * 16);
+    w.crows = (size_t)8 * tail * (per_group * 16);
   }
   return w;
 }
 
+// bwd_wgt256_kernel addresses a block's rows with 32-bit byte offsets
+bool wgt256_takes(const Problem& p) {
+  return p.dh == kW2Dh && p.ldx < ((int64_t)1 << 24) && p.ldy < ((int64_t)1 << 24);
+}
+
 size_t wgt_split_bytes(const Problem& p) {
   if (p.N == 0) return 0;
-  if (p.dh == kDh) {
+  if (p.dh == kDh || wgt256_takes(p)) {
     const Wgt16Plan w16 = plan_wgt16(p);
-    return w16.segs > 1 ? (size_t)w16.segs * 3 * w16.crows * kDh * sizeof(float) : 0;
+    return w16.segs > 1 ? (size_t)w16.segs * 3 * w16.crows * p.dh * sizeof(float) : 0;
   }
   const WgtSplit w = plan_wgt_split(p);
   return w.segs > 1 ? (size_t)w.segs * 3 * p.H * p.E * p.de * p.dh * sizeof(float) : 0;
@@ -1278,6 +1289,406 @@ __global__ __launch_bounds__(64 * NW, DH == 64 ? 2 : 1) void bwd_wgt_dh_kernel(B
 }
 
 // ---------------------------------------------------------------------------
+// weight-major kernel for d_h = 256, two waves per SIMD
+//
+// The 16 neurons of a block have 3 x 16 x 256 resident operands and as many fp32 gradient
+// accumulators: more than one wave's 256 registers.  Two waves share the block instead: wave
+// `hf` of the pair owns columns 128 hf .. 128 hf + 127 of d_h and finishes tokens 16 hf ..
+// 16 hf + 15 of every block of 32.  Per block:
+//   M, N, dA [32 tok][16]: each wave contracts over its own 128 columns (24 MFMA) and hands the
+//       partial sums of the partner's 16 tokens over through LDS (exchange 1)
+//   a, dn, dm of its own 16 tokens: fp32 VALU on 4 elements per lane; the packed bf16 results
+//       go to the partner through LDS as well (exchange 2)
+//   dV^T[j][c] += dY^T a; dK^T += q^T dm; dU^T += q^T dn for the wave's own 128 rows j (24 MFMA)
+// so a wave needs 48 resident + 96 accumulator registers, as in bwd_wgt16_kernel, and the
+// workgroup's eight waves (four blocks of 16 neurons) run two per SIMD.  A step has two
+// barriers: A, after the partial sums are written, and B, after the packed results are.  Waves
+// 4-7 pass one barrier more before the loop and waves 0-3 one more after it, so that the two
+// waves of a SIMD are half a step apart: one does the arithmetic (between A and B) while the
+// other runs its 48 MFMAs (between B and the next A: the gradient products of block b, then
+// the recompute products of block b + 1, as one operand stream, at raised priority).
+// What bounds a step is instruction issue, not the MFMA pipe: a wave's stream of 44 LDS reads,
+// 32 waits and 48 MFMAs takes about 1250 cycles alone on its SIMD against 768 cycles of MFMA,
+// and the other wave's VALU and load instructions come on top.  Hence no address arithmetic in
+// the stream (all operand addresses are loop-invariant registers plus immediate offsets), the
+// arithmetic shared out over the pair, and the few staging loads per wave.
+// Token tiles ([32][256] bf16 of q and of dY, chunks permuted as in bwd_wgt_dh_kernel) go
+// global -> LDS directly into three stages; see the loop for when a stage may be requested again.
+// ---------------------------------------------------------------------------
+constexpr int kW2Waves = 8;
+constexpr int kW2Threads = 64 * kW2Waves;
+constexpr int kW2Tile = 32 * kW2Dh * 2;            // 16 KB
+constexpr int kW2Stages = 3;
+constexpr int kW2YRing = kW2Stages * kW2Tile;      // start of the dY ring
+constexpr int kW2RRing = 2 * kW2YRing;             // start of the r ring
+constexpr int kW2RSlot = kW2Waves * 64 * 4;
+// exchange slots per wave, read by its partner: 3 KB of partial sums, 1.5 KB of packed results
+constexpr int kW2Xchg1 = kW2RRing + kW2Stages * kW2RSlot;
+constexpr int kW2Xchg1Slot = 3 * 1024;
+constexpr int kW2Xchg2 = kW2Xchg1 + kW2Waves * kW2Xchg1Slot;
+constexpr int kW2Xchg2Slot = 3 * 512;
+constexpr int kW2LdsBytes = kW2Xchg2 + kW2Waves * kW2Xchg2Slot;
+static_assert(kW2LdsBytes <= 160 * 1024, "LDS of a CU");
+static_assert((kW2Stages - 1) * kW2Tile + 4096 < 65536, "LDS read offsets are 16-bit");
+constexpr int kW2Window = 4;   // operands kept in flight ahead of the one being consumed
+// Operand stream of a step (position = consumption order):
+//   0..15   transposed windows of block b: dY^T 0, q^T 0, dY^T 1, q^T 1 ..       (2 LDS reads each)
+//   16..23  q rows of block b + 1: own 16 tokens steps 0..3, the partner's 16    (1)
+//   24..31  dY rows of block b + 1                                                (1)
+// A pass that starts at position 16 does only the recompute products (the first block).
+constexpr int w2_instrs(int p) { return p < 16 ? 2 : 1; }
+constexpr int w2_issued_before(int c) { return c + kW2Window > 31 ? 31 : c + kW2Window; }
+constexpr int w2_pending(int c) {
+  int n = 0;
+  for (int p = c + 1; p <= w2_issued_before(c); ++p) n += w2_instrs(p);
+  return n;
+}
+
+__global__ __launch_bounds__(kW2Threads) void bwd_wgt256_kernel(BwdArgs a) {
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];   // (address bits are XORed: see below)
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int cn = lane & 15, gq = lane >> 4;
+  const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+  const int pair = wave_u >> 1, hf = wave_u & 1;
+  const bool lag = wave_u >= 4;
+  const int nblk = a.E * a.de / 16;              // 16-neuron blocks per head
+  const int wg_per_head = (nblk + kW2Blocks - 1) / kW2Blocks;
+  // work list as in bwd_wgt16_kernel: XCD x takes neuron groups x gpx .. (x+1) gpx - 1, first
+  // those that take all tokens, then, `wsplit` workgroups each, the groups of its last round
+  const int xcd = blockIdx.x & 7, widx = blockIdx.x >> 3;
+  const int g_first = xcd * a.gpx;
+  const int n_here = min(a.n_groups - g_first, a.gpx);
+  const int n_full = min(a.full_px, n_here);
+  int group, seg = 0, cgroup = 0;
+  bool split = false;
+  if (widx < n_full) {
+    group = g_first + widx;
+  } else {
+    const int j = widx - n_full, lt = j / a.wsplit;
+    if (n_full + lt >= n_here) return;   // whole workgroup leaves together
+    group = g_first + n_full + lt;
+    seg = j - lt * a.wsplit;
+    split = a.wsplit > 1;
+    cgroup = xcd * (a.gpx - a.full_px) + lt;
+  }
+  const int h = group / wg_per_head;
+  const int blk = (group % wg_per_head) * kW2Blocks + pair;
+  const bool active = blk < nblk;
+  const int blk_c = active ? blk : nblk - 1;     // idle pairs shadow a valid block, store nothing
+  const int64_t N = a.N;
+  const size_t row0 = ((size_t)h * nblk + blk_c) * 16;   // first neuron row of this pair
+  const int e_wave = blk_c / (a.de / 16);
+
+  // resident weight operands: lane (neuron cn, group gq) holds columns 128hf + 32ks + 8gq ..
+  bf16x8 Kf[4], Uf[4], Vf[4];
+  {
+    const size_t off = (row0 + cn) * kW2Dh + 128 * hf + 8 * gq;
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      Kf[ks] = *reinterpret_cast<const bf16x8*>(a.Wg + off + 32 * ks);
+      Uf[ks] = *reinterpret_cast<const bf16x8*>(a.Wu + off + 32 * ks);
+      Vf[ks] = *reinterpret_cast<const bf16x8*>(a.Wd + off + 32 * ks);
+    }
+  }
+  f32x4 dK[8], dU[8], dV[8];
+#pragma unroll
+  for (int jb = 0; jb < 8; ++jb) { dK[jb] = f32x4{0, 0, 0, 0}; dU[jb] = dK[jb]; dV[jb] = dK[jb]; }
+
+  // ---- staging -----------------------------------------------------------------
+  // Wave w moves rows 2w, 2w+1 and 2w+16, 2w+17 of the q and dY tiles (a 1 KB image of two
+  // rows per load; LDS position p of a row holds chunk (p & 16) | ((p & 15) ^ 2 (row % 8)),
+  // the same for rows 16 apart) and the 32 r values of its own sub-network.  Addresses are a
+  // wave-uniform base that advances block by block plus a 32-bit per-lane byte offset.
+  const float* Rw = a.Rws + ((size_t)h * a.E + e_wave) * N;
+  const int64_t nb = (N + 31) / 32;                       // all blocks of 32 tokens
+  const int64_t b0 = split ? seg * a.blocks_per_seg : 0;  // this workgroup's blocks: b0 .. b1-1
+  const int64_t b1 = (split && b0 + a.blocks_per_seg < nb) ? b0 + a.blocks_per_seg : nb;
+  auto lane_col = [&](int l) {   // element column inside the head of the chunk lane l moves
+    const int row = 2 * wave_u + (l >> 5), pos = l & 31;
+    return ((pos & 16) | ((pos & 15) ^ ((row & 7) << 1))) << 3;
+  };
+  const unsigned vx = (unsigned)(((2 * wave_u + (lane >> 5)) * a.ldx + lane_col(lane)) * 2);
+  const unsigned vy = (unsigned)(((2 * wave_u + (lane >> 5)) * a.ldy + lane_col(lane)) * 2);
+  const unsigned vr = 4 * (lane & 31);
+  const unsigned char* xbase = reinterpret_cast<const unsigned char*>(a.X + b0 * 32 * a.ldx + h * kW2Dh);
+  const unsigned char* ybase = reinterpret_cast<const unsigned char*>(a.dY + b0 * 32 * a.ldy + h * kW2Dh);
+  const unsigned char* rbase = reinterpret_cast<const unsigned char*>(Rw + b0 * 32);
+  // blocks are requested in order, each once: the bases just advance
+  auto dma = [&](int64_t blkidx, int stage) {
+    unsigned x0 = vx, x1 = vx + (unsigned)(32 * a.ldx), y0 = vy, y1 = vy + (unsigned)(32 * a.ldy), r0 = vr;
+    if (blkidx == nb - 1) {   // the last block may be ragged: rows past N read row N-1
+      int l = lane;
+      asm volatile("" : "+v"(l));   // recomputed here, not kept in registers through the loop
+      const int64_t last = N - 1 - blkidx * 32;   // >= 0
+      const int64_t ra = 2 * wave_u + (l >> 5), rb = ra + 16, rr = l & 31;
+      const int64_t ca = ra < last ? ra : last, cb = rb < last ? rb : last;
+      x0 = (unsigned)((ca * a.ldx + lane_col(l)) * 2);
+      x1 = (unsigned)((cb * a.ldx + lane_col(l)) * 2);
+      y0 = (unsigned)((ca * a.ldy + lane_col(l)) * 2);
+      y1 = (unsigned)((cb * a.ldy + lane_col(l)) * 2);
+      r0 = 4 * (unsigned)(rr < last ? rr : last);
+    }
+    unsigned char* dst = smem + stage * kW2Tile + wave_u * 1024;
+    global_to_lds_16B(xbase + x0, dst);
+    global_to_lds_16B(xbase + x1, dst + 8192);
+    global_to_lds_16B(ybase + y0, dst + kW2YRing);
+    global_to_lds_16B(ybase + y1, dst + kW2YRing + 8192);
+    __builtin_amdgcn_global_load_lds(
+        (__attribute__((address_space(1))) const void*)(rbase + r0),
+        (__attribute__((address_space(3))) void*)(smem + kW2RRing + stage * kW2RSlot + wave_u * 256),
+        4, 0, 0);
+    xbase += 64 * a.ldx;
+    ybase += 64 * a.ldy;
+    rbase += 128;
+  };
+  dma(b0, 0);
+  if (b0 + 1 < b1) dma(b0 + 1, 1);
+  if (b0 + 2 < b1) dma(b0 + 2, 2);
+
+  // ---- loop-invariant LDS addresses -----------------------------------------------
+  const unsigned lbase = lds_addr_of(smem);
+  // Row operands: token row cn (+16), 16-byte chunk 16hf + 4ks + gq; transposed operands: token
+  // rows 4gq + cn/4 (+16), columns 128hf + 16jb + 4(cn%4).  The chunk permutation is an XOR on
+  // address bits 5-7, so the address for step ks is that for step 0 ^ (ks << 6) and the one for
+  // row tile jb that for tile 0 ^ (jb << 5).
+  const unsigned qa0 = lbase + wdh_off<kW2Dh>(cn, 16 * hf + gq), ya0 = qa0 + kW2YRing;
+  const unsigned ta0 = lbase + wdh_off8<kW2Dh>(4 * gq + (cn >> 2), 128 * hf + 4 * (cn & 3)), tya0 = ta0 + kW2YRing;
+  const unsigned raddr = lbase + kW2RRing + wave * 256 + 16 * gq;   // r of MFMA rows 4gq.. (+64: next 16 tokens)
+  // exchange slots: own (written) and the partner's (read)
+  float* x1own = reinterpret_cast<float*>(smem + kW2Xchg1 + wave_u * kW2Xchg1Slot) + 4 * lane;
+  const unsigned x1par = lbase + kW2Xchg1 + (wave ^ 1) * kW2Xchg1Slot + 16 * lane;
+  unsigned* x2own = reinterpret_cast<unsigned*>(smem + kW2Xchg2 + wave_u * kW2Xchg2Slot) + 2 * lane;
+  const unsigned x2par = lbase + kW2Xchg2 + (wave ^ 1) * kW2Xchg2Slot + 8 * lane;
+  // all 24 operand addresses stay in registers (immediate offsets select stage and token
+  // half): an XOR in front of every read costs the stream more than the registers do
+  unsigned qx[4], yx[4], tx[8], tyx[8];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) { qx[i] = qa0 ^ (i << 6); yx[i] = ya0 ^ (i << 6); }
+#pragma unroll
+  for (int i = 0; i < 8; ++i) { tx[i] = ta0 ^ (i << 5); tyx[i] = tya0 ^ (i << 5); }
+
+  f32x4 M[2], Nn[2], Ad[2];   // this wave's partial M, N, dA of the next block to be finished
+  bf16x8 agf, dmf, dnf;       // B operands of the gradient products of the current block
+
+  // One pass over the operand stream from position FIRST: the gradient products of the block
+  // in stage S (FIRST = 0), then the partial recompute products of the block in stage S + 1.
+  // Before item c is consumed everything up to kW2Window positions ahead of it has been
+  // issued, and the wait names exactly the number of reads issued after it.
+  auto stream = [&](auto S_, auto FIRST_, auto PREFETCH_ONLY_, bf16x8 (&op)[16], s16x4 (&xlo)[16], s16x4 (&xhi)[16]) {
+    constexpr int S = decltype(S_)::value, FIRST = decltype(FIRST_)::value;
+    constexpr bool PREFETCH_ONLY = decltype(PREFETCH_ONLY_)::value;
+    constexpr int SO = S * kW2Tile, SN = ((S + 1) % kW2Stages) * kW2Tile;
+
+    auto issue = [&](auto P_) {
+      constexpr int P = decltype(P_)::value;
+      if constexpr (P < 16) {
+        constexpr int J = P, JB = J >> 1;
+        if constexpr ((J & 1) == 0) {
+          xlo[J] = lds_read_tr16_untracked<SO>(tyx[JB]);
+          xhi[J] = lds_read_tr16_untracked<SO + 8192>(tyx[JB]);   // 16 rows further: same permutation
+        } else {
+          xlo[J] = lds_read_tr16_untracked<SO>(tx[JB]);
+          xhi[J] = lds_read_tr16_untracked<SO + 8192>(tx[JB]);
+        }
+      } else if constexpr (P < 24) {
+        constexpr int I = P - 16;
+        op[I] = lds_read_b128_untracked<SN + (I >> 2) * 8192>(qx[I & 3]);
+      } else {
+        constexpr int I = P - 16;
+        op[I] = lds_read_b128_untracked<SN + ((I - 8) >> 2) * 8192>(yx[I & 3]);
+      }
+    };
+    if constexpr (PREFETCH_ONLY) {
+      static_for<FIRST, w2_issued_before(FIRST) + 1>(issue);
+    } else {
+      auto advance = [&](auto C_) {   // what item C needs in flight beyond what item C-1 required
+        constexpr int C = decltype(C_)::value;
+        if constexpr (C > FIRST) static_for<w2_issued_before(C - 1) + 1, w2_issued_before(C) + 1>(issue);
+      };
+      static_for<FIRST, 16>([&](auto C_) {
+        constexpr int C = decltype(C_)::value, J = C, JB = J >> 1;
+        advance(C_);
+        lds_wait<w2_pending(C)>(xlo[J], xhi[J]);
+        const bf16x8 xt = join_tr(xlo[J], xhi[J]);
+        if constexpr ((J & 1) == 0) {
+          dV[JB] = mfma16(xt, agf, dV[JB]);
+        } else {
+          dK[JB] = mfma16(xt, dmf, dK[JB]);
+          dU[JB] = mfma16(xt, dnf, dU[JB]);
+        }
+      });
+#pragma unroll
+      for (int t = 0; t < 2; ++t) { M[t] = f32x4{0, 0, 0, 0}; Nn[t] = M[t]; Ad[t] = M[t]; }
+      static_for<16, 24>([&](auto C_) {
+        constexpr int C = decltype(C_)::value, I = C - 16;
+        advance(C_);
+        lds_wait<w2_pending(C)>(op[I]);
+        M[I >> 2] = mfma16(op[I], Kf[I & 3], M[I >> 2]);
+        Nn[I >> 2] = mfma16(op[I], Uf[I & 3], Nn[I >> 2]);
+      });
+      static_for<24, 32>([&](auto C_) {
+        constexpr int C = decltype(C_)::value, I = C - 16;
+        advance(C_);
+        lds_wait<w2_pending(C)>(op[I]);
+        Ad[(I - 8) >> 2] = mfma16(op[I], Vf[I & 3], Ad[(I - 8) >> 2]);
+      });
+      // exchange 1: the partial sums of the partner's tokens (wave hf finishes tokens 16hf ..)
+      if (hf == 0) {
+        *reinterpret_cast<f32x4*>(x1own) = M[1];
+        *reinterpret_cast<f32x4*>(x1own + 256) = Nn[1];
+        *reinterpret_cast<f32x4*>(x1own + 512) = Ad[1];
+      } else {
+        *reinterpret_cast<f32x4*>(x1own) = M[0];
+        *reinterpret_cast<f32x4*>(x1own + 256) = Nn[0];
+        *reinterpret_cast<f32x4*>(x1own + 512) = Ad[0];
+      }
+    }
+  };
+  using T = std::true_type;
+  using F = std::false_type;
+  using C0 = std::integral_constant<int, 0>;
+  using C1 = std::integral_constant<int, 1>;
+  using C2 = std::integral_constant<int, 2>;
+  using C16 = std::integral_constant<int, 16>;
+
+  __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): the first blocks have landed
+  __syncthreads();
+  {
+    // recompute products of block b0 (stage 0 = the stage after stage 2)
+    bf16x8 op[16];
+    s16x4 xlo[16], xhi[16];
+    stream(C2{}, C16{}, T{}, op, xlo, xhi);
+    stream(C2{}, C16{}, F{}, op, xlo, xhi);
+  }
+
+  // Between the barriers A and B of block b (in stage S), for wave HF of a pair: finish M, N,
+  // dA of the tokens 16 HF .. of the block, arithmetic on them, packed results to the partner;
+  // after B the partner's packed results complete the B operands of the gradient products.
+  auto finish = [&](int64_t b, bool req, auto S_, auto HF_, bf16x8 (&op)[16], s16x4 (&xlo)[16], s16x4 (&xhi)[16]) {
+    constexpr int S = decltype(S_)::value, HF = decltype(HF_)::value, S2 = (S + 2) % kW2Stages;
+    f32x4 pp[3], rv;   // the partner's partial sums of these tokens; their r
+#pragma unroll
+    for (int i = 0; i < 3; ++i)
+      asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(pp[i]) : "v"(x1par), "n"(i * 1024));
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(rv) : "v"(raddr), "n"(S * kW2RSlot + 64 * HF));
+    stream(S_, C0{}, T{}, op, xlo, xhi);   // first transposed windows of block b: in flight under the arithmetic
+    asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(pp[0]), "+v"(pp[1]), "+v"(pp[2]), "+v"(rv) : "n"(2 * (kW2Window + 1)));
+    if (b == nb - 1) {   // rows past N were read from row N-1: give them r = 0
+      asm volatile("" ::: "memory");   // (a real branch: the last block only)
+#pragma unroll
+      for (int v = 0; v < 4; ++v)
+        if (b * 32 + 16 * HF + 4 * gq + v >= N) rv[v] = 0.f;
+    }
+    float Aw[4], Dn[4], Dm[4];
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      const float m = M[HF][v] + pp[0][v], n = Nn[HF][v] + pp[1][v], d = Ad[HF][v] + pp[2][v];
+      const float e = __builtin_amdgcn_exp2f(-MHFFN_LOG2E * m);
+      const float sg = __builtin_amdgcn_rcpf(1.0f + e);
+      const float sw = rv[v] * sg;
+      const float x = (1.0f + m) - m * sg;   // silu'(m) = sg (1 + m - silu(m))
+      const float pw = m * sw;
+      Aw[v] = pw * n;
+      Dn[v] = pw * d;
+      Dm[v] = ((n * sw) * x) * d;
+    }
+    const u32x2 pa_o = {pack_bf16(Aw[0], Aw[1]), pack_bf16(Aw[2], Aw[3])};
+    const u32x2 pm_o = {pack_bf16(Dm[0], Dm[1]), pack_bf16(Dm[2], Dm[3])};
+    const u32x2 pn_o = {pack_bf16(Dn[0], Dn[1]), pack_bf16(Dn[2], Dn[3])};
+    // exchange 2 (the stores also keep the arithmetic on this side of the barrier)
+    *reinterpret_cast<u32x2*>(x2own) = pa_o;
+    *reinterpret_cast<u32x2*>(x2own + 128) = pm_o;
+    *reinterpret_cast<u32x2*>(x2own + 256) = pn_o;
+    // ---- barrier B: packed results written; early waves: their request of a step ago has landed
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    if (!lag) __builtin_amdgcn_s_waitcnt(0x0F70);
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    s16x4 pa_p, pm_p, pn_p;
+    asm volatile("ds_read_b64 %0, %1" : "=v"(pa_p) : "v"(x2par));
+    asm volatile("ds_read_b64 %0, %1 offset:512" : "=v"(pm_p) : "v"(x2par));
+    asm volatile("ds_read_b64 %0, %1 offset:1024" : "=v"(pn_p) : "v"(x2par));
+    if (!lag && req) dma(b + 2, S2);
+    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(pa_p), "+v"(pm_p), "+v"(pn_p));
+    // k-slot s = 4t + v of every gradient product is token 16t + 4gq + v
+    const s16x4 ao = __builtin_bit_cast(s16x4, pa_o), mo = __builtin_bit_cast(s16x4, pm_o);
+    const s16x4 no = __builtin_bit_cast(s16x4, pn_o);
+    if constexpr (HF == 0) { agf = join_tr(ao, pa_p); dmf = join_tr(mo, pm_p); dnf = join_tr(no, pn_p); }
+    else { agf = join_tr(pa_p, ao); dmf = join_tr(pm_p, mo); dnf = join_tr(pn_p, no); }
+  };
+  // block b: barrier A, the part above, then the stream of gradient products of b and recompute
+  // products of b + 1
+  auto step = [&](int64_t b, auto S_) {
+    constexpr int S = decltype(S_)::value, S2 = (S + 2) % kW2Stages;
+    const bool req = (b + 2 >= b0 + 3) && (b + 2 < b1);   // the first three blocks were requested up front
+    // ---- barrier A: partial sums written; late waves: their request of a step ago has landed
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    if (lag) __builtin_amdgcn_s_waitcnt(0x0F70);
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    if (lag && req) dma(b + 2, S2);
+    bf16x8 op[16];
+    s16x4 xlo[16], xhi[16];
+    if (hf == 0) finish(b, req, S_, C0{}, op, xlo, xhi);
+    else finish(b, req, S_, C1{}, op, xlo, xhi);
+    // the wave that feeds the MFMA pipe goes first; the other wave's arithmetic fills the gaps
+    __builtin_amdgcn_s_setprio(1);
+    stream(S_, C0{}, F{}, op, xlo, xhi);
+    __builtin_amdgcn_s_setprio(0);
+  };
+  // Waves w and w + 4 share a SIMD: waves 4-7 pass one barrier more before the loop, waves 0-3
+  // one more after it.  Barrier events then alternate between (early waves at A, late at B) and
+  // (early at B, late at A).  Block b is last read in the early waves' pass after their B(b)
+  // and in the late waves' pass one event later, which ends at the event where the early waves
+  // are at B(b+1) and the late ones at A(b+1): both request block b + 3 into its stage right
+  // after that event, and wait for that request two events (one step) later, before the
+  // event after which block b + 3 is first read.
+  if (lag) {
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+  }
+  for (int64_t b = b0; b < b1; b += 3) {
+    step(b, C0{});
+    if (b + 1 < b1) step(b + 1, C1{});
+    if (b + 2 < b1) step(b + 2, C2{});
+  }
+  // (the last pass has run the recompute products on a block that does not exist)
+  if (!lag) __builtin_amdgcn_s_barrier();
+
+  if (active && split) {
+    // fp32 partial gradients of this token segment: [seg][K | U | V][split group][block][16][256]
+    const size_t rows = (size_t)8 * (a.gpx - a.full_px) * (kW2Blocks * 16);
+    float* dst = a.WPws + (((size_t)seg * 3) * rows + ((size_t)cgroup * kW2Blocks + pair) * 16 + cn) * kW2Dh +
+                 128 * hf + 4 * gq;
+#pragma unroll
+    for (int jb = 0; jb < 8; ++jb) {
+      *reinterpret_cast<f32x4*>(dst + 16 * jb) = dK[jb];
+      *reinterpret_cast<f32x4*>(dst + rows * kW2Dh + 16 * jb) = dU[jb];
+      *reinterpret_cast<f32x4*>(dst + 2 * rows * kW2Dh + 16 * jb) = dV[jb];
+    }
+  } else if (active) {
+    // accumulators are [j][c]: lane = neuron column cn, register v = row 128hf + 16jb + 4gq + v
+    const size_t off = (row0 + cn) * kW2Dh + 128 * hf + 4 * gq;
+#pragma unroll
+    for (int jb = 0; jb < 8; ++jb) {
+      const size_t o = off + 16 * jb;
+      if (a.dWg) {
+        u32x2 pk = {pack_bf16(dK[jb][0], dK[jb][1]), pack_bf16(dK[jb][2], dK[jb][3])};
+        *reinterpret_cast<u32x2*>(a.dWg + o) = pk;
+      }
+      if (a.dWu) {
+        u32x2 pk = {pack_bf16(dU[jb][0], dU[jb][1]), pack_bf16(dU[jb][2], dU[jb][3])};
+        *reinterpret_cast<u32x2*>(a.dWu + o) = pk;
+      }
+      if (a.dWd) {
+        u32x2 pk = {pack_bf16(dV[jb][0], dV[jb][1]), pack_bf16(dV[jb][2], dV[jb][3])};
+        *reinterpret_cast<u32x2*>(a.dWd + o) = pk;
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
 // dW_r[h][j][e] = sum_tok q[tok][j] dp[tok][e]: partial sums per token split,
 // then a fixed-order reduction (deterministic).
 // ---------------------------------------------------------------------------
@@ -1444,11 +1855,16 @@ int launch_wgt16(const Problem& p, BwdArgs a, hipStream_t stream) {
   a.n_groups = wsp.n_groups;
   const unsigned grid = 8u * (unsigned)(wsp.full_px + (wsp.gpx - wsp.full_px) * wsp.segs);
   a.n_items = grid;
-  if (hipError_t e = LdsLimit<&bwd_wgt16_kernel, kFullLds>::ensure(); e != hipSuccess) return (int)e;
-  hipLaunchKernelGGL(bwd_wgt16_kernel, dim3(grid), dim3(kW16Threads), kW16LdsBytes, stream, a);
+  if (p.dh == kW2Dh) {
+    if (hipError_t e = LdsLimit<&bwd_wgt256_kernel, kFullLds>::ensure(); e != hipSuccess) return (int)e;
+    hipLaunchKernelGGL(bwd_wgt256_kernel, dim3(grid), dim3(kW2Threads), kW2LdsBytes, stream, a);
+  } else {
+    if (hipError_t e = LdsLimit<&bwd_wgt16_kernel, kFullLds>::ensure(); e != hipSuccess) return (int)e;
+    hipLaunchKernelGGL(bwd_wgt16_kernel, dim3(grid), dim3(kW16Threads), kW16LdsBytes, stream, a);
+  }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || wsp.segs == 1) return (int)e;
-  const size_t count4 = wsp.crows * kDh / 4;
+  const size_t count4 = wsp.crows * p.dh / 4;
   hipLaunchKernelGGL(bwd_wgt16_reduce_kernel, dim3((unsigned)((count4 + 255) / 256)), dim3(256), 0,
                      stream, a, wsp.crows);
   return (int)hipGetLastError();
@@ -1584,8 +2000,8 @@ int launch_bwd(const Problem& p, int dtype, const void* X, const void* Wg, const
   if (mark(1) != hipSuccess) return (int)hipErrorInvalidHandle;
   if (dWg || dWu || dWd) {
     if (p.dh == 64) rc = launch_wgt_dh<64, 4>(p, a, stream);
-    else if (p.dh == 256) rc = launch_wgt_dh<256, 4>(p, a, stream);
-    else rc = launch_wgt16(p, a, stream);
+    else if (p.dh == 256 && !wgt256_takes(p)) rc = launch_wgt_dh<256, 4>(p, a, stream);
+    else rc = launch_wgt16(p, a, stream);   // d_h = 128 and 256
     if (rc) return rc;
   }
   if (mark(2) != hipSuccess) return (int)hipErrorInvalidHandle;

@@ -34,6 +34,30 @@ def test_backward_small_shapes(N, H, dh, E, de):
     check_all(got, ref, TOL["bf16"], single_subnetwork=(E == 1))
 
 
+@pytest.mark.parametrize("N,H,E,de", [
+    # 54 groups of four 16-neuron blocks: 7 per XCD, less than a round, every group shares its
+    # tokens out over four workgroups
+    (2048, 9, 4, 96),
+    # 300 groups (98 blocks per head: the last group of a head has two idle wave pairs): 38 per XCD
+    # = 32 that take all tokens + 6 that share them out over two workgroups; ragged last block
+    (1100, 12, 7, 224)])
+def test_dh256_weight_major_rounds_and_token_shares(N, H, E, de):
+    """d_h = 256 weight-major kernel on shapes whose neuron groups leave a partly filled last
+    round per XCD: those groups write fp32 partials per token segment, summed in fixed order by
+    a second kernel.  Every weight row against the oracle, bit-identical from run to run."""
+    from tests.helpers import check_parity
+    w = small_workload("hw_rounds", N, H, E, de, "bf16", dh=256, backward=True)
+    desc = mhffn.Desc(N, H, 256, E, de, 0, 0, mhffn.BF16, mhffn.ROUTE_PARAMS, w.eps)
+    a256 = lambda x: (x + 255) // 256 * 256
+    assert mhffn.workspace_bytes(desc, mhffn.OP_BACKWARD) > 2 * a256(N * H * E * 4) + a256(H * 64 * 256 * E * 4)
+    d, got = run_backward(w, seed=N, want=("dW_gate", "dW_up", "dW_down"))
+    _, again = run_backward(w, seed=N, want=("dW_gate", "dW_up", "dW_down"))
+    for k in got:
+        assert np.array_equal(got[k], again[k]), k
+    ref = orc.backward(d["X"], d["W_gate"], d["W_up"], d["W_down"], d["W_r"], d["dY"], w.eps)
+    check_parity(got, {k: ref[k] for k in got}, TOL["bf16"], w.d_head, "rounds256")
+
+
 @pytest.mark.parametrize("dh", [64, 256])
 def test_weights_mode(dh):
     w = small_workload("hw_weights", 333, 2, 6, 64, "bf16", dh=dh, backward=True)
