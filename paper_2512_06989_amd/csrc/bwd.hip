@@ -952,7 +952,7 @@ __global__ void bwd_wgt16_reduce_kernel(BwdArgs a, size_t crows) {
 struct WgtSplit { int segs; int64_t blocks_per_seg; };
 // waves per workgroup and workgroups the chip holds at once, per head width
 constexpr int wgt_waves(int dh) { return dh == kDh ? kW16Waves : 4; }
-constexpr int wgt_slots(int dh) { return dh == 64 ? 512 : 256; }
+constexpr int wgt_slots(int dh) { return dh == 64 ? 768 : 256; }
 WgtSplit plan_wgt_split(const Problem& p) {
   const int64_t nb = (p.N + 31) / 32;
   const int waves = wgt_waves(p.dh), slots = wgt_slots(p.dh);
@@ -1067,7 +1067,6 @@ __global__ __launch_bounds__(64 * NW, DH == 64 ? 2 : 1) void bwd_wgt_dh_kernel(B
   constexpr int kTileBytes = 32 * DH * 2;
   constexpr int CHUNKS = 32 * CPR;
   constexpr int CH = (CHUNKS + THREADS - 1) / THREADS;
-  constexpr bool kAllLoad = (CHUNKS % THREADS == 0);
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];   // 2 x (q tile | dY tile)
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int cn = lane & 15, gq = lane >> 4;
@@ -1100,7 +1099,12 @@ __global__ __launch_bounds__(64 * NW, DH == 64 ? 2 : 1) void bwd_wgt_dh_kernel(B
 #pragma unroll
   for (int jb = 0; jb < JB; ++jb) { dK[jb] = f32x4{0, 0, 0, 0}; dU[jb] = dK[jb]; dV[jb] = dK[jb]; }
 
-  // ---- staging: rows past N are zero (and get r = 0), so they add nothing ----------
+  // ---- staging: rows past N are read from row N-1 (finite data) and get r = 0, so they add
+  // nothing.  The loop is bound by instruction issue (at d_h = 64 the arithmetic alone keeps
+  // the VALU busier than the products keep the MFMA pipe), so everything around it is kept
+  // short: source pointers that advance block by block, r as two 16-byte loads, LDS read
+  // addresses in registers with the buffer as an immediate offset, no per-row branches.
+  static_assert(CHUNKS % THREADS == 0, "every thread moves CH chunks of each tile");
   const int64_t nb = (N + 31) / 32;
   const int64_t b0 = seg * a.blocks_per_seg;              // this workgroup's blocks: b0 .. b1-1
   const int64_t b1 = b0 + a.blocks_per_seg < nb ? b0 + a.blocks_per_seg : nb;
@@ -1108,70 +1112,87 @@ __global__ __launch_bounds__(64 * NW, DH == 64 ? 2 : 1) void bwd_wgt_dh_kernel(B
   // at the end of the step) and the loads of block b+2 are in flight into the other.  At
   // d_h = 256 there are no registers for a second set: one set, requested one block ahead.
   constexpr int SETS = (DH == 256) ? 1 : 2;
+  constexpr int RSTEP = THREADS / CPR;          // rows between a thread's chunks
   u32x4 xreg[SETS][CH], yreg[SETS][CH];
-  float rnext[SETS][2][4];
+  f32x4 rnext[SETS][2];
+  typedef float f32x4_a4 __attribute__((ext_vector_type(4), aligned(4)));
+  const int srow = tid / CPR, scol = h * DH + (tid % CPR) * 8;
+  // blocks are loaded in order, each once: the pointers just advance
+  const uint16_t* xp = a.X + (b0 * 32 + srow) * a.ldx + scol;
+  const uint16_t* yp = a.dY + (b0 * 32 + srow) * a.ldy + scol;
+  const float* rp = Rw + b0 * 32 + 4 * gq;
   auto gload = [&](int64_t b, auto S_) {
     constexpr int S = decltype(S_)::value;
+    if (b != nb - 1) {
 #pragma unroll
-    for (int i = 0; i < CH; ++i) {
-      const int chunk = tid + THREADS * i;
-      if (!kAllLoad && chunk >= CHUNKS) continue;
-      const int64_t t = b * 32 + chunk / CPR;
-      const int col = h * DH + (chunk % CPR) * 8;
-      u32x4 vx = {0, 0, 0, 0}, vy = {0, 0, 0, 0};
-      if (t < N) {
-        vx = *reinterpret_cast<const u32x4*>(a.X + t * a.ldx + col);
-        vy = *reinterpret_cast<const u32x4*>(a.dY + t * a.ldy + col);
+      for (int i = 0; i < CH; ++i) {
+        xreg[S][i] = *reinterpret_cast<const u32x4*>(xp + (int64_t)(RSTEP * i) * a.ldx);
+        yreg[S][i] = *reinterpret_cast<const u32x4*>(yp + (int64_t)(RSTEP * i) * a.ldy);
       }
-      xreg[S][i] = vx;
-      yreg[S][i] = vy;
+      rnext[S][0] = *reinterpret_cast<const f32x4_a4*>(rp);
+      rnext[S][1] = *reinterpret_cast<const f32x4_a4*>(rp + 16);
+    } else {   // the last block may be ragged
+#pragma unroll
+      for (int i = 0; i < CH; ++i) {
+        int64_t t = b * 32 + srow + RSTEP * i;
+        t = t < N ? t : N - 1;
+        xreg[S][i] = *reinterpret_cast<const u32x4*>(a.X + t * a.ldx + scol);
+        yreg[S][i] = *reinterpret_cast<const u32x4*>(a.dY + t * a.ldy + scol);
+      }
+#pragma unroll
+      for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+          const int64_t t = b * 32 + 16 * tb + 4 * gq + v;
+          rnext[S][tb][v] = (t < N) ? Rw[t] : 0.f;
+        }
     }
-#pragma unroll
-    for (int tb = 0; tb < 2; ++tb)
-#pragma unroll
-      for (int v = 0; v < 4; ++v) {
-        const int64_t t = b * 32 + 16 * tb + 4 * gq + v;
-        rnext[S][tb][v] = (t < N) ? Rw[t] : 0.f;
-      }
+    xp += 32 * a.ldx;
+    yp += 32 * a.ldy;
+    rp += 32;
   };
-  auto lstore = [&](int buf, auto S_) {
+  int soff[CH];   // where this thread's chunks go in a tile
+#pragma unroll
+  for (int i = 0; i < CH; ++i) soff[i] = wdh_off<DH>(srow + RSTEP * i, tid % CPR);
+  auto lstore = [&](auto BUF_, auto S_) {
     constexpr int S = decltype(S_)::value;
-    unsigned char* dst = smem + buf * 2 * kTileBytes;
+    unsigned char* dst = smem + decltype(BUF_)::value * 2 * kTileBytes;
 #pragma unroll
     for (int i = 0; i < CH; ++i) {
-      const int chunk = tid + THREADS * i;
-      if (!kAllLoad && chunk >= CHUNKS) continue;
-      const int off = wdh_off<DH>(chunk / CPR, chunk % CPR);
-      *reinterpret_cast<u32x4*>(dst + off) = xreg[S][i];
-      *reinterpret_cast<u32x4*>(dst + kTileBytes + off) = yreg[S][i];
+      *reinterpret_cast<u32x4*>(dst + soff[i]) = xreg[S][i];
+      *reinterpret_cast<u32x4*>(dst + kTileBytes + soff[i]) = yreg[S][i];
     }
   };
   using S0 = std::integral_constant<int, 0>;
   using SB = std::integral_constant<int, SETS - 1>;   // the second set, if there is one
+  using B0 = std::integral_constant<int, 0>;
+  using B1 = std::integral_constant<int, 1>;
   gload(b0, S0{});
   if (SETS == 2 && b0 + 1 < b1) gload(b0 + 1, SB{});
-  lstore((int)(b0 & 1), S0{});
-  float rv[2][4];
+  lstore(B0{}, S0{});
+  // LDS read addresses (buffer, tensor and token half are immediate offsets): rows of the
+  // q / dY tiles: token row cn (+16), columns 32ks + 8gq ..; transposed windows: lane (cn, gq)
+  // points at token row 4gq + cn/4 (+16), columns 16jb + 4(cn%4) ..
+  const unsigned lbase = lds_addr_of(smem);
+  unsigned arow[KS], atr[JB];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) arow[ks] = lbase + wdh_off<DH>(cn, 4 * ks + gq);
+#pragma unroll
+  for (int jb = 0; jb < JB; ++jb) atr[jb] = lbase + wdh_off8<DH>(4 * gq + (cn >> 2), 16 * jb + 4 * (cn & 3));
   __syncthreads();
 
-  // block b: its tiles are in LDS buffer b & 1 and its r in register set SL, which is then
+  // block b: its tiles are in LDS buffer BUF and its r in register set SL, which is then
   // free and receives block b+2; SS holds block b+1
-  auto step = [&](int64_t b, auto SL, auto SS) {
+  auto step = [&](int64_t b, auto BUF_, auto SL, auto SS) {
+    constexpr int BO = decltype(BUF_)::value * 2 * kTileBytes;   // dY tile: + kTileBytes
     const bool more = (b + 1 < b1);
-#pragma unroll
-    for (int tb = 0; tb < 2; ++tb)
-#pragma unroll
-      for (int v = 0; v < 4; ++v) rv[tb][v] = rnext[decltype(SL)::value][tb][v];
+    const f32x4 rv0 = rnext[decltype(SL)::value][0], rv1 = rnext[decltype(SL)::value][1];
     if (b + SETS < b1) gload(b + SETS, SL);
-    const unsigned char* qt = smem + (b & 1) * 2 * kTileBytes;   // dY tile: + kTileBytes
 
     // All LDS operands of the step form one stream, issued untracked kDhWindow items ahead
     // of their use with counted waits (the compiler, left alone, waits for each read right
-    // after issuing it):
-    //   items 0 .. NA-1   rows of the q / dY tiles: token row 16tb + cn, columns 32ks + 8gq ..
-    //   items NA ..       transposed windows, dY^T and q^T alternating: lane (cn, gq) points at
-    //                     token row 4gq + cn/4 (and + 16), columns 16jb + 4(cn%4) ..
-    const unsigned qb = lds_addr_of(qt);
+    // after issuing it): items 0 .. NA-1 rows of the q / dY tiles, items NA .. transposed
+    // windows, dY^T and q^T alternating.
     constexpr int NA = 4 * KS, NTOT = NA + 2 * JB;
     bf16x8 opa[NA];
     s16x4 xlo[2 * JB], xhi[2 * JB];
@@ -1179,12 +1200,11 @@ __global__ __launch_bounds__(64 * NW, DH == 64 ? 2 : 1) void bwd_wgt_dh_kernel(B
       constexpr int P = decltype(P_)::value;
       if constexpr (P < NA) {
         constexpr int tb = P / (2 * KS), ks = (P / 2) % KS, which = P & 1;   // 0: q, 1: dY
-        opa[P] = lds_read_b128_untracked<which * kTileBytes>(qb + wdh_off<DH>(16 * tb + cn, 4 * ks + gq));
+        opa[P] = lds_read_b128_untracked<BO + which * kTileBytes + tb * 16 * 2 * DH>(arow[ks]);   // 16 rows further: same swizzle
       } else {
-        constexpr int J = P - NA, jb = J >> 1, TO = (J & 1) ? 0 : kTileBytes;  // even: dY^T, odd: q^T
-        const unsigned ad = qb + wdh_off8<DH>(4 * gq + (cn >> 2), 16 * jb + 4 * (cn & 3));
-        xlo[J] = lds_read_tr16_untracked<TO>(ad);
-        xhi[J] = lds_read_tr16_untracked<TO + 16 * 2 * DH>(ad);   // 16 rows further: same swizzle
+        constexpr int J = P - NA, jb = J >> 1, TO = BO + ((J & 1) ? 0 : kTileBytes);  // even: dY^T, odd: q^T
+        xlo[J] = lds_read_tr16_untracked<TO>(atr[jb]);
+        xhi[J] = lds_read_tr16_untracked<TO + 16 * 2 * DH>(atr[jb]);
       }
     };
     auto advance = [&](auto C_) {
@@ -1210,17 +1230,18 @@ __global__ __launch_bounds__(64 * NW, DH == 64 ? 2 : 1) void bwd_wgt_dh_kernel(B
     // 4tb + v of the gradient products
     float ag[8], dm[8], dn[8];
 #pragma unroll
-    for (int tb = 0; tb < 2; ++tb)
-#pragma unroll
-      for (int v = 0; v < 4; ++v) {
-        const float m = M[tb][v], n = Nn[tb][v], da = Ad[tb][v], rw = rv[tb][v];
-        const float sg = sigmoid_fast(m);
-        const float silu = m * sg;
-        const float rda = rw * da;
-        ag[4 * tb + v] = rw * silu * n;
-        dn[4 * tb + v] = rda * silu;
-        dm[4 * tb + v] = rda * n * fmaf(silu, 1.0f - sg, sg);
-      }
+    for (int i = 0; i < 8; ++i) {
+      const int tb = i >> 2, v = i & 3;
+      const float m = M[tb][v], n = Nn[tb][v], da = Ad[tb][v], rw = tb ? rv1[v] : rv0[v];
+      const float t = __builtin_amdgcn_exp2f(-MHFFN_LOG2E * m);
+      const float sg = __builtin_amdgcn_rcpf(1.0f + t);
+      const float sw = rw * sg;
+      const float x = (1.0f + m) - m * sg;   // silu'(m) = sg (1 + m - silu(m))
+      const float pw = m * sw;
+      ag[i] = pw * n;
+      dn[i] = pw * da;
+      dm[i] = ((n * sw) * x) * da;
+    }
     u32x4 pa, pm, pn;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -1244,16 +1265,12 @@ __global__ __launch_bounds__(64 * NW, DH == 64 ? 2 : 1) void bwd_wgt_dh_kernel(B
         dU[jb] = mfma16(xt, dnf, dU[jb]);
       }
     });
-    if (more) lstore((int)((b + 1) & 1), SS);
+    if (more) lstore(std::integral_constant<int, 1 - decltype(BUF_)::value>{}, SS);
     __syncthreads();
   };
-  if constexpr (SETS == 1) {
-    for (int64_t b = b0; b < b1; ++b) step(b, S0{}, S0{});
-  } else {
-    for (int64_t b = b0; b < b1; b += 2) {
-      step(b, S0{}, SB{});
-      if (b + 1 < b1) step(b + 1, SB{}, S0{});
-    }
+  for (int64_t b = b0; b < b1; b += 2) {
+    step(b, B0{}, S0{}, SB{});
+    if (b + 1 < b1) step(b + 1, B1{}, SB{}, S0{});
   }
 
   if (active && a.wsplit > 1) {
@@ -1271,6 +1288,272 @@ __global__ __launch_bounds__(64 * NW, DH == 64 ? 2 : 1) void bwd_wgt_dh_kernel(B
     const size_t off = (row0 + cn) * DH + 4 * gq;
 #pragma unroll
     for (int jb = 0; jb < JB; ++jb) {
+      const size_t o = off + 16 * jb;
+      if (a.dWg) {
+        u32x2 pk = {pack_bf16(dK[jb][0], dK[jb][1]), pack_bf16(dK[jb][2], dK[jb][3])};
+        *reinterpret_cast<u32x2*>(a.dWg + o) = pk;
+      }
+      if (a.dWu) {
+        u32x2 pk = {pack_bf16(dU[jb][0], dU[jb][1]), pack_bf16(dU[jb][2], dU[jb][3])};
+        *reinterpret_cast<u32x2*>(a.dWu + o) = pk;
+      }
+      if (a.dWd) {
+        u32x2 pk = {pack_bf16(dV[jb][0], dV[jb][1]), pack_bf16(dV[jb][2], dV[jb][3])};
+        *reinterpret_cast<u32x2*>(a.dWd + o) = pk;
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// weight-major kernel for d_h = 64
+//
+// Same decomposition as bwd_wgt16_kernel (one wave = 16 neurons, K/U/V rows resident, loop
+// over all tokens in blocks of 32), for a head width at which the arithmetic, not the
+// products, is the longer pipe: per block a wave runs 24 MFMAs (384 cycles) against about
+// 650 cycles of VALU work on its 8 elements per lane.  What helps is more waves to fill the
+// VALU and as few other instructions as possible: workgroups of 4 waves with about 160
+// registers each, three per CU; token tiles ([32][64] bf16 of q and of dY, chunks permuted as
+// in bwd_wgt_dh_kernel) and r go global -> LDS directly into four stages, requested three
+// blocks ahead (no staging registers, no LDS stores); one barrier per block.
+// ---------------------------------------------------------------------------
+constexpr int kW6Dh = 64;
+constexpr int kW6Waves = 4;
+constexpr int kW6Threads = 64 * kW6Waves;
+constexpr int kW6Tile = 32 * kW6Dh * 2;             // 4 KB
+constexpr int kW6Stages = 4;
+constexpr int kW6YRing = kW6Stages * kW6Tile;       // start of the dY ring
+constexpr int kW6RRing = 2 * kW6YRing;              // start of the r ring
+constexpr int kW6RSlot = kW6Waves * 64 * 4;
+constexpr int kW6LdsBytes = kW6RRing + kW6Stages * kW6RSlot;   // 36 KB
+constexpr int kW6DmaInstrs = 3;                     // direct loads per wave and block
+constexpr int kW6Window = 4;                        // operands kept in flight ahead of the one being consumed
+// operand stream of a block: items 0..7 rows of the q / dY tiles (1 LDS read each), items
+// 8..15 transposed windows, dY^T and q^T alternating (2 reads each)
+constexpr int w6_issued_before(int c) { return c + kW6Window > 15 ? 15 : c + kW6Window; }
+constexpr int w6_pending(int c) {
+  int n = 0;
+  for (int p = c + 1; p <= w6_issued_before(c); ++p) n += (p < 8) ? 1 : 2;
+  return n;
+}
+
+__global__ __launch_bounds__(kW6Threads, 3) void bwd_wgt64_kernel(BwdArgs a) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int cn = lane & 15, gq = lane >> 4;
+  const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+  const int nblk = a.E * a.de / 16;              // 16-neuron blocks per head
+  const int wg_per_head = (nblk + kW6Waves - 1) / kW6Waves;
+  const int64_t item_s = xcd_work_item(blockIdx.x, a.n_items);
+  if (item_s >= a.n_items) return;
+  const int seg = (int)(item_s % a.wsplit);          // this workgroup's share of the tokens
+  const int64_t item = item_s / a.wsplit;
+  const int h = (int)(item / wg_per_head);
+  const int blk = (int)(item % wg_per_head) * kW6Waves + wave_u;
+  const bool active = blk < nblk;
+  const int blk_c = active ? blk : nblk - 1;     // idle waves shadow a valid block, store nothing
+  const int64_t N = a.N;
+  const size_t row0 = ((size_t)h * nblk + blk_c) * 16;
+  const int e_wave = blk_c / (a.de / 16);
+
+  // resident weight operands: lane (neuron cn, group gq) holds columns 32ks + 8gq ..
+  bf16x8 Kf[2], Uf[2], Vf[2];
+  {
+    const size_t off = (row0 + cn) * kW6Dh + 8 * gq;
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+      Kf[ks] = *reinterpret_cast<const bf16x8*>(a.Wg + off + 32 * ks);
+      Uf[ks] = *reinterpret_cast<const bf16x8*>(a.Wu + off + 32 * ks);
+      Vf[ks] = *reinterpret_cast<const bf16x8*>(a.Wd + off + 32 * ks);
+    }
+  }
+  f32x4 dK[4], dU[4], dV[4];
+#pragma unroll
+  for (int jb = 0; jb < 4; ++jb) { dK[jb] = f32x4{0, 0, 0, 0}; dU[jb] = dK[jb]; dV[jb] = dK[jb]; }
+
+  // ---- staging -----------------------------------------------------------------
+  // Wave w moves rows 8w .. 8w+7 of the q and of the dY tile (one 1 KB image each: LDS position
+  // p of a row holds chunk p ^ (row & 6)) and the 32 r values of its own sub-network.  Addresses
+  // are a wave-uniform base that advances block by block plus a 32-bit per-lane byte offset.
+  // Rows past N are read from row N-1 (finite data) and get r = 0, so they add nothing.
+  const int64_t nb = (N + 31) / 32;
+  const int64_t b0 = seg * a.blocks_per_seg;              // this workgroup's blocks: b0 .. b1-1
+  const int64_t b1 = b0 + a.blocks_per_seg < nb ? b0 + a.blocks_per_seg : nb;
+  auto lane_col = [&](int l) {   // element column inside the head of the chunk lane l moves
+    const int row = 8 * wave_u + (l >> 3);
+    return ((l & 7) ^ (row & 6)) << 3;
+  };
+  const unsigned vx = (unsigned)(((8 * wave_u + (lane >> 3)) * a.ldx + lane_col(lane)) * 2);
+  const unsigned vy = (unsigned)(((8 * wave_u + (lane >> 3)) * a.ldy + lane_col(lane)) * 2);
+  const unsigned vr = 4 * (lane & 31);
+  const unsigned char* xbase = reinterpret_cast<const unsigned char*>(a.X + b0 * 32 * a.ldx + h * kW6Dh);
+  const unsigned char* ybase = reinterpret_cast<const unsigned char*>(a.dY + b0 * 32 * a.ldy + h * kW6Dh);
+  const float* Rw = a.Rws + ((size_t)h * a.E + e_wave) * N;
+  const unsigned char* rbase = reinterpret_cast<const unsigned char*>(Rw + b0 * 32);
+  // blocks are requested in order, each once: the bases just advance
+  auto dma = [&](int64_t blkidx, int stage) {
+    unsigned x0 = vx, y0 = vy, r0 = vr;
+    if (blkidx == nb - 1) {   // the last block may be ragged
+      int l = lane;
+      asm volatile("" : "+v"(l));   // recomputed here, not kept in registers through the loop
+      const int64_t last = N - 1 - blkidx * 32;   // >= 0
+      const int64_t ra = 8 * wave_u + (l >> 3), rr = l & 31;
+      const int64_t ca = ra < last ? ra : last;
+      x0 = (unsigned)((ca * a.ldx + lane_col(l)) * 2);
+      y0 = (unsigned)((ca * a.ldy + lane_col(l)) * 2);
+      r0 = 4 * (unsigned)(rr < last ? rr : last);
+    }
+    unsigned char* dst = smem + stage * kW6Tile + wave_u * 1024;
+    global_to_lds_16B(xbase + x0, dst);
+    global_to_lds_16B(ybase + y0, dst + kW6YRing);
+    __builtin_amdgcn_global_load_lds(
+        (__attribute__((address_space(1))) const void*)(rbase + r0),
+        (__attribute__((address_space(3))) void*)(smem + kW6RRing + stage * kW6RSlot + wave_u * 256),
+        4, 0, 0);
+    xbase += 64 * a.ldx;
+    ybase += 64 * a.ldy;
+    rbase += 128;
+  };
+  dma(b0, 0);
+  if (b0 + 1 < b1) dma(b0 + 1, 1);
+  if (b0 + 2 < b1) dma(b0 + 2, 2);
+
+  // LDS read addresses (stage, tensor and token half are immediate offsets): rows of the
+  // q / dY tiles: token row cn (+16), columns 32ks + 8gq ..; transposed windows: lane (cn, gq)
+  // points at token row 4gq + cn/4 (+16), columns 16jb + 4(cn%4) ..
+  const unsigned lbase = lds_addr_of(smem);
+  unsigned arow[2], atr[4];
+#pragma unroll
+  for (int ks = 0; ks < 2; ++ks) arow[ks] = lbase + wdh_off<kW6Dh>(cn, 4 * ks + gq);
+#pragma unroll
+  for (int jb = 0; jb < 4; ++jb) atr[jb] = lbase + wdh_off8<kW6Dh>(4 * gq + (cn >> 2), 16 * jb + 4 * (cn & 3));
+  const unsigned raddr = lbase + kW6RRing + wave * 256 + 16 * gq;   // r of MFMA rows 4gq.. (+64: next 16 tokens)
+
+  // block b, in stage S
+  auto step = [&](int64_t b, auto S_) {
+    constexpr int S = decltype(S_)::value, SO = S * kW6Tile;
+    // Own requests in flight: blocks b, b+1, b+2 as far as they exist; block b must have landed.
+    // After the barrier every wave's part of it is visible and every wave is done with block
+    // b-1, whose stage the next request overwrites.
+    if (b + 2 < b1) __builtin_amdgcn_s_waitcnt(0x0F70 | (2 * kW6DmaInstrs));
+    else if (b + 1 < b1) __builtin_amdgcn_s_waitcnt(0x0F70 | kW6DmaInstrs);
+    else __builtin_amdgcn_s_waitcnt(0x0F70);
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    if (b + 3 < b1) dma(b + 3, (S + 3) % kW6Stages);
+
+    f32x4 rv[2];
+    bf16x8 opa[8];
+    s16x4 xlo[8], xhi[8];
+    auto issue = [&](auto P_) {
+      constexpr int P = decltype(P_)::value;
+      if constexpr (P < 8) {
+        constexpr int tb = P >> 2, ks = (P >> 1) & 1, which = P & 1;   // 0: q, 1: dY
+        opa[P] = lds_read_b128_untracked<SO + which * kW6YRing + tb * 2048>(arow[ks]);   // 16 rows further: same permutation
+      } else {
+        constexpr int J = P - 8, jb = J >> 1, TO = SO + ((J & 1) ? 0 : kW6YRing);  // even: dY^T, odd: q^T
+        xlo[J] = lds_read_tr16_untracked<TO>(atr[jb]);
+        xhi[J] = lds_read_tr16_untracked<TO + 2048>(atr[jb]);
+      }
+    };
+    auto advance = [&](auto C_) {
+      constexpr int C = decltype(C_)::value;
+      constexpr int lo = (C == 0) ? 0 : w6_issued_before(C - 1) + 1;
+      static_for<lo, w6_issued_before(C) + 1>(issue);
+    };
+    rv[0] = __builtin_bit_cast(f32x4, lds_read_b128_untracked<S * kW6RSlot>(raddr));
+    rv[1] = __builtin_bit_cast(f32x4, lds_read_b128_untracked<S * kW6RSlot + 64>(raddr));
+    f32x4 M[2], Nn[2], Ad[2];
+#pragma unroll
+    for (int tb = 0; tb < 2; ++tb) { M[tb] = f32x4{0, 0, 0, 0}; Nn[tb] = M[tb]; Ad[tb] = M[tb]; }
+    static_for<0, 8>([&](auto C_) {
+      constexpr int C = decltype(C_)::value, tb = C >> 2, ks = (C >> 1) & 1;
+      advance(C_);
+      lds_wait<w6_pending(C)>(opa[C]);
+      if constexpr ((C & 1) == 0) {
+        M[tb] = mfma16(opa[C], Kf[ks], M[tb]);
+        Nn[tb] = mfma16(opa[C], Uf[ks], Nn[tb]);
+      } else {
+        Ad[tb] = mfma16(opa[C], Vf[ks], Ad[tb]);
+      }
+    });
+    // (the r reads are older than every read of the stream)
+    asm volatile("" : "+v"(rv[0]), "+v"(rv[1]));
+    if (b == nb - 1) {   // rows past N were read from row N-1: give them r = 0
+      asm volatile("" ::: "memory");   // (a real branch: the last block only)
+#pragma unroll
+      for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+        for (int v = 0; v < 4; ++v)
+          if (b * 32 + 16 * tb + 4 * gq + v >= N) rv[tb][v] = 0.f;
+    }
+    // element (tb, v): token 16tb + 4gq + v, neuron cn; it becomes contraction slot
+    // 4tb + v of the gradient products
+    float ag[8], dm[8], dn[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int tb = i >> 2, v = i & 3;
+      const float m = M[tb][v], n = Nn[tb][v], da = Ad[tb][v];
+      const float t = __builtin_amdgcn_exp2f(-MHFFN_LOG2E * m);
+      const float sg = __builtin_amdgcn_rcpf(1.0f + t);
+      const float sw = rv[tb][v] * sg;
+      const float x = (1.0f + m) - m * sg;   // silu'(m) = sg (1 + m - silu(m))
+      const float pw = m * sw;
+      ag[i] = pw * n;
+      dn[i] = pw * da;
+      dm[i] = ((n * sw) * x) * da;
+    }
+    u32x4 pa, pm, pn;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      pa[i] = pack_bf16(ag[2 * i], ag[2 * i + 1]);
+      pm[i] = pack_bf16(dm[2 * i], dm[2 * i + 1]);
+      pn[i] = pack_bf16(dn[2 * i], dn[2 * i + 1]);
+    }
+    const bf16x8 agf = __builtin_bit_cast(bf16x8, pa);
+    const bf16x8 dmf = __builtin_bit_cast(bf16x8, pm), dnf = __builtin_bit_cast(bf16x8, pn);
+
+    // dV^T[j][c] += dY^T a ; dK^T[j][c] += q^T dM ; dU^T[j][c] += q^T dN
+    static_for<8, 16>([&](auto C_) {
+      constexpr int C = decltype(C_)::value, J = C - 8, jb = J >> 1;
+      advance(C_);
+      lds_wait<w6_pending(C)>(xlo[J], xhi[J]);
+      const bf16x8 xt = join_tr(xlo[J], xhi[J]);
+      if constexpr ((J & 1) == 0) {
+        dV[jb] = mfma16(xt, agf, dV[jb]);
+      } else {
+        dK[jb] = mfma16(xt, dmf, dK[jb]);
+        dU[jb] = mfma16(xt, dnf, dU[jb]);
+      }
+    });
+  };
+  using C0 = std::integral_constant<int, 0>;
+  using C1 = std::integral_constant<int, 1>;
+  using C2 = std::integral_constant<int, 2>;
+  using C3 = std::integral_constant<int, 3>;
+  for (int64_t b = b0; b < b1; b += 4) {
+    step(b, C0{});
+    if (b + 1 < b1) step(b + 1, C1{});
+    if (b + 2 < b1) step(b + 2, C2{});
+    if (b + 3 < b1) step(b + 3, C3{});
+  }
+
+  if (active && a.wsplit > 1) {
+    // fp32 partial gradients of this token segment: [seg][K | U | V][row][d_h]
+    const size_t rows = (size_t)a.H * nblk * 16;
+    float* dst = a.WPws + (((size_t)seg * 3) * rows + row0 + cn) * kW6Dh + 4 * gq;
+#pragma unroll
+    for (int jb = 0; jb < 4; ++jb) {
+      *reinterpret_cast<f32x4*>(dst + 16 * jb) = dK[jb];
+      *reinterpret_cast<f32x4*>(dst + rows * kW6Dh + 16 * jb) = dU[jb];
+      *reinterpret_cast<f32x4*>(dst + 2 * rows * kW6Dh + 16 * jb) = dV[jb];
+    }
+  } else if (active) {
+    // accumulators are [j][c]: lane = neuron column cn, register v = row 16jb + 4gq + v
+    const size_t off = (row0 + cn) * kW6Dh + 4 * gq;
+#pragma unroll
+    for (int jb = 0; jb < 4; ++jb) {
       const size_t o = off + 16 * jb;
       if (a.dWg) {
         u32x2 pk = {pack_bf16(dK[jb][0], dK[jb][1]), pack_bf16(dK[jb][2], dK[jb][3])};
@@ -1891,6 +2174,25 @@ int launch_wgt_dh(const Problem& p, BwdArgs a, hipStream_t stream) {
   return (int)hipGetLastError();
 }
 
+int launch_wgt64(const Problem& p, BwdArgs a, hipStream_t stream) {
+  static_assert(kW6Waves == wgt_waves(kW6Dh) && 3 * 256 == wgt_slots(kW6Dh), "plan_wgt_split assumes this launch shape");
+  const int nblk = p.E * p.de / 16;
+  const int wg_per_head = (nblk + kW6Waves - 1) / kW6Waves;
+  const WgtSplit wsp = plan_wgt_split(p);
+  a.wsplit = wsp.segs;
+  a.blocks_per_seg = wsp.blocks_per_seg;
+  a.n_items = (int64_t)wg_per_head * p.H * wsp.segs;
+  if (hipError_t e = LdsLimit<&bwd_wgt64_kernel, kFullLds>::ensure(); e != hipSuccess) return (int)e;
+  hipLaunchKernelGGL(bwd_wgt64_kernel, dim3((unsigned)xcd_grid_size(a.n_items)), dim3(kW6Threads),
+                     kW6LdsBytes, stream, a);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess || wsp.segs == 1) return (int)e;
+  const size_t count = (size_t)p.H * p.E * p.de * kW6Dh;
+  hipLaunchKernelGGL(bwd_wgt_reduce_kernel, dim3((unsigned)((count / 4 + 255) / 256)), dim3(256), 0,
+                     stream, a, count);
+  return (int)hipGetLastError();
+}
+
 template <int DH>
 int launch_route(const Problem& p, const BwdArgs& a, hipStream_t stream) {
   const dim3 rgrid(p.H, kRouteSplit);
@@ -1999,7 +2301,8 @@ int launch_bwd(const Problem& p, int dtype, const void* X, const void* Wg, const
   if (rc) return rc;
   if (mark(1) != hipSuccess) return (int)hipErrorInvalidHandle;
   if (dWg || dWu || dWd) {
-    if (p.dh == 64) rc = launch_wgt_dh<64, 4>(p, a, stream);
+    if (p.dh == 64 && p.ldx < ((int64_t)1 << 24) && p.ldy < ((int64_t)1 << 24)) rc = launch_wgt64(p, a, stream);
+    else if (p.dh == 64) rc = launch_wgt_dh<64, 4>(p, a, stream);
     else if (p.dh == 256 && !wgt256_takes(p)) rc = launch_wgt_dh<256, 4>(p, a, stream);
     else rc = launch_wgt16(p, a, stream);   // d_h = 128 and 256
     if (rc) return rc;
