@@ -59,6 +59,32 @@ def test_dh256_weight_major_rounds_and_token_shares(N, H, E, de):
 
 
 @pytest.mark.parametrize("dh", [64, 256])
+def test_strided_rows_and_partial_requests(dh):
+    """X and dY as column slices of wider buffers with different row strides, a ragged token
+    count, and a request for one weight gradient only (the weight-major kernels of these head
+    widths stage their tiles from row-strided sources and skip the outputs not asked for)."""
+    import torch
+    w = small_workload("hw_strided", 333, 3, 5, 96, "bf16", dh=dh, backward=True)
+    d = inputs.make_inputs(w, seed=21, with_dy=True)
+    g = device_inputs(d, w.dtype)
+    dm = w.d_model
+    Xp = torch.zeros(w.n_tokens, dm + 64, dtype=g["X"].dtype, device="cuda")
+    Xp[:, :dm] = g["X"]
+    dYp = torch.zeros(w.n_tokens, dm + 192, dtype=g["X"].dtype, device="cuda")
+    dYp[:, :dm] = g["dY"]
+    ref = orc.backward(d["X"], d["W_gate"], d["W_up"], d["W_down"], d["W_r"], d["dY"], w.eps)
+    out = mhffn.backward(Xp[:, :dm], g["W_gate"], g["W_up"], g["W_down"], g["W_r"], dYp[:, :dm], w.eps)
+    torch.cuda.synchronize()
+    full = {k: to_host(v) for k, v in out.items()}
+    check_all(full, ref, TOL["bf16"])
+    only = mhffn.backward(Xp[:, :dm], g["W_gate"], g["W_up"], g["W_down"], g["W_r"], dYp[:, :dm], w.eps,
+                          want=("dW_up",))
+    torch.cuda.synchronize()
+    assert set(only) == {"dW_up"}
+    assert np.array_equal(to_host(only["dW_up"]), full["dW_up"])
+
+
+@pytest.mark.parametrize("dh", [64, 256])
 def test_weights_mode(dh):
     w = small_workload("hw_weights", 333, 2, 6, 64, "bf16", dh=dh, backward=True)
     d, Y = run_forward(w, seed=5, route_weights=True)
