@@ -85,6 +85,28 @@ def test_strided_rows_and_partial_requests(dh):
 
 
 @pytest.mark.parametrize("dh", [64, 256])
+def test_very_large_row_stride_takes_the_generic_weight_major_kernel(dh):
+    """Row strides of 2^24 elements and more do not fit the 32-bit row offsets of the kernels
+    above; the backward then runs the register-staged kernel (1.3 GB buffers, 40 tokens)."""
+    import torch
+    w = small_workload("hw_wide", 40, 2, 3, 64, "bf16", dh=dh, backward=True)
+    d = inputs.make_inputs(w, seed=22, with_dy=True)
+    g = device_inputs(d, w.dtype)
+    dm, ld = w.d_model, 1 << 24
+    Xp = torch.zeros(w.n_tokens, ld, dtype=g["X"].dtype, device="cuda")
+    Xp[:, :dm] = g["X"]
+    dYp = torch.zeros(w.n_tokens, ld, dtype=g["X"].dtype, device="cuda")
+    dYp[:, :dm] = g["dY"]
+    ref = orc.backward(d["X"], d["W_gate"], d["W_up"], d["W_down"], d["W_r"], d["dY"], w.eps)
+    out = mhffn.backward(Xp[:, :dm], g["W_gate"], g["W_up"], g["W_down"], g["W_r"], dYp[:, :dm], w.eps,
+                         want=("dW_gate", "dW_up", "dW_down", "d_route"))
+    torch.cuda.synchronize()
+    check_all({k: to_host(v) for k, v in out.items()}, {k: ref[k] for k in out}, TOL["bf16"])
+    del Xp, dYp
+    torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("dh", [64, 256])
 def test_weights_mode(dh):
     w = small_workload("hw_weights", 333, 2, 6, 64, "bf16", dh=dh, backward=True)
     d, Y = run_forward(w, seed=5, route_weights=True)
