@@ -126,7 +126,7 @@ constexpr int tok_stages(bool dma) { return dma ? 3 : 2; }
 // the early ones in its middle), and every wave waits for its own requests at the end of the
 // half-step in which it made them, two half-steps before the first use.
 template <int DH, int TB, int NW, bool DMA = false, bool PHASED = false>
-__global__ __launch_bounds__(64 * NW) void bwd_tok_kernel(BwdArgs a) {
+__global__ __launch_bounds__(64 * NW, DH == 64 ? 2 : 1) void bwd_tok_kernel(BwdArgs a) {
   static_assert(!DMA || (DH == 128 && TB == 1 && NW == 8), "direct staging: 32 rows x 16 chunks = 512 lanes");
   static_assert(DMA || !PHASED, "the half-step schedule relies on direct staging");
   constexpr int kTokStages = tok_stages(DMA);

@@ -60,7 +60,7 @@ struct FwdArgs {
 };
 
 template <int DH, int TB, int NW>
-__global__ __launch_bounds__(64 * NW) void fwd_bf16_kernel(FwdArgs a) {
+__global__ __launch_bounds__(64 * NW, NW == 2 ? 2 : 1) void fwd_bf16_kernel(FwdArgs a) {
   constexpr int BM = 32 * TB * NW;
   constexpr int THREADS = 64 * NW;
   constexpr int KS = DH / 16;                  // contraction steps over the head width
