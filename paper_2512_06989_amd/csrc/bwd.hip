@@ -325,6 +325,155 @@ __global__ __launch_bounds__(64 * NW, DH == 64 ? 2 : 1) void bwd_tok_kernel(BwdA
     if (requested) __builtin_amdgcn_s_waitcnt(0x0073);  // vmcnt(3) lgkmcnt(0)
     else __builtin_amdgcn_s_waitcnt(0x0070);            // vmcnt(0) lgkmcnt(0)
   };
+  if constexpr (PHASED) {
+    // Half A of step t: the dX products of tile t-1 (operands packed in half B of step t-1),
+    // then the gate/up/dA products of tile t: 40 MFMAs and their LDS reads, no VALU work.
+    // Half B: the activation arithmetic, no MFMA.  A SIMD's two waves are always in opposite
+    // halves.  Tile t is read in four consecutive half-steps (A of step t and of step t+1, for
+    // the early and the late waves); its stage is requested again at the start of the fifth,
+    // for tile t+3, by the early waves at the top of their half A and by the late ones at the
+    // top of their half B, and each wave waits for its request at the end of its next half,
+    // one barrier before the first read.
+    f32x16 accM, accN, accA;
+    bf16x8 dmf[2], dnf[2];
+    // Half A as one stream of LDS reads and MFMAs: items 0 .. NT-1 are the K^T / U^T windows of
+    // the previous tile (two transposing reads each, one dX product), items NT .. NT+NOP-1 the
+    // K / U / V row operands of this tile (one read, one product each).  Reads run kWin items
+    // ahead of their use with counted waits; the first kWin items (all windows of the previous
+    // tile, which has been in place for a step) are issued before the barrier that opens the
+    // half, so their latency is hidden behind it.
+    constexpr int NT = 2 * JB * 2, NOP = 3 * KS, kWin = 4;
+    static_assert(kWin <= NT, "the reads issued before the barrier touch the previous tile only");
+    s16x4 lo[NT], hi[NT];
+    bf16x8 op[NOP];
+    const int li = lane & 15;
+    const int trow = 4 * g + (li >> 2), tcol = 16 * ((lane >> 4) & 1) + 4 * (li & 3);
+    auto issue_item = [&](auto C_, unsigned sto_prev, unsigned sto_cur) {
+      constexpr int c = decltype(C_)::value;
+      if constexpr (c < NT) {
+        constexpr int which = c & 1, jb = (c >> 1) % JB, t2 = c / (2 * JB);
+        constexpr int OFF = which * kTileBytes + t2 * 16 * 2 * DH;   // 16 rows further: same swizzle
+        lo[c] = lds_read_tr16_untracked<OFF>(sto_prev + btile_off8<DH>(trow, 32 * jb + tcol));
+        hi[c] = lds_read_tr16_untracked<OFF>(sto_prev + btile_off8<DH>(trow + 8, 32 * jb + tcol));
+      } else {
+        constexpr int k = c - NT, ks = k / 3, which = k % 3;
+        op[k] = lds_read_b128_untracked<which * kTileBytes>(sto_cur + btile_off<DH>(r, 2 * ks + g));
+      }
+    };
+    // LDS operations issued after those of item c when item c is consumed
+    auto pending_after = [](int c, int n_all) {
+      int n = 0;
+      for (int i = c + 1; i <= c + kWin && i < n_all; ++i) n += (i < NT) ? 2 : 1;
+      return n;
+    };
+    auto prefetch_windows = [&](unsigned sto_prev) {
+      static_for<0, kWin>([&](auto C_) { issue_item(C_, sto_prev, 0u); });
+    };
+    // the stream from item FIRST on (the kWin items from FIRST on have been issued)
+    auto run_stream = [&](auto FIRST_, auto NALL_, unsigned sto_prev, unsigned sto_cur) {
+      constexpr int FIRST = decltype(FIRST_)::value, NALL = decltype(NALL_)::value;
+      static_for<FIRST, NALL>([&](auto C_) {
+        constexpr int c = decltype(C_)::value;
+        if constexpr (c + kWin < NALL) issue_item(std::integral_constant<int, c + kWin>{}, sto_prev, sto_cur);
+        constexpr int pend = pending_after(c, NALL);
+        if constexpr (c < NT) {
+          constexpr int which = c & 1, jb = (c >> 1) % JB, t2 = c / (2 * JB);
+          lds_wait<pend>(lo[c], hi[c]);
+          const bf16x8 xt = join_tr(lo[c], hi[c]);
+          dXa[0][jb] = mfma32(xt, which ? dnf[t2] : dmf[t2], dXa[0][jb]);
+        } else {
+          constexpr int k = c - NT, ks = k / 3, which = k % 3;
+          lds_wait<pend>(op[k]);
+          if constexpr (which == 0) accM = mfma32(op[k], q[0][ks], ks == 0 ? f32x16{0} : accM);
+          if constexpr (which == 1) accN = mfma32(op[k], q[0][ks], ks == 0 ? f32x16{0} : accN);
+          if constexpr (which == 2) accA = mfma32(op[k], dy[0][ks], ks == 0 ? f32x16{0} : accA);
+        }
+      });
+    };
+    using IC0 = std::integral_constant<int, 0>;
+    using ICT = std::integral_constant<int, NT>;
+    using ICA = std::integral_constant<int, NT + NOP>;
+    auto arith = [&]() {
+#pragma unroll
+      for (int t2 = 0; t2 < 2; ++t2) {
+        u32x4 pm, pn;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          float dmv[2], dnv[2];
+#pragma unroll
+          for (int u = 0; u < 2; ++u) {
+            const int v = 8 * t2 + 2 * i + u;
+            const float m = accM[v], n = accN[v], da = accA[v];
+            const float sg = sigmoid_fast(m);
+            const float silu = m * sg;
+            drp[0] = fmaf(da * silu, n, drp[0]);
+            const float rda = rw[0] * da;
+            dnv[u] = rda * silu;
+            dmv[u] = rda * n * fmaf(silu, 1.0f - sg, sg);  // SiLU'(m) = sg + silu (1 - sg)
+          }
+          pm[i] = pack_bf16(dmv[0], dmv[1]);
+          pn[i] = pack_bf16(dnv[0], dnv[1]);
+        }
+        dmf[t2] = __builtin_bit_cast(bf16x8, pm);
+        dnf[t2] = __builtin_bit_cast(bf16x8, pn);
+      }
+    };
+    // end of a half: this wave's LDS traffic (and its tile request, if one is due) has landed;
+    // with `windows_of`, the first reads of the next half A go out ahead of the barrier
+    auto close_half = [&](bool own_request_due, bool prefetch, unsigned windows_of) {
+      asm volatile("" ::: "memory");
+      if (own_request_due) __builtin_amdgcn_s_waitcnt(0x0070);   // vmcnt(0) lgkmcnt(0)
+      else __builtin_amdgcn_s_waitcnt(0xC07F);                   // lgkmcnt(0)
+      if (prefetch) prefetch_windows(windows_of);
+      bare_barrier();
+    };
+    // A request is made by the early waves alone, at the top of their half A (the shorter of
+    // the two halves): wave w moves its own rows and those of wave w + NW/2.
+    auto dma_pair = [&](int t, int stage) {
+      const size_t off = (size_t)t * (32 * DH) + dma_goff;
+      unsigned char* dst = stage_base + stage * kTokStageBytes + wave_u * 1024;
+      constexpr int kHalfTile = (NW / 2) * 4 * DH;   // elements: rows 4 (w + NW/2) .. +3
+#pragma unroll
+      for (int hf = 0; hf < 2; ++hf) {
+        global_to_lds_16B(Kh + off + hf * kHalfTile, dst + hf * (kTileBytes / 2));
+        global_to_lds_16B(Uh + off + hf * kHalfTile, dst + hf * (kTileBytes / 2) + kTileBytes);
+        global_to_lds_16B(Vh + off + hf * kHalfTile, dst + hf * (kTileBytes / 2) + 2 * kTileBytes);
+      }
+    };
+    const unsigned sto0 = lds_addr_of(stage_base);
+    int prev = 2;   // (t - 1) % 3
+    if (late) bare_barrier();
+    for (int t = 0; t < T; ++t) {
+      const int e = t / tiles_per_sub;
+      if (t % tiles_per_sub == 0) rw[0] = DRs[e * BM + wtok + r];
+      const unsigned sto_cur = sto0 + stage * kTokStageBytes, sto_prev = sto0 + prev * kTokStageBytes;
+      // ---- half A
+      const bool request = !late && t >= 1 && t + 1 < T;
+      if (request) dma_pair(t + 1, stage == 2 ? 0 : stage + 1);
+      if (t == 0) {
+        static_for<NT, NT + kWin>([&](auto C_) { issue_item(C_, 0u, sto_cur); });
+        run_stream(ICT{}, ICA{}, 0u, sto_cur);
+      } else {
+        run_stream(IC0{}, ICA{}, sto_prev, sto_cur);
+      }
+      close_half(false, false, 0u);
+      // ---- half B
+      arith();
+      // (left alone, the compiler sinks half of the arithmetic below the wait that closes the half)
+      asm volatile("" : "+v"(dmf[0]), "+v"(dmf[1]), "+v"(dnf[0]), "+v"(dnf[1]), "+v"(drp[0]));
+      if ((t + 1) % tiles_per_sub == 0) {
+        const float dr = drp[0] + __shfl_xor(drp[0], 32);
+        if (g == 0) DRs[e * BM + wtok + r] = dr;
+        drp[0] = 0.f;
+      }
+      close_half(!late, true, sto_cur);
+      prev = stage;
+      stage = (stage == 2) ? 0 : stage + 1;
+    }
+    run_stream(IC0{}, ICT{}, sto0 + prev * kTokStageBytes, 0u);
+    close_half(false, false, 0u);
+    if (!late) bare_barrier();
+  } else {
   if (late) bare_barrier();
   for (int t = 0; t < T; ++t) {
     const bool more = (t + 1 < T);
@@ -458,6 +607,7 @@ __global__ __launch_bounds__(64 * NW, DH == 64 ? 2 : 1) void bwd_tok_kernel(BwdA
     }
   }
   if (PHASED && !late) bare_barrier();
+  }
 
   // ---- derivative through the gating weights ------------------------------------
   if (a.route_mode == 0) {

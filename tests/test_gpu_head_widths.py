@@ -15,6 +15,9 @@ pytestmark = pytest.mark.gpu
 # forward (few tokens), more than 32 sub-networks, the paper's sub-network widths
 SHAPES = [(1, 1, 64, 1, 32), (63, 2, 64, 3, 96), (300, 2, 64, 5, 64), (1000, 3, 64, 14, 192),
           (257, 1, 64, 40, 32), (130, 2, 64, 70, 32),
+          # 96 sub-networks, the most the bf16 kernels take: W_r^T then fills a whole weight
+          # stage of the token-major backward during its gating prologue
+          (140, 1, 64, 96, 32),
           (1, 1, 256, 1, 32), (63, 2, 256, 3, 96), (300, 2, 256, 3, 64), (700, 1, 256, 4, 704),
           (257, 1, 256, 40, 32)]
 
