@@ -443,14 +443,17 @@ __global__ __launch_bounds__(64 * NW, DH == 64 ? 2 : 1) void bwd_tok_kernel(BwdA
     const unsigned sto0 = lds_addr_of(stage_base);
     int prev = 2;   // (t - 1) % 3
     if (late) bare_barrier();
-    for (int t = 0; t < T; ++t) {
+    // (the first step, which has no previous tile, is a copy of its own: as a branch inside the
+    // loop it can cost the loop sixty spilled registers)
+    auto step = [&](int t, auto FIRST_) {
+      constexpr bool kFirst = decltype(FIRST_)::value;
       const int e = t / tiles_per_sub;
       if (t % tiles_per_sub == 0) rw[0] = DRs[e * BM + wtok + r];
       const unsigned sto_cur = sto0 + stage * kTokStageBytes, sto_prev = sto0 + prev * kTokStageBytes;
       // ---- half A
       const bool request = !late && t >= 1 && t + 1 < T;
       if (request) dma_pair(t + 1, stage == 2 ? 0 : stage + 1);
-      if (t == 0) {
+      if constexpr (kFirst) {
         static_for<NT, NT + kWin>([&](auto C_) { issue_item(C_, 0u, sto_cur); });
         run_stream(ICT{}, ICA{}, 0u, sto_cur);
       } else {
@@ -458,9 +461,11 @@ __global__ __launch_bounds__(64 * NW, DH == 64 ? 2 : 1) void bwd_tok_kernel(BwdA
       }
       close_half(false, false, 0u);
       // ---- half B
+      __builtin_amdgcn_s_setprio(1);
       arith();
       // (left alone, the compiler sinks half of the arithmetic below the wait that closes the half)
       asm volatile("" : "+v"(dmf[0]), "+v"(dmf[1]), "+v"(dnf[0]), "+v"(dnf[1]), "+v"(drp[0]));
+      __builtin_amdgcn_s_setprio(0);
       if ((t + 1) % tiles_per_sub == 0) {
         const float dr = drp[0] + __shfl_xor(drp[0], 32);
         if (g == 0) DRs[e * BM + wtok + r] = dr;
@@ -469,7 +474,9 @@ __global__ __launch_bounds__(64 * NW, DH == 64 ? 2 : 1) void bwd_tok_kernel(BwdA
       close_half(!late, true, sto_cur);
       prev = stage;
       stage = (stage == 2) ? 0 : stage + 1;
-    }
+    };
+    step(0, std::true_type{});
+    for (int t = 1; t < T; ++t) step(t, std::false_type{});
     run_stream(IC0{}, ICT{}, sto0 + prev * kTokStageBytes, 0u);
     close_half(false, false, 0u);
     if (!late) bare_barrier();
