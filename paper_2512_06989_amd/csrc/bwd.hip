@@ -125,10 +125,12 @@ constexpr int tok_stages(bool dma) { return dma ? 3 : 2; }
 // requested again at the start of the fourth (the late waves are then at the top of a step,
 // the early ones in its middle), and every wave waits for its own requests at the end of the
 // half-step in which it made them, two half-steps before the first use.
-template <int DH, int TB, int NW, bool DMA = false, bool PHASED = false>
+template <int DH, int TB, int NW, bool DMA = false, bool PHASED = false, bool PIPE = false>
 __global__ __launch_bounds__(64 * NW, DH == 64 ? 2 : 1) void bwd_tok_kernel(BwdArgs a) {
-  static_assert(!DMA || (DH == 128 && TB == 1 && NW == 8), "direct staging: 32 rows x 16 chunks = 512 lanes");
+  static_assert(!DMA || (TB == 1 && ((DH == 128 && NW == 8) || (DH == 256 && NW == 4))),
+                "direct staging: a wave-wide load moves 1 KB, a tile is 32 rows");
   static_assert(DMA || !PHASED, "the half-step schedule relies on direct staging");
+  static_assert(!PIPE || (DMA && !PHASED && DH == 256), "the one-wave pipeline is written for d_h = 256");
   constexpr int kTokStages = tok_stages(DMA);
   constexpr int BM = 32 * TB * NW;
   constexpr int THREADS = 64 * NW;
@@ -140,7 +142,7 @@ __global__ __launch_bounds__(64 * NW, DH == 64 ? 2 : 1) void bwd_tok_kernel(BwdA
   constexpr int CHUNKS = 32 * CPR;
   constexpr int CH = (CHUNKS + THREADS - 1) / THREADS;
   constexpr bool kAllLoad = (CHUNKS % THREADS == 0);   // else the upper threads carry none
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];   // (the one-wave pipeline XORs address bits)
   unsigned char* stage_base = smem;
   float* DRs = reinterpret_cast<float*>(smem + kTokStages * kTokStageBytes);  // [E][BM]: r_e, then dr_e
 
@@ -162,17 +164,31 @@ __global__ __launch_bounds__(64 * NW, DH == 64 ? 2 : 1) void bwd_tok_kernel(BwdA
   const uint16_t* Kh = a.Wg + head_off;
   const uint16_t* Uh = a.Wu + head_off;
   const uint16_t* Vh = a.Wd + head_off;
-  // direct staging: wave w moves rows 4w .. 4w+3 of a tile; lane l lands at chunk position
-  // l % 16 of row 4w + l / 16 and fetches the global chunk that the swizzle maps there
-  const int drow = 4 * wave + (lane >> 4);
-  const int dma_goff = drow * DH + (((lane & 15) ^ swz(drow)) << 3);   // elements
+  // direct staging: a wave-wide load fills 1 KB of a tile, kDmaRows rows; the NW waves fill
+  // kDmaRows NW rows per round, a tile in kDmaRounds rounds (d_h = 128: one round of 8 waves x 4
+  // rows; d_h = 256: four rounds of 4 waves x 2 rows).  Lane l lands at chunk position l % CPR
+  // of its row and fetches the global chunk that the swizzle maps there (the swizzle is an
+  // involution on the chunk index of a row).
+  constexpr int kDmaRows = DMA ? 1024 / (2 * DH) : 1;
+  constexpr int kDmaRounds = DMA ? 32 / (kDmaRows * NW) : 1;
   const int wave_u = __builtin_amdgcn_readfirstlane(wave);
-  auto dma = [&](int t, int stage) {
-    const size_t off = (size_t)t * (32 * DH) + dma_goff;
-    unsigned char* dst = stage_base + stage * kTokStageBytes + wave_u * 1024;
+  int dma_goff[kDmaRounds];   // elements
+#pragma unroll
+  for (int i = 0; i < kDmaRounds; ++i) {
+    const int drow = kDmaRows * (NW * i + wave) + lane / CPR;
+    const int dchunk = (btile_off<DH>(drow, lane % CPR) - drow * 2 * DH) >> 4;
+    dma_goff[i] = drow * DH + dchunk * 8;
+  }
+  auto dma_round = [&](int t, int stage, int i) {
+    const size_t off = (size_t)t * (32 * DH) + dma_goff[i];
+    unsigned char* dst = stage_base + stage * kTokStageBytes + (NW * i + wave_u) * 1024;
     global_to_lds_16B(Kh + off, dst);
     global_to_lds_16B(Uh + off, dst + kTileBytes);
     global_to_lds_16B(Vh + off, dst + 2 * kTileBytes);
+  };
+  auto dma = [&](int t, int stage) {
+#pragma unroll
+    for (int i = 0; i < kDmaRounds; ++i) dma_round(t, stage, i);
   };
   // the gating prologue stages W_r^T (up to 24 KB) in one stage: the last one, so that the
   // first two tiles can be on their way meanwhile (the epilogue, with all stages retired,
@@ -325,6 +341,168 @@ __global__ __launch_bounds__(64 * NW, DH == 64 ? 2 : 1) void bwd_tok_kernel(BwdA
     if (requested) __builtin_amdgcn_s_waitcnt(0x0073);  // vmcnt(3) lgkmcnt(0)
     else __builtin_amdgcn_s_waitcnt(0x0070);            // vmcnt(0) lgkmcnt(0)
   };
+  if constexpr (PIPE) {
+    // One wave per SIMD (d_h = 256: the accumulators and token operands of a wave take 256
+    // registers), so nothing hides one wave's arithmetic but its own products: the loop is a
+    // software pipeline inside the wave.  Step t = the 48 products M, N, dA of tile t+1, each
+    // followed by up to five VALU instructions of the activation arithmetic of tile t (a wave
+    // issues one VALU instruction per six cycles or so, a product runs for 32), then the 32 dX
+    // products of tile t, between which the 12 direct loads of tile t+2 are issued.  The
+    // arithmetic of an element pair is laid over six product slots such that no slot holds
+    // more than five instructions and a transcendental result is first used a slot later;
+    // 8 pairs x 6 slots = the 48 products.  Accumulators M, N, dA in two sets by parity of the
+    // tile.  Three stages: tile t (windows), t+1 (rows), t+2 (in flight); one barrier per step.
+    constexpr int NOP = 3 * KS, NT = 2 * JB * 2, kWinP = 4, kWinD = 4;
+    static_assert(NOP == 48, "eight element pairs x six slots");
+    f32x16 accM[2], accN[2], accA[2];
+    u32x4 pmv[2], pnv[2];   // packed dM, dN of the two 16-neuron halves of the tile
+    bf16x8 op[NOP];
+    s16x4 lo[NT], hi[NT];
+    float tt[16], sg[16], silu[16], rda[16], rn[16], om[16], sp[16], ds[16], dnv[16], dmv[16];
+    const int li = lane & 15;
+    const int trow = 4 * g + (li >> 2), tcol = 16 * ((lane >> 4) & 1) + 4 * (li & 3);
+    const unsigned sto0 = lds_addr_of(stage_base);
+    // direct loads with a wave-uniform base and a 32-bit lane offset (bytes).  Round i moves
+    // rows 8 i + 2 w, + 1: 4096 i bytes further, and the swizzle of a row 8 further differs in
+    // one bit of the chunk index.
+    const unsigned dma_b0 = 2u * (unsigned)dma_goff[0], dma_b1 = dma_b0 ^ 32u;
+    // load n of a request (0..11): round n / 3 of matrix n % 3 (K, U, V)
+    auto dma_one = [&](int t, int stage, auto N_) __attribute__((always_inline)) {
+      constexpr int i = decltype(N_)::value / 3, which = decltype(N_)::value % 3;
+      const size_t base = ((size_t)t * (32 * DH) + i * 8 * DH) * 2;
+      const unsigned lane_off = (i & 1) ? dma_b1 : dma_b0;
+      unsigned char* dst = stage_base + stage * kTokStageBytes + (NW * i + wave_u) * 1024 + which * kTileBytes;
+      const uint16_t* src = which == 0 ? Kh : which == 1 ? Uh : Vh;
+      global_to_lds_16B(reinterpret_cast<const unsigned char*>(src) + base + lane_off, dst);
+    };
+
+    // slot SL (0..5) of the arithmetic of pair PR (0..7; elements 2 PR and 2 PR + 1 of set R)
+    auto pair_slot = [&](auto PR_, auto SL_, auto R_) __attribute__((always_inline)) {
+      constexpr int pr = decltype(PR_)::value, sl = decltype(SL_)::value, R = decltype(R_)::value;
+      constexpr int v0 = 2 * pr, v1 = 2 * pr + 1, t2 = pr / 4, i = pr % 4;
+      if constexpr (sl == 0) {
+        tt[v0] = __builtin_amdgcn_exp2f(-MHFFN_LOG2E * accM[R][v0]);
+        tt[v1] = __builtin_amdgcn_exp2f(-MHFFN_LOG2E * accM[R][v1]);
+        rda[v0] = rw[0] * accA[R][v0];
+      } else if constexpr (sl == 1) {
+        sg[v0] = __builtin_amdgcn_rcpf(1.0f + tt[v0]);
+        sg[v1] = __builtin_amdgcn_rcpf(1.0f + tt[v1]);
+        rda[v1] = rw[0] * accA[R][v1];
+      } else if constexpr (sl == 2) {
+        silu[v0] = accM[R][v0] * sg[v0];
+        om[v0] = 1.0f - sg[v0];
+        silu[v1] = accM[R][v1] * sg[v1];
+        om[v1] = 1.0f - sg[v1];
+        rn[v0] = rda[v0] * accN[R][v0];
+      } else if constexpr (sl == 3) {
+        rn[v1] = rda[v1] * accN[R][v1];
+        sp[v0] = fmaf(silu[v0], om[v0], sg[v0]);   // SiLU'(m) = sg + silu (1 - sg)
+        sp[v1] = fmaf(silu[v1], om[v1], sg[v1]);
+        ds[v0] = accA[R][v0] * silu[v0];
+        ds[v1] = accA[R][v1] * silu[v1];
+      } else if constexpr (sl == 4) {
+        drp[0] = fmaf(ds[v0], accN[R][v0], drp[0]);
+        drp[0] = fmaf(ds[v1], accN[R][v1], drp[0]);
+        dnv[v0] = rda[v0] * silu[v0];
+        dnv[v1] = rda[v1] * silu[v1];
+        dmv[v0] = rn[v0] * sp[v0];
+      } else {
+        dmv[v1] = rn[v1] * sp[v1];
+        pmv[t2][i] = pack_bf16(dmv[v0], dmv[v1]);
+        pnv[t2][i] = pack_bf16(dnv[v0], dnv[v1]);
+      }
+    };
+    // products of the tile in stage `sto` into set W, arithmetic on set 1 - W in their shadow
+    auto row_products = [&](unsigned sto, auto W_, auto ARITH_, bool request, int t_req, int stage_req) __attribute__((always_inline)) {
+      constexpr int W = decltype(W_)::value;
+      constexpr bool kArith = decltype(ARITH_)::value;
+      // chunk 2 ks + g of a row, swizzled: the address of ks = 0 with bits 5..7 XORed by ks % 8
+      // (the stage base is a multiple of 256), 256 bytes further for ks >= 8: one address
+      // register instead of sixteen
+      const unsigned pb = sto + btile_off<DH>(r, g);
+      auto issue = [&](auto C_) __attribute__((always_inline)) {
+        constexpr int c = decltype(C_)::value, ks = c / 3, which = c % 3;
+        op[c] = lds_read_b128_untracked<which * kTileBytes + (ks >> 3) * 256>(pb ^ ((ks & 7) << 5));
+      };
+      static_for<0, kWinP>(issue);
+      static_for<0, NOP>([&](auto C_) __attribute__((always_inline)) {
+        constexpr int c = decltype(C_)::value, ks = c / 3, which = c % 3;
+        if constexpr (c + kWinP < NOP) issue(std::integral_constant<int, c + kWinP>{});
+        lds_wait<(NOP - 1 - c) < kWinP ? (NOP - 1 - c) : kWinP>(op[c]);
+        if constexpr (which == 0) accM[W] = mfma32(op[c], q[0][ks], ks == 0 ? f32x16{0} : accM[W]);
+        if constexpr (which == 1) accN[W] = mfma32(op[c], q[0][ks], ks == 0 ? f32x16{0} : accN[W]);
+        if constexpr (which == 2) accA[W] = mfma32(op[c], dy[0][ks], ks == 0 ? f32x16{0} : accA[W]);
+        // three slots of arithmetic (pieces 0..35: pairs 0..5), then one with a load of the tile
+        // after next (a direct load is tracked by vmcnt, the reads above by lgkmcnt)
+        if constexpr (c % 4 == 3) {
+          if (request) dma_one(t_req, stage_req, std::integral_constant<int, c / 4>{});
+        } else if constexpr (kArith) {
+          constexpr int piece = c - c / 4;
+          pair_slot(std::integral_constant<int, piece / 6>{}, std::integral_constant<int, piece % 6>{},
+                    std::integral_constant<int, 1 - W>{});
+        }
+        MHFFN_SB();
+      });
+    };
+    auto arith_alone = [&](auto R_) __attribute__((always_inline)) {
+      static_for<0, 36>([&](auto C_) {
+        constexpr int c = decltype(C_)::value;
+        pair_slot(std::integral_constant<int, c / 6>{}, std::integral_constant<int, c % 6>{}, R_);
+      });
+    };
+    // dX products of the tile in stage `sto`; the loads of tile t_req go out between them
+    auto window_products = [&](unsigned sto, auto R_) __attribute__((always_inline)) {
+      // columns 32 jb + tcol of a row: chunk 4 jb + tcol / 8, i.e. the address of jb = 0 with
+      // bits 6..7 XORed by jb % 4, 256 bytes further for jb >= 4
+      const unsigned wlo = sto + btile_off8<DH>(trow, tcol), whi = sto + btile_off8<DH>(trow + 8, tcol);
+      unsigned wl[4], wh[4];   // (the row operands are dead here: eight registers are to be had)
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        wl[k] = wlo ^ (k << 6);
+        wh[k] = whi ^ (k << 6);
+      }
+      auto issue2 = [&](auto C_) __attribute__((always_inline)) {
+        constexpr int c = decltype(C_)::value, which = c & 1, jb = (c >> 1) % JB, t2 = c / (2 * JB);
+        constexpr int OFF = which * kTileBytes + t2 * 16 * 2 * DH + (jb >> 2) * 256;   // 16 rows further: same swizzle
+        lo[c] = lds_read_tr16_untracked<OFF>(wl[jb & 3]);
+        hi[c] = lds_read_tr16_untracked<OFF>(wh[jb & 3]);
+      };
+      static_for<0, kWinD>(issue2);
+      static_for<0, NT>([&](auto C_) __attribute__((always_inline)) {
+        constexpr int c = decltype(C_)::value, which = c & 1, jb = (c >> 1) % JB, t2 = c / (2 * JB);
+        if constexpr (c + kWinD < NT) issue2(std::integral_constant<int, c + kWinD>{});
+        lds_wait<2 * ((NT - 1 - c) < kWinD ? (NT - 1 - c) : kWinD)>(lo[c], hi[c]);
+        const bf16x8 xt = join_tr(lo[c], hi[c]);
+        dXa[0][jb] = mfma32(xt, __builtin_bit_cast(bf16x8, which ? pnv[t2] : pmv[t2]), dXa[0][jb]);
+        // pieces 36..47 of the arithmetic (pairs 6 and 7, operands of the windows from item 16 on)
+        if constexpr (c < 12)
+          pair_slot(std::integral_constant<int, (36 + c) / 6>{}, std::integral_constant<int, (36 + c) % 6>{}, R_);
+        MHFFN_SB();
+      });
+    };
+    auto step = [&](int t, auto S_) __attribute__((always_inline)) {
+      constexpr int S = decltype(S_)::value;
+      const int e = t / tiles_per_sub;
+      if (t % tiles_per_sub == 0) rw[0] = DRs[e * BM + wtok + r];
+      const int st_t = t % 3, st_n = (t + 1) % 3, st_r = (t + 2) % 3;
+      if (t + 1 < T) row_products(sto0 + st_n * kTokStageBytes, std::integral_constant<int, 1 - S>{}, std::true_type{}, t + 2 < T, t + 2, st_r);
+      else arith_alone(S_);
+      window_products(sto0 + st_t * kTokStageBytes, S_);
+      if ((t + 1) % tiles_per_sub == 0) {
+        const float dr = drp[0] + __shfl_xor(drp[0], 32);
+        if (g == 0) DRs[e * BM + wtok + r] = dr;
+        drp[0] = 0.f;
+      }
+      asm volatile("" ::: "memory");
+      __builtin_amdgcn_s_waitcnt(0x0070);   // vmcnt(0) lgkmcnt(0): this wave's part of tile t+2 is in
+      bare_barrier();
+    };
+    row_products(sto0, std::integral_constant<int, 0>{}, std::false_type{}, false, 0, 0);
+    for (int t = 0; t < T; t += 2) {
+      step(t, std::integral_constant<int, 0>{});
+      if (t + 1 < T) step(t + 1, std::integral_constant<int, 1>{});
+    }
+  } else
   if constexpr (PHASED) {
     // Half A of step t: the dX products of tile t-1 (operands packed in half B of step t-1),
     // then the gate/up/dA products of tile t: 40 MFMAs and their LDS reads, no VALU work.
@@ -430,7 +608,7 @@ __global__ __launch_bounds__(64 * NW, DH == 64 ? 2 : 1) void bwd_tok_kernel(BwdA
     // A request is made by the early waves alone, at the top of their half A (the shorter of
     // the two halves): wave w moves its own rows and those of wave w + NW/2.
     auto dma_pair = [&](int t, int stage) {
-      const size_t off = (size_t)t * (32 * DH) + dma_goff;
+      const size_t off = (size_t)t * (32 * DH) + dma_goff[0];
       unsigned char* dst = stage_base + stage * kTokStageBytes + wave_u * 1024;
       constexpr int kHalfTile = (NW / 2) * 4 * DH;   // elements: rows 4 (w + NW/2) .. +3
 #pragma unroll
@@ -2267,21 +2445,22 @@ size_t tok_lds_bytes(const Problem& p, bool dma) {
   return (size_t)tok_stages(dma) * tok_stage_bytes(p.dh) +
          (size_t)p.E * tok_block_tokens(p.dh) * sizeof(float);
 }
-// direct staging (three stages) where it fits: d_h = 128 with up to 88 sub-networks
+// direct staging (three stages) where it fits: d_h = 128 with up to 88 sub-networks, d_h = 256
+// (stages of 48 KB) with up to 32
 bool tok_direct_staging(const Problem& p) {
-  return p.dh == 128 && tok_lds_bytes(p, true) <= kLdsBytesPerWorkgroup;
+  return (p.dh == 128 || p.dh == 256) && tok_lds_bytes(p, true) <= kLdsBytesPerWorkgroup;
 }
 
-template <int DH, int TB, int NW, bool DMA = false, bool PHASED = false>
+template <int DH, int TB, int NW, bool DMA = false, bool PHASED = false, bool PIPE = false>
 int launch_tok(const Problem& p, BwdArgs a, hipStream_t stream) {
   constexpr int BM = 32 * TB * NW;
   static_assert(BM == tok_block_tokens(DH), "bwd_bf16_lds_bytes assumes this block size");
   a.n_tiles = (p.N + BM - 1) / BM;
   a.n_items = a.n_tiles * p.H;
   const size_t lds = tok_lds_bytes(p, DMA);
-  if (hipError_t e = LdsLimit<&bwd_tok_kernel<DH, TB, NW, DMA, PHASED>, kFullLds>::ensure(); e != hipSuccess)
+  if (hipError_t e = LdsLimit<&bwd_tok_kernel<DH, TB, NW, DMA, PHASED, PIPE>, kFullLds>::ensure(); e != hipSuccess)
     return (int)e;
-  hipLaunchKernelGGL((bwd_tok_kernel<DH, TB, NW, DMA, PHASED>), dim3((unsigned)xcd_grid_size(a.n_items)),
+  hipLaunchKernelGGL((bwd_tok_kernel<DH, TB, NW, DMA, PHASED, PIPE>), dim3((unsigned)xcd_grid_size(a.n_items)),
                      dim3(64 * NW), lds, stream, a);
   return (int)hipGetLastError();
 }
@@ -2452,6 +2631,7 @@ int launch_bwd(const Problem& p, int dtype, const void* X, const void* Wg, const
   // d_h = 64: workgroups of 4 waves, two or three of them per CU in different phases of
   // their steps (measured 4 % and 11 % faster than one workgroup of 8 waves)
   if (p.dh == 64) rc = launch_tok<64, 1, 4>(p, a, stream);
+  else if (p.dh == 256 && tok_direct_staging(p)) rc = launch_tok<256, 1, 4, true, false, true>(p, a, stream);
   else if (p.dh == 256) rc = launch_tok<256, 1, 4>(p, a, stream);   // needs one wave per SIMD: see the kernel
   else if (tok_direct_staging(p)) rc = launch_tok<kDh, 1, 8, true, true>(p, a, stream);
   else rc = launch_tok<kDh, 1, 8>(p, a, stream);
