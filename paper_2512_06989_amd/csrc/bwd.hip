@@ -413,9 +413,11 @@ __global__ __launch_bounds__(64 * NW, DH == 64 ? 2 : 1) void bwd_tok_kernel(BwdA
       }
     };
     // products of the tile in stage `sto` into set W, arithmetic on set 1 - W in their shadow
-    auto row_products = [&](unsigned sto, auto W_, auto ARITH_, bool request, int t_req, int stage_req) __attribute__((always_inline)) {
+    // (REQ_ is a compile-time flag: a branch around a load would split the stream into basic
+    // blocks, and the compiler then gathers the arithmetic of all slots in one of them)
+    auto row_products = [&](unsigned sto, auto W_, auto ARITH_, auto REQ_, int t_req, int stage_req) __attribute__((always_inline)) {
       constexpr int W = decltype(W_)::value;
-      constexpr bool kArith = decltype(ARITH_)::value;
+      constexpr bool kArith = decltype(ARITH_)::value, kReq = decltype(REQ_)::value;
       // chunk 2 ks + g of a row, swizzled: the address of ks = 0 with bits 5..7 XORed by ks % 8
       // (the stage base is a multiple of 256), 256 bytes further for ks >= 8: one address
       // register instead of sixteen
@@ -435,7 +437,7 @@ __global__ __launch_bounds__(64 * NW, DH == 64 ? 2 : 1) void bwd_tok_kernel(BwdA
         // three slots of arithmetic (pieces 0..35: pairs 0..5), then one with a load of the tile
         // after next (a direct load is tracked by vmcnt, the reads above by lgkmcnt)
         if constexpr (c % 4 == 3) {
-          if (request) dma_one(t_req, stage_req, std::integral_constant<int, c / 4>{});
+          if constexpr (kReq) dma_one(t_req, stage_req, std::integral_constant<int, c / 4>{});
         } else if constexpr (kArith) {
           constexpr int piece = c - c / 4;
           pair_slot(std::integral_constant<int, piece / 6>{}, std::integral_constant<int, piece % 6>{},
@@ -485,7 +487,8 @@ __global__ __launch_bounds__(64 * NW, DH == 64 ? 2 : 1) void bwd_tok_kernel(BwdA
       const int e = t / tiles_per_sub;
       if (t % tiles_per_sub == 0) rw[0] = DRs[e * BM + wtok + r];
       const int st_t = t % 3, st_n = (t + 1) % 3, st_r = (t + 2) % 3;
-      if (t + 1 < T) row_products(sto0 + st_n * kTokStageBytes, std::integral_constant<int, 1 - S>{}, std::true_type{}, t + 2 < T, t + 2, st_r);
+      if (t + 2 < T) row_products(sto0 + st_n * kTokStageBytes, std::integral_constant<int, 1 - S>{}, std::true_type{}, std::true_type{}, t + 2, st_r);
+      else if (t + 1 < T) row_products(sto0 + st_n * kTokStageBytes, std::integral_constant<int, 1 - S>{}, std::true_type{}, std::false_type{}, 0, 0);
       else arith_alone(S_);
       window_products(sto0 + st_t * kTokStageBytes, S_);
       if ((t + 1) % tiles_per_sub == 0) {
@@ -497,7 +500,7 @@ __global__ __launch_bounds__(64 * NW, DH == 64 ? 2 : 1) void bwd_tok_kernel(BwdA
       __builtin_amdgcn_s_waitcnt(0x0070);   // vmcnt(0) lgkmcnt(0): this wave's part of tile t+2 is in
       bare_barrier();
     };
-    row_products(sto0, std::integral_constant<int, 0>{}, std::false_type{}, false, 0, 0);
+    row_products(sto0, std::integral_constant<int, 0>{}, std::false_type{}, std::false_type{}, 0, 0);
     for (int t = 0; t < T; t += 2) {
       step(t, std::integral_constant<int, 0>{});
       if (t + 1 < T) step(t + 1, std::integral_constant<int, 1>{});

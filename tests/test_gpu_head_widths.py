@@ -37,6 +37,23 @@ def test_backward_small_shapes(N, H, dh, E, de):
     check_all(got, ref, TOL["bf16"], single_subnetwork=(E == 1))
 
 
+@pytest.mark.parametrize("N,H,E,de,route_weights", [
+    # enough token tiles (48 x 8 heads) that a workgroup of the d_h = 256 forward walks the whole
+    # intermediate dimension instead of a share of it (the small shapes above all run split):
+    # ragged last tile, odd and even tile counts, one tile, more than 32 sub-networks, given
+    # gating weights
+    (6100, 8, 3, 64, False), (6200, 8, 32, 32, False), (6144, 8, 1, 32, False), (6100, 8, 2, 96, True),
+    (6100, 8, 33, 32, False),
+])
+def test_dh256_forward_whole_depth_workgroups(N, H, E, de, route_weights):
+    w = small_workload("hw_fwd_wide", N, H, E, de, "bf16", dh=256)
+    d, Y = run_forward(w, seed=N + E, route_weights=route_weights)
+    # the oracle on a sample of rows: first and last tile of 128, and a stride through the rest
+    rows = np.unique(np.concatenate([np.arange(0, 130), np.arange(N - 130, N), np.arange(0, N, 37)]))
+    ref = oracle_forward(d, w, rows=rows, route_weights=route_weights)
+    assert relerr(Y[rows], ref) <= TOL["bf16"]
+
+
 @pytest.mark.parametrize("N,H,E,de", [
     # 54 groups of four 16-neuron blocks: 7 per XCD, less than a round, every group shares its
     # tokens out over four workgroups
