@@ -19,7 +19,11 @@ SHAPES = [(1, 1, 64, 1, 32), (63, 2, 64, 3, 96), (300, 2, 64, 5, 64), (1000, 3, 
           # stage of the token-major backward during its gating prologue
           (140, 1, 64, 96, 32),
           (1, 1, 256, 1, 32), (63, 2, 256, 3, 96), (300, 2, 256, 3, 64), (700, 1, 256, 4, 704),
-          (257, 1, 256, 40, 32)]
+          (257, 1, 256, 40, 32),
+          # the token-major backward at d_h = 256 pipelines up to 32 sub-networks inside a wave
+          # (two accumulator sets by parity of the tile: one, two and an odd number of tiles above
+          # and here, the most sub-networks it takes, and one more: the register-staged kernel)
+          (40, 1, 256, 2, 32), (130, 1, 256, 32, 32), (130, 1, 256, 33, 32)]
 
 
 @pytest.mark.parametrize("N,H,dh,E,de", SHAPES)
